@@ -1,0 +1,282 @@
+"""Pins of the planner oracle: closed forms, hand traces, invariants, brute force."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+import synthdata
+from oracle import planner as op
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------------------------------------------------------------- estimator (P5)
+def test_exact_coefficient_recovery():
+    c = (123456.0, 789.0, 0.0625)
+    xs = [640, 2048, 4096, 6400, 9000]
+    ys = [c[0] + c[1] * x + c[2] * x * x for x in xs]
+    m = op.fit_poly(xs, ys, 2)
+    for x in (64, 5000, 16384, 40000):
+        want = c[0] + c[1] * x + c[2] * x * x
+        assert abs(op.eval_poly(m, x) - want) < 1e-6 * want
+    # three samples determine the parabola exactly (Lagrange closed form)
+    m3 = op.fit_poly(xs[:3], ys[:3], 2)
+    assert abs(op.eval_poly(m3, 12345) - (c[0] + c[1] * 12345 + c[2] * 12345 ** 2)) < 1e-3
+
+
+def test_zero_quadratic_term_is_handled():
+    xs = [256, 512, 1024, 2048]
+    ys = [4096 + 64 * x for x in xs]
+    m = op.fit_poly(xs, ys, 2)
+    assert abs(op.eval_poly(m, 8192) - (4096 + 64 * 8192)) < 1e-3
+
+
+def test_quadratic_beats_linear_on_unfused_attention_model():
+    """Section 4.3: an unfused attention keeps seqlen x seqlen tensors, so bytes are
+    quadratic in the input size; Table 3 reports percent-level error for order 1
+    and sub-percent for order 2."""
+    wl = synthdata.WORKLOADS["bert_base"]
+    s = wl.shape
+    lens = synthdata.seq_lengths(wl.length_recipe, 40, wl.seed)
+    f = lambda L: op.analytic_layer_bytes(wl.batch, L, s.hidden, s.n_heads, s.ffn, 4, True)
+    train, test = lens[:10], lens[10:]
+    xs = [wl.batch * L for L in train]
+    m1 = op.fit_poly(xs, [f(L) for L in train], 1)
+    m2 = op.fit_poly(xs, [f(L) for L in train], 2)
+    mape = lambda m: np.mean([abs(op.eval_poly(m, wl.batch * L) - f(L)) / f(L) for L in test])
+    assert mape(m2) < 1e-9
+    assert mape(m1) > 0.01
+
+
+def test_rounding_granule_and_guard():
+    assert op.to_bytes(1000.0, 0) == 1024
+    assert op.to_bytes(1151.9, 0) == 1024 and op.to_bytes(1152.0, 0) == 1280
+    assert op.to_bytes(-5.0, 1024) == 1024
+    assert op.to_bytes(2560.0000001, 1024) == 3584
+
+
+# ---------------------------------------------------------------- Algorithm 1 hand traces
+def read_traces():
+    out = []
+    with open(os.path.join(GOLDEN, "algorithm1_traces.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            est, excess, sel = [p.strip() for p in line.split("|")]
+            out.append(([int(v) for v in est.split(",")], int(excess),
+                        [int(v) for v in sel.split(",")] if sel else []))
+    return out
+
+
+@pytest.mark.parametrize("est,excess,want", read_traces())
+def test_algorithm1_hand_traces(est, excess, want):
+    buckets = op.make_buckets(est, 100)
+    chosen = []
+    op.greedy_select(est, buckets, excess, chosen)
+    assert chosen == want
+
+
+def test_bucket_construction():
+    assert op.make_buckets([50, 100, 48, 95, 20, 47]) == [[1, 3], [0, 2, 5], [4]]
+    assert op.make_buckets([80, 80, 40, 40, 20, 20, 10, 10]) == [[0, 1], [2, 3], [4, 5], [6, 7]]
+    # membership is relative to the bucket's first member, not chained: 100, 91, 83
+    assert op.make_buckets([100, 91, 83]) == [[0, 1], [2]]
+    # strict comparison: exactly 90 % starts a new bucket
+    assert op.make_buckets([100, 90]) == [[0], [1]]
+
+
+# ---------------------------------------------------------------- P6: equal layers, closed form
+def homogeneous(n, a, b, w, g, F=1000, e=500):
+    return op.Components(F=F, e=e, g=g, a=[a] * n, b=[b] * n, w=[w] * n)
+
+
+@pytest.mark.parametrize("g,w", [(700, 300), (300, 700)])
+@pytest.mark.parametrize("n", [2, 12, 24])
+def test_equal_layers_closed_form(n, g, w):
+    a, b = 1000, 60
+    c = homogeneous(n, a, b, w, g)
+    p0 = op.simulate_peak(c, 0)
+    assert p0 == 1000 + 500 + n * a + max(g, w)
+    s = a - b
+    for excess in [-5, 0, 1, s - 1, s, s + 1, 3 * s + 7, (n - 1) * s]:
+        res = op.plan_from_components(c, p0 - excess)
+        k = 0 if excess <= 0 else math.ceil(excess / s)
+        if k >= n:                                  # beyond what dropping layers can cover
+            continue
+        assert res.plan == (1 << k) - 1, (excess, bin(res.plan))
+        assert res.feasible and res.predicted_peak <= p0 - excess
+        assert res.predicted_peak == p0 - k * s
+
+
+# ---------------------------------------------------------------- P7: greedy invariants
+def test_greedy_invariants_random():
+    rng = np.random.default_rng(7)
+    for _ in range(300):
+        n = int(rng.integers(1, 12))
+        est = [int(v) for v in rng.integers(1, 1000, n)]
+        excess = int(rng.integers(-50, sum(est) + 100))
+        chosen = []
+        left = op.greedy_select(est, op.make_buckets(est), excess, chosen)
+        tot = sum(est[l] for l in chosen)
+        assert len(set(chosen)) == len(chosen)
+        if excess <= 0:
+            assert chosen == []
+            continue
+        assert tot >= excess or len(chosen) == n
+        assert left == excess - tot
+        assert excess - (tot - est[chosen[-1]]) > 0               # last pick was needed
+        # within one bucket, layers leave in forward order
+        for b in op.make_buckets(est):
+            picked = [l for l in chosen if l in b]
+            assert picked == sorted(picked)
+
+
+# ---------------------------------------------------------------- P8 / P9: peak simulator laws
+def test_single_layer_checkpoint_position_law():
+    """Checkpointing the last encoder saves nothing at the backward peak, earlier ones
+    save more (Section 4.4, discussion of the per-encoder peak figure)."""
+    n = 12
+    c = homogeneous(n, 1000, 60, w=500, g=100)
+    p0 = op.simulate_peak(c, 0)
+    peaks = [op.simulate_peak(c, 1 << i) for i in range(n)]
+    assert peaks[n - 1] == p0
+    assert all(peaks[i] <= peaks[i + 1] for i in range(n - 1))
+    assert peaks[0] == p0 - 940
+    # memory at the end of the forward pass does not depend on which layer was chosen
+    end_fwd = lambda plan: sum(c.b[l] if (plan >> l) & 1 else c.a[l] for l in range(n))
+    assert len({end_fwd(1 << i) for i in range(n)}) == 1
+
+
+def test_all_checkpointed_footprint():
+    rng = np.random.default_rng(5)
+    for _ in range(50):
+        n = int(rng.integers(1, 9))
+        b = [int(v) for v in rng.integers(10, 100, n)]
+        a = [bb + int(v) for bb, v in zip(b, rng.integers(100, 2000, n))]
+        w = [int(v) for v in rng.integers(0, 800, n)]
+        c = op.Components(F=7, e=11, g=int(rng.integers(0, 3000)), a=a, b=b, w=w)
+        want = 7 + 11 + max(sum(b) + c.g, max(sum(b[:l]) + a[l] + w[l] for l in range(n)))
+        assert op.simulate_peak(c, (1 << n) - 1) == want
+
+
+# ---------------------------------------------------------------- P10: brute force over subsets
+def test_greedy_feasible_whenever_any_subset_is():
+    rng = np.random.default_rng(11)
+    gaps = []
+    for trial in range(200):
+        n = int(rng.integers(1, 11))
+        scale = [1.0, 0.5, 0.25][trial % 3]
+        b = [int(v) for v in rng.integers(10, 200, n)]
+        a = [bb + int(scale ** (l * 4 // n) * v) for l, (bb, v) in enumerate(zip(b, rng.integers(500, 3000, n)))]
+        w = [int(v) for v in rng.integers(0, 1500, n)]
+        c = op.Components(F=100, e=50, g=int(rng.integers(0, 4000)), a=a, b=b, w=w)
+        peaks = op.brute_force_peaks(c)
+        assert peaks[(1 << n) - 1] == peaks.min()                  # all-checkpointed is the floor
+        for plan in (0, 1, (1 << n) - 1, int(rng.integers(0, 1 << n))):
+            assert peaks[plan] == op.simulate_peak(c, plan)
+        lo, hi = int(peaks.min()), int(peaks.max())
+        for M in (lo - 1, lo, (lo + hi) // 2, hi - 1, hi, hi + 10):
+            res = op.plan_from_components(c, M)
+            any_ok = bool((peaks <= M).any())
+            assert res.feasible == any_ok, (trial, M)
+            if any_ok:
+                assert peaks[res.plan] <= M
+                assert res.predicted_peak == peaks[res.plan]
+                # recompute bytes of the greedy plan against the best feasible subset (informational)
+                s = np.array([a[l] - b[l] for l in range(n)])
+                cost = lambda m: int(sum(s[l] for l in range(n) if (m >> l) & 1))
+                best = min(cost(m) for m in np.nonzero(peaks <= M)[0])
+                gaps.append(cost(res.plan) - best)
+    assert min(gaps) >= 0
+
+
+def test_bruteforce_24_layers_runs():
+    c = homogeneous(20, 1000, 60, 500, 700)
+    peaks = op.brute_force_peaks(c)
+    assert peaks.shape == (1 << 20,)
+    assert peaks[0] == op.simulate_peak(c, 0)
+
+
+# ---------------------------------------------------------------- planner end to end + cache (P11)
+def feed_exact(pl, B, L, n_layers, coeffs):
+    x = B * L
+    poly = lambda c: int(c[0] + c[1] * x + c[2] * x * x)
+    for l in range(n_layers):
+        pl.feed(x, op.Q_A, l, poly(coeffs["a"]))
+        pl.feed(x, op.Q_B, l, poly(coeffs["b"]))
+        pl.feed(x, op.Q_W, l, poly(coeffs["w"]))
+    pl.feed(x, op.Q_E, -1, poly(coeffs["e"]))
+    pl.feed(x, op.Q_G, -1, poly(coeffs["g"]))
+    pl.feed(x, op.Q_F, -1, coeffs["F"])
+    pl.end_sheltered_step(x)
+
+
+def test_planner_phases_cache_and_budget():
+    wl = synthdata.WORKLOADS["bert_base"]
+    n, B = wl.shape.n_layers, wl.batch
+    co = dict(a=(0, 16 * 768 * 2, 0), b=(0, 768 * 2, 0), w=(0, 4 * 768 * 2 + 0, 0),
+              e=(2048, 4 * 768 * 2, 0), g=(0, (30528 + 4 * 768) * 2, 0), F=700_000_000)
+    true_comp = lambda x, guard: op.Components(
+        F=co["F"], e=int(co["e"][0] + co["e"][1] * x) + guard, g=int(co["g"][1] * x) + guard,
+        a=[int(co["a"][1] * x) + guard] * n, b=[int(co["b"][1] * x) + guard] * n,
+        w=[int(co["w"][1] * x) + guard] * n)
+    budget = int(0.6 * op.simulate_peak(true_comp(B * 512, 0), 0))
+    pl = op.Planner(n, budget)
+    lens = synthdata.seq_lengths(wl.length_recipe, 200, wl.seed)
+    assert pl.sheltered()
+    for L in lens[:10]:
+        assert pl.sheltered()
+        feed_exact(pl, B, L, n, co)
+    assert not pl.sheltered()
+    seen = set()
+    new_keys = 0
+    for L in lens[10:]:
+        x = B * L
+        res = pl.query(x)
+        ref = op.plan_from_components(true_comp(x, 1024), budget)
+        assert res.plan == ref.plan and res.predicted_peak == ref.predicted_peak
+        assert res.feasible and res.predicted_peak <= budget
+        assert op.simulate_peak(true_comp(x, 0), res.plan) <= budget
+        if x not in seen:
+            new_keys += 1
+            seen.add(x)
+    assert pl.misses == new_keys and pl.hits == len(lens) - 10 - new_keys
+    # short batches need no checkpointing, the longest ones do, and plans are prefixes
+    assert pl.query(B * 64).plan == 0
+    long_plan = pl.query(B * 512).plan
+    assert long_plan != 0 and (long_plan & (long_plan + 1)) == 0
+
+
+def test_planner_stays_sheltered_until_three_distinct_sizes():
+    pl = op.Planner(2, 10 ** 9)
+    co = dict(a=(0, 100, 0), b=(0, 10, 0), w=(0, 5, 0), e=(0, 1, 0), g=(0, 1, 0), F=1)
+    for _ in range(12):
+        feed_exact(pl, 4, 16, 2, co)
+    assert pl.sheltered()
+    feed_exact(pl, 4, 17, 2, co)
+    assert pl.sheltered()
+    feed_exact(pl, 4, 18, 2, co)
+    assert not pl.sheltered()
+
+
+def test_size_quantum_plans_for_upper_end():
+    pl = op.Planner(4, 50_000, quantum=64, guard=0)
+    co = dict(a=(0, 100, 0), b=(0, 10, 0), w=(0, 20, 0), e=(0, 4, 0), g=(0, 30, 0), F=1000)
+    for L in (10, 20, 30, 40, 50, 60, 70, 80, 90, 100):
+        feed_exact(pl, 1, L, 4, co)
+    r1 = pl.query(65)
+    r2 = pl.query(128)
+    assert pl.hits == 1 and pl.misses == 1 and r1 is r2
+    assert pl.key_of(65) == 128 and pl.key_of(128) == 128 and pl.key_of(129) == 192
+
+
+def test_stress_workload_hit_rate():
+    wl = synthdata.WORKLOADS["bert_large_stress"]
+    lens = synthdata.seq_lengths(wl.length_recipe, wl.steps, wl.seed)
+    assert len(set(lens)) <= 26
+    assert all((32 <= L <= 96 or 384 <= L <= 512) and L % 8 == 0 for L in lens)
+    responsive = lens[10:]
+    hit_rate = 1 - len(set(responsive)) / len(responsive)
+    assert hit_rate >= 0.94
