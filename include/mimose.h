@@ -1,0 +1,207 @@
+/*
+ * libmimose - input-aware activation checkpointing for transformer training on
+ * one MI355X (gfx950).  C ABI; no C++ or framework types cross this boundary.
+ *
+ * The library runs the checkpointed training iteration of Mimose
+ * (arXiv 2209.02478): forward keeping activations, loss, backward consuming
+ * them (Section 2.1), with layer-granular checkpointing (Section 1, Section 5:
+ * a dropped layer keeps only its boundary tensor and is replayed in backward),
+ * driven by the paper's planner: sheltered / responsive phases (Section 4.1),
+ * a per-layer quadratic memory estimator (Section 4.3), the greedy bucketed
+ * scheduler (Section 4.4, Algorithm 1) and a plan cache keyed by input size
+ * (Section 5).
+ *
+ * Conventions
+ *   - every function returns MIMOSE_OK (0) or a negative MIMOSE_ERR_* code;
+ *     mimose_last_error() gives a text for the last failure on that context;
+ *   - "host" pointers are ordinary process memory, "device" pointers are HIP
+ *     device memory on the current device; the library never frees, resizes or
+ *     retains caller memory beyond what is stated per function;
+ *   - all device memory the library uses is carved out of the arena passed to
+ *     mimose_init; all device work is enqueued on the stream passed there;
+ *   - a failed call leaves the context usable.
+ */
+#ifndef MIMOSE_H
+#define MIMOSE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MIMOSE_OK 0
+#define MIMOSE_ERR_INVALID_ARG (-1)
+#define MIMOSE_ERR_OOM_BUDGET (-2)        /* an allocation would exceed the memory budget   */
+#define MIMOSE_ERR_BUDGET_INFEASIBLE (-3) /* even the all-checkpointed plan exceeds budget  */
+#define MIMOSE_ERR_HIP (-4)
+#define MIMOSE_ERR_NOT_READY (-5)
+
+typedef struct mimose_ctx mimose_ctx; /* opaque, owned by the library */
+
+/* Plain data, caller-owned, copied by mimose_init. */
+typedef struct {
+  int32_t n_layers, hidden, n_heads, ffn, vocab, max_seq;
+  int32_t dtype;     /* 0: fp32 storage and arithmetic; 1: bf16 storage, fp32 accumulation */
+  int32_t causal;    /* 1: causal attention mask                                          */
+  int32_t pre_ln;    /* 0: post-LN blocks (BERT-shaped); 1: pre-LN blocks + final LN       */
+  int32_t gelu_tanh; /* 0: erf GELU; 1: tanh approximation                                 */
+  int32_t head;      /* 1: dense+GELU+LN transform, tied decoder + bias; 0: tied decoder   */
+  float ln_eps;
+  /* planner; zero selects the paper's value given in brackets */
+  int32_t sheltered_steps;     /* [10]  iterations of data collection, Section 6.4          */
+  int32_t bucket_tol_permille; /* [100] bucket similarity, Section 4.4                       */
+  int32_t poly_order;          /* [2]   estimator order, Section 6.5                         */
+  int32_t size_quantum;        /* [1]   plan-cache key granularity, Section 5                */
+  uint64_t reserve_bytes;      /* kept free below the budget (Section 6.4 keeps 0.5-1 GB)    */
+  uint64_t guard_bytes;        /* added to every predicted component; 0 selects 4096         */
+} mimose_model_cfg;
+
+typedef struct {
+  uint64_t steps, sheltered_steps;
+  uint64_t cache_hits, cache_misses, cache_entries;
+  uint64_t planner_ns_last, planner_ns_total;
+  uint64_t recomputed_layers_last, recomputed_layers_total;
+  double useful_flops_last, recompute_flops_last;
+  double useful_flops_total, recompute_flops_total;
+  uint64_t peak_bytes_last, peak_bytes_max, predicted_peak_last;
+  uint64_t fixed_bytes, budget_bytes;
+} mimose_stats;
+
+/* quantities of the collector's sample table (Section 4.2), see mimose_planner_feed */
+#define MIMOSE_Q_LAYER_KEPT 0    /* a_l: bytes layer l holds from forward to backward       */
+#define MIMOSE_Q_LAYER_BOUNDARY 1/* b_l: bytes it holds when checkpointed (its output)      */
+#define MIMOSE_Q_LAYER_BWD 2     /* w_l: transient bytes of its backward                    */
+#define MIMOSE_Q_EMBED 3         /* e: bytes of the embedding stage held all step           */
+#define MIMOSE_Q_HEAD 4          /* g: transient bytes of head forward + backward           */
+#define MIMOSE_Q_FIXED 5         /* F: parameters, gradients, persistent scratch            */
+
+/*
+ * Create a context (Section 4.1: the planner wraps the training iteration).
+ *   cfg              model and planner configuration (host, copied)
+ *   mem_budget_bytes memory budget M of Algorithm 1, covering everything the
+ *                    library keeps on the device; 0 = unlimited (calibration)
+ *   arena_dev        device buffer the library sub-allocates from; stays owned by
+ *                    the caller and must outlive the context.  NULL creates a
+ *                    host-only context: planner calls and mimose_dry_step work,
+ *                    mimose_train_step returns MIMOSE_ERR_NOT_READY.
+ *   arena_bytes      its size; must be >= mem_budget_bytes when both are non-zero
+ *   hip_stream       hipStream_t (as void*) all work is enqueued on; NULL = default
+ * Errors: INVALID_ARG (bad shapes, hidden % n_heads, head_dim not 32/64/128,
+ * n_layers > 64), OOM_BUDGET (parameters and gradients do not fit).
+ */
+int mimose_init(const mimose_model_cfg* cfg, uint64_t mem_budget_bytes, void* arena_dev,
+                uint64_t arena_bytes, void* hip_stream, mimose_ctx** out);
+
+/* Named parameter tensors.  name stays valid for the context's life; shape has ndim entries. */
+int mimose_param_count(mimose_ctx* ctx, int32_t* n);
+int mimose_param_info(mimose_ctx* ctx, int32_t i, const char** name, int64_t shape[4], int32_t* ndim);
+/* Copy parameter i from host fp32 (row-major); the library rounds to its storage type
+ * (round to nearest even).  Synchronous. */
+int mimose_load_param(mimose_ctx* ctx, int32_t i, const float* host_fp32, uint64_t n_elems);
+
+/*
+ * One training iteration on a mini-batch of B sequences of exactly L tokens
+ * (Section 2.1; input size x = B*L, Section 3.1).  Chooses the plan (sheltered:
+ * all layers; responsive: cache or Algorithm 1), runs forward / loss / backward
+ * with recomputation of dropped layers, and waits for completion.
+ *   tokens_host  [B,L] row-major ids in [0,vocab); borrowed for the call
+ *   labels_host  [B,L], -1 = position not scored; borrowed for the call
+ *   loss         mean cross-entropy over scored positions
+ *   peak_bytes   true high-water mark of device memory in this step
+ *   plan_id      bitmask, bit l set = layer l was dropped and recomputed
+ * Errors: INVALID_ARG, OOM_BUDGET (the step is abandoned, the arena is reset),
+ * BUDGET_INFEASIBLE, HIP, NOT_READY (host-only context).
+ */
+int mimose_train_step(mimose_ctx* ctx, const int32_t* tokens_host, const int32_t* labels_host,
+                      int32_t B, int32_t L, float* loss, uint64_t* peak_bytes, uint64_t* plan_id);
+
+/* Same planning, allocation and bookkeeping as mimose_train_step but no device work:
+ * reports the peak the step would reach.  Works on host-only contexts. */
+int mimose_dry_step(mimose_ctx* ctx, int32_t B, int32_t L, uint64_t* peak_bytes, uint64_t* plan_id);
+
+/* Gradient of parameter i from the last completed step, as fp32 to host. Synchronous. */
+int mimose_get_grad(mimose_ctx* ctx, int32_t i, float* host_fp32, uint64_t n_elems);
+
+/* Test hook: plan >= 0 forces that bitmask on every following step (0 = keep everything)
+ * and suspends the phase logic; -1 returns control to the planner. */
+int mimose_force_plan(mimose_ctx* ctx, int64_t plan_or_minus1);
+
+/* Host-only planner access (Section 4.2-4.4): inject a collected sample / ask for a plan. */
+int mimose_planner_feed(mimose_ctx* ctx, int32_t B, int32_t L, int32_t quantity, int32_t layer,
+                        uint64_t bytes);
+/* Marks the end of one sheltered iteration at this input size (phase accounting). */
+int mimose_planner_end_step(mimose_ctx* ctx, int32_t B, int32_t L);
+/* Plan for input size B*L from the fitted estimator (fits on first use); counts as a cache
+ * lookup.  Returns NOT_READY while the planner is still in the sheltered phase and
+ * BUDGET_INFEASIBLE (plan = all layers, predicted_peak filled) if no plan fits. */
+int mimose_planner_query(mimose_ctx* ctx, int32_t B, int32_t L, uint64_t* plan,
+                         uint64_t* predicted_peak);
+
+/* What the collector measured in the last completed step (Section 4.2), in bytes: fixed F,
+ * embedding stage e, head transient g, and per layer (arrays of n_layers, may be NULL) the
+ * bytes kept (a_l), kept when checkpointed (b_l) and the backward transient (w_l). */
+int mimose_get_step_memory(mimose_ctx* ctx, uint64_t* fixed, uint64_t* embed, uint64_t* head,
+                           uint64_t* kept, uint64_t* boundary, uint64_t* bwd);
+
+int mimose_get_stats(mimose_ctx* ctx, mimose_stats* out);
+const char* mimose_last_error(mimose_ctx* ctx); /* ctx may be NULL: last init error */
+void mimose_destroy(mimose_ctx* ctx);
+
+/* ------------------------------------------------------------------------
+ * Kernel-level entry points (device pointers, current device, given stream).
+ * These are the kernels the training step is made of, exposed for parity tests
+ * and per-kernel measurement.  dtype as in mimose_model_cfg.  No allocation.
+ * ---------------------------------------------------------------------- */
+
+/* C[M,N] = sum_k A(m,k) B(n,k) (+ bias[n]) (+ resid[m,n]); optional GELU: C receives the
+ * pre-activation, gelu_out the activation.  a_kmajor: A(m,k) = A[m*lda+k], else A[k*lda+m];
+ * likewise B with ldb.  c_f32: C is fp32 regardless of dtype (weight gradients).
+ * a_rowsum (optional, fp32[M]) receives sum_k A(m,k) (the bias gradient of a weight-gradient
+ * product).  gelu: 0 none, 1 erf, 2 tanh.  bf16: lda, ldb must be multiples of 8 and A, B
+ * 16-byte aligned, otherwise INVALID_ARG. */
+int mimose_op_gemm(int32_t dtype, const void* A, int64_t lda, int32_t a_kmajor, const void* B,
+                   int64_t ldb, int32_t b_kmajor, void* C, int64_t ldc, int32_t c_f32, int32_t M,
+                   int32_t N, int32_t K, const void* bias, const void* resid, int64_t ldr,
+                   void* gelu_out, int32_t gelu, float* a_rowsum, void* stream);
+/* y = LayerNorm(x) * gamma + beta over rows of length H <= 1024. */
+int mimose_op_layernorm_fwd(int32_t dtype, const void* x, const void* gamma, const void* beta,
+                            void* y, int32_t T, int32_t H, float eps, void* stream);
+/* dx (may alias dy) = LayerNorm backward of dy at x (+ add[T,H] when not NULL); dgamma, dbeta
+ * fp32[H]; partial: fp32 scratch of mimose_op_partial_rows(T)*2*H elements. */
+int mimose_op_layernorm_bwd(int32_t dtype, const void* dy, const void* x, const void* gamma,
+                            void* dx, const void* add, float* dgamma, float* dbeta, float* partial,
+                            int32_t T, int32_t H, float eps, void* stream);
+int32_t mimose_op_partial_rows(int32_t T);
+/* d[n] (in place) *= gelu'(pre[n]). */
+int mimose_op_gelu_bwd(int32_t dtype, void* d, const void* pre, int64_t n, int32_t tanh_form,
+                       void* stream);
+/* qkv [B*L, 3*H] (q | k | v, heads contiguous inside each) -> ctx [B*L, H], lse fp32 [B, h, L].
+ * head_dim must be 32, 64 or 128. */
+int mimose_op_attention_fwd(int32_t dtype, const void* qkv, void* ctx, float* lse, int32_t B,
+                            int32_t L, int32_t n_heads, int32_t head_dim, int32_t causal,
+                            void* stream);
+/* dqkv from qkv, ctx, dctx, lse; delta: fp32 scratch [B, h, L]. */
+int mimose_op_attention_bwd(int32_t dtype, const void* qkv, const void* ctx, const void* dctx,
+                            const float* lse, float* delta, void* dqkv, int32_t B, int32_t L,
+                            int32_t n_heads, int32_t head_dim, int32_t causal, void* stream);
+/* logits [T, ld] (first V columns valid) -> in place d loss / d logits (columns >= V zeroed);
+ * row_loss fp32[T]; loss: device fp32 scalar = sum(row_loss)/n_valid. */
+int mimose_op_softmax_xent(int32_t dtype, void* logits, int64_t ld, const int32_t* labels,
+                           float* row_loss, float* loss, int32_t T, int32_t V, int32_t n_valid,
+                           void* stream);
+/* sum_out (may be NULL when has_ln = 0) = tok_emb[id] + pos_emb[pos]; y = LN(sum) or sum. */
+int mimose_op_embed_fwd(int32_t dtype, const int32_t* ids, const void* tok_emb, const void* pos_emb,
+                        const void* gamma, const void* beta, void* sum_out, void* y, int32_t B,
+                        int32_t L, int32_t H, float eps, int32_t has_ln, void* stream);
+/* Deterministic scatter-add of d[T,H] into dtok (fp32 [V,H], accumulated onto) and dpos
+ * (fp32 [max_seq,H], overwritten; rows >= L cleared).  order: token positions sorted by id
+ * (ties by position); seg: start offsets of each distinct id's run in order (n_seg+1 entries). */
+int mimose_op_embed_bwd(int32_t dtype, const void* d, const int32_t* ids, const int32_t* order,
+                        const int32_t* seg, int32_t n_seg, float* dtok, float* dpos, int32_t B,
+                        int32_t L, int32_t H, int32_t max_seq, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

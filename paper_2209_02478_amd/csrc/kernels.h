@@ -1,0 +1,58 @@
+// Launchers of the gfx950 kernels the training step is made of.
+// All pointers are device pointers; every launcher only enqueues work on `st`.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mk {
+
+enum DType : int { F32 = 0, BF16 = 1 };
+enum Gelu : int { GELU_NONE = 0, GELU_ERF = 1, GELU_TANH = 2 };
+
+constexpr int kMaxRowWidth = 1024;  // widest row the row-wise kernels accept (hidden size)
+
+inline size_t elt_size(int dtype) { return dtype == BF16 ? 2 : 4; }
+
+struct GemmArgs {
+  const void* A; int64_t lda; bool a_kmajor;
+  const void* B; int64_t ldb; bool b_kmajor;
+  void* C; int64_t ldc; bool c_f32;
+  int M, N, K;
+  const void* bias = nullptr;      // [N], storage dtype
+  const void* resid = nullptr;     // [M, ldr], storage dtype
+  int64_t ldr = 0;
+  void* gelu_out = nullptr;        // [M, ldc], storage dtype
+  int gelu = GELU_NONE;
+  float* a_rowsum = nullptr;       // [M] fp32: sum_k A(m,k) (bias gradient of a weight-gradient product)
+};
+
+// returns false when the arguments violate the kernel's alignment assumptions
+bool gemm(int dtype, const GemmArgs& g, hipStream_t st);
+
+void layernorm_fwd(int dtype, const void* x, const void* gamma, const void* beta, void* y,
+                   int T, int H, float eps, hipStream_t st);
+// partial: fp32 scratch of partial_rows(T) * 2 * H elements
+// dx = LayerNorm backward (+ add when given); dx may alias dy
+void layernorm_bwd(int dtype, const void* dy, const void* x, const void* gamma, void* dx,
+                   const void* add, float* dgamma, float* dbeta, float* partial, int T, int H,
+                   float eps, hipStream_t st);
+int partial_rows(int T);
+void gelu_bwd(int dtype, void* d, const void* pre, int64_t n, int tanh_form, hipStream_t st);
+void attention_fwd(int dtype, const void* qkv, void* ctx, float* lse, int B, int L, int nh, int d,
+                   int causal, hipStream_t st);
+void attention_bwd(int dtype, const void* qkv, const void* ctx, const void* dctx, const float* lse,
+                   float* delta, void* dqkv, int B, int L, int nh, int d, int causal,
+                   hipStream_t st);
+void softmax_xent(int dtype, void* logits, int64_t ld, const int32_t* labels, float* row_loss,
+                  float* loss, int T, int V, int n_valid, hipStream_t st);
+void embed_fwd(int dtype, const int32_t* ids, const void* tok, const void* pos, const void* gamma,
+               const void* beta, void* sum_out, void* y, int B, int L, int H, float eps, int has_ln,
+               hipStream_t st);
+void embed_bwd(int dtype, const void* d, const int32_t* ids, const int32_t* order,
+               const int32_t* seg, int n_seg, float* dtok, float* dpos, int B, int L, int H,
+               int max_seq, hipStream_t st);
+// dst (storage dtype) = round(src fp32)
+void convert_from_f32(int dtype, const float* src, void* dst, int64_t n, hipStream_t st);
+void fill_zero(void* p, int64_t bytes, hipStream_t st);
+
+}  // namespace mk

@@ -1,0 +1,737 @@
+// libmimose: context, budget-enforcing activation stack, step executor and the C ABI.
+//
+// Device memory is one caller-provided arena.  The bottom holds parameters and fp32
+// gradients (the fixed bytes F); above it a LIFO stack holds the step's activations.
+// Every layer allocates its output first and its internal tensors above it, so dropping a
+// layer (paper Section 5: checkpointing keeps only the boundary tensor) is a pop to just
+// above the output, and rebuilding it in backward pushes the same tensors again and replays
+// the same kernel launches.  The stack's high-water mark is the step's true peak.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cstdio>
+#include <cstring>
+#include <memory>
+#include <string>
+#include <vector>
+
+#include "../../include/mimose.h"
+#include "kernels.h"
+#include "planner.h"
+
+namespace {
+
+struct OomError { uint64_t want, top, cap; };
+struct StepError { int code; std::string msg; };
+
+constexpr uint64_t kAlign = 256;
+inline uint64_t align_up(uint64_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+class Arena {
+ public:
+  void init(char* base, uint64_t cap) { base_ = base; cap_ = cap; top_ = high_ = section_high_ = 0; }
+  void* alloc(uint64_t bytes) {
+    const uint64_t sz = align_up(bytes);
+    if (top_ + sz > cap_) throw OomError{sz, top_, cap_};
+    void* p = base_ ? base_ + top_ : nullptr;
+    top_ += sz;
+    high_ = std::max(high_, top_);
+    section_high_ = std::max(section_high_, top_);
+    return p;
+  }
+  uint64_t top() const { return top_; }
+  uint64_t high() const { return high_; }
+  void pop_to(uint64_t mark) { top_ = mark; }
+  void reset_high() { high_ = top_; }
+  void begin_section() { section_high_ = top_; }
+  uint64_t section_high() const { return section_high_; }
+  uint64_t cap() const { return cap_; }
+ private:
+  char* base_ = nullptr;
+  uint64_t cap_ = 0, top_ = 0, high_ = 0, section_high_ = 0;
+};
+
+struct Param {
+  std::string name;
+  int64_t shape[4] = {0, 0, 0, 0};
+  int ndim = 0;
+  int64_t n = 0;
+  void* w = nullptr;    // storage dtype
+  float* g = nullptr;   // fp32 gradient
+};
+
+struct LayerIdx { int wqkv, bqkv, wo, bo, ln1g, ln1b, w1, b1, w2, b2, ln2g, ln2b; };
+
+struct LayerActs {       // device tensors of one layer, in allocation order
+  uint64_t mark = 0;     // stack top before the layer
+  uint64_t after_out = 0;
+  bool dropped = false;
+  const void* x = nullptr;                       // layer input (previous boundary)
+  void *out = nullptr, *n1 = nullptr, *qkv = nullptr, *ctx = nullptr, *s1 = nullptr, *u = nullptr,
+       *pre = nullptr, *act = nullptr, *s2 = nullptr;
+  float* lse = nullptr;
+};
+
+}  // namespace
+
+struct mimose_ctx {
+  mimose_model_cfg cfg;
+  uint64_t budget = 0;
+  bool has_device = false;
+  hipStream_t stream = nullptr;
+  Arena arena;
+  uint64_t fixed_top = 0;
+  std::vector<Param> params;
+  std::vector<LayerIdx> lidx;
+  int i_tok = -1, i_pos = -1, i_eg = -1, i_eb = -1, i_fg = -1, i_fb = -1, i_wt = -1, i_bt = -1, i_hg = -1,
+      i_hb = -1, i_bdec = -1;
+  std::unique_ptr<mimose::Planner> planner;
+  int64_t forced_plan = -1;
+  mimose_stats stats;
+  std::string err;
+  // pinned host staging for ids / labels / sort order / segments and the loss
+  int32_t* stage = nullptr;
+  size_t stage_ints = 0;
+  float* loss_host = nullptr;
+  bool dry = false;
+  std::vector<LayerActs> acts;
+  // memory components measured in the last completed step
+  uint64_t last_e = 0, last_g = 0;
+  std::vector<uint64_t> last_a, last_b, last_w;
+
+  int elt() const { return cfg.dtype == mk::BF16 ? 2 : 4; }
+  int64_t ldv() const { return (cfg.vocab + 63) / 64 * 64; }
+};
+
+static thread_local std::string g_init_error;
+
+namespace {
+
+int fail(mimose_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg; else g_init_error = msg;
+  return code;
+}
+
+#define HIPCHK(c, call)                                                                     \
+  do {                                                                                      \
+    hipError_t e_ = (call);                                                                 \
+    if (e_ != hipSuccess) throw StepError{MIMOSE_ERR_HIP, std::string(#call) + ": " + hipGetErrorString(e_)}; \
+  } while (0)
+
+int add_param(mimose_ctx* c, const std::string& name, std::initializer_list<int64_t> shape) {
+  Param p;
+  p.name = name;
+  p.n = 1;
+  for (int64_t s : shape) { p.shape[p.ndim++] = s; p.n *= s; }
+  c->params.push_back(p);
+  return (int)c->params.size() - 1;
+}
+
+void build_params(mimose_ctx* c) {
+  const auto& f = c->cfg;
+  const int64_t H = f.hidden, F = f.ffn, V = f.vocab;
+  c->i_tok = add_param(c, "tok_emb", {V, H});
+  c->i_pos = add_param(c, "pos_emb", {f.max_seq, H});
+  if (!f.pre_ln) { c->i_eg = add_param(c, "emb_ln_g", {H}); c->i_eb = add_param(c, "emb_ln_b", {H}); }
+  for (int l = 0; l < f.n_layers; ++l) {
+    const std::string p = "layer" + std::to_string(l) + ".";
+    LayerIdx x;
+    x.wqkv = add_param(c, p + "wqkv", {3 * H, H}); x.bqkv = add_param(c, p + "bqkv", {3 * H});
+    x.wo = add_param(c, p + "wo", {H, H});         x.bo = add_param(c, p + "bo", {H});
+    x.ln1g = add_param(c, p + "ln1_g", {H});       x.ln1b = add_param(c, p + "ln1_b", {H});
+    x.w1 = add_param(c, p + "w1", {F, H});         x.b1 = add_param(c, p + "b1", {F});
+    x.w2 = add_param(c, p + "w2", {H, F});         x.b2 = add_param(c, p + "b2", {H});
+    x.ln2g = add_param(c, p + "ln2_g", {H});       x.ln2b = add_param(c, p + "ln2_b", {H});
+    c->lidx.push_back(x);
+  }
+  if (f.pre_ln) { c->i_fg = add_param(c, "final_ln_g", {H}); c->i_fb = add_param(c, "final_ln_b", {H}); }
+  if (f.head) {
+    c->i_wt = add_param(c, "head.wt", {H, H});   c->i_bt = add_param(c, "head.bt", {H});
+    c->i_hg = add_param(c, "head.ln_g", {H});    c->i_hb = add_param(c, "head.ln_b", {H});
+    c->i_bdec = add_param(c, "head.bdec", {V});
+  }
+}
+
+// ------------------------------------------------------------------ step executor
+class Step {
+ public:
+  Step(mimose_ctx* c, int B, int L, uint64_t plan, bool collect)
+      : c_(c), f_(c->cfg), B_(B), L_(L), T_(B * L), plan_(plan), collect_(collect), dry_(c->dry),
+        st_(c->stream), dt_(c->cfg.dtype), es_(c->elt()) {}
+
+  void run(const int32_t* tokens, const int32_t* labels, float* loss_out);
+
+  // collected bytes (valid after run)
+  uint64_t e_bytes = 0, g_bytes = 0;
+  std::vector<uint64_t> a_bytes, b_bytes, w_bytes;
+
+ private:
+  mimose_ctx* c_;
+  const mimose_model_cfg& f_;
+  int B_, L_, T_;
+  uint64_t plan_;
+  bool collect_, dry_;
+  hipStream_t st_;
+  int dt_, es_;
+  // embedding-stage tensors
+  int32_t *ids_ = nullptr, *labels_ = nullptr, *order_ = nullptr, *seg_ = nullptr;
+  void *dA_ = nullptr, *dB_ = nullptr, *emb_sum_ = nullptr, *h0_ = nullptr;
+  int n_seg_ = 0, n_valid_ = 0;
+
+  void* w(int i) const { return c_->params[i].w; }
+  float* g(int i) const { return c_->params[i].g; }
+  void* talloc(int64_t elems) { return c_->arena.alloc((uint64_t)elems * es_); }
+
+  void gemm(const mk::GemmArgs& a) {
+    if (dry_) return;
+    if (!mk::gemm(dt_, a, st_)) throw StepError{MIMOSE_ERR_INVALID_ARG, "gemm: unsupported alignment"};
+  }
+  // Y[T,out] = X[T,in] W[out,in]^T + bias (+ resid) (GELU: Y = pre-activation, act = GELU(Y))
+  void linear(const void* X, int in, int wi, int bi, void* Y, int out, int64_t ldy, const void* resid = nullptr,
+              void* act = nullptr, int gelu = 0, int rows = -1) {
+    mk::GemmArgs a{X, in, true, w(wi), in, true, Y, ldy, false, rows < 0 ? T_ : rows, out, in};
+    a.bias = bi >= 0 ? w(bi) : nullptr;
+    a.resid = resid; a.ldr = out;
+    a.gelu_out = act; a.gelu = gelu;
+    gemm(a);
+  }
+  // dX[T,in] = dY[T,out] W[out,in] (+ resid)
+  void dgrad(const void* dY, int64_t ldy, int out, int wi, void* dX, int in, const void* resid = nullptr) {
+    mk::GemmArgs a{dY, ldy, true, w(wi), in, false, dX, in, false, T_, in, out};
+    a.resid = resid; a.ldr = in;
+    gemm(a);
+  }
+  // dW[out,in] = dY^T X, db[out] = column sums of dY
+  void wgrad(const void* dY, int64_t ldy, int out, const void* X, int in, int wi, int bi) {
+    mk::GemmArgs a{dY, ldy, false, X, in, false, g(wi), in, true, out, in, T_};
+    a.a_rowsum = bi >= 0 ? g(bi) : nullptr;
+    gemm(a);
+  }
+  void ln_fwd(const void* x, int gi, int bi, void* y) {
+    if (!dry_) mk::layernorm_fwd(dt_, x, w(gi), w(bi), y, T_, f_.hidden, f_.ln_eps, st_);
+  }
+  void ln_bwd(const void* dy, const void* x, int gi, int bi, void* dx, const void* add) {
+    const uint64_t m = c_->arena.top();
+    float* partial = (float*)c_->arena.alloc((uint64_t)mk::partial_rows(T_) * 2 * f_.hidden * 4);
+    if (!dry_) mk::layernorm_bwd(dt_, dy, x, w(gi), dx, add, g(gi), g(bi), partial, T_, f_.hidden, f_.ln_eps, st_);
+    c_->arena.pop_to(m);
+  }
+
+  void embed_stage(const int32_t* tokens, const int32_t* labels);
+  void alloc_layer(int l, LayerActs& A);
+  void layer_forward(int l, LayerActs& A);
+  void layer_backward(int l, LayerActs& A);
+  void head(float* loss_dev);
+  void embed_backward();
+};
+
+void Step::embed_stage(const int32_t* tokens, const int32_t* labels) {
+  const int H = f_.hidden;
+  int32_t* ints = (int32_t*)c_->arena.alloc((uint64_t)(4 * (int64_t)T_ + 1) * 4);
+  ids_ = ints; labels_ = ints ? ints + T_ : nullptr; order_ = ints ? ints + 2 * (int64_t)T_ : nullptr;
+  seg_ = ints ? ints + 3 * (int64_t)T_ : nullptr;
+  dA_ = talloc((int64_t)T_ * H);
+  dB_ = talloc((int64_t)T_ * H);
+  if (!f_.pre_ln) emb_sum_ = talloc((int64_t)T_ * H);
+  h0_ = talloc((int64_t)T_ * H);
+  if (dry_) return;
+
+  // host side: stable sort of positions by token id, run boundaries of equal ids
+  const size_t need = 4 * (size_t)T_ + 1;
+  if (c_->stage_ints < need) {
+    if (c_->stage) HIPCHK(c_, hipHostFree(c_->stage));
+    c_->stage = nullptr;
+    HIPCHK(c_, hipHostMalloc((void**)&c_->stage, need * 4 + 1024, hipHostMallocDefault));
+    c_->stage_ints = need;
+  }
+  int32_t* s = c_->stage;
+  std::memcpy(s, tokens, (size_t)T_ * 4);
+  std::memcpy(s + T_, labels, (size_t)T_ * 4);
+  std::vector<int32_t> count((size_t)f_.vocab + 1, 0);
+  for (int t = 0; t < T_; ++t) ++count[(size_t)tokens[t] + 1];
+  n_seg_ = 0;
+  int32_t* seg = s + 3 * (size_t)T_;
+  for (int v = 0; v < f_.vocab; ++v) {
+    if (count[v + 1]) seg[n_seg_++] = count[v];
+    count[v + 1] += count[v];
+  }
+  seg[n_seg_] = T_;
+  int32_t* order = s + 2 * (size_t)T_;
+  for (int t = 0; t < T_; ++t) order[count[tokens[t]]++] = t;
+  HIPCHK(c_, hipMemcpyAsync(ints, s, need * 4, hipMemcpyHostToDevice, st_));
+  mk::embed_fwd(dt_, ids_, w(c_->i_tok), w(c_->i_pos), f_.pre_ln ? nullptr : w(c_->i_eg),
+                f_.pre_ln ? nullptr : w(c_->i_eb), emb_sum_, h0_, B_, L_, H, f_.ln_eps, !f_.pre_ln, st_);
+}
+
+void Step::alloc_layer(int l, LayerActs& A) {
+  (void)l;
+  const int64_t TH = (int64_t)T_ * f_.hidden, TF = (int64_t)T_ * f_.ffn;
+  if (!A.out) {                       // first pass: the boundary tensor goes first
+    A.mark = c_->arena.top();
+    A.out = talloc(TH);
+    A.after_out = c_->arena.top();
+  }
+  if (f_.pre_ln) A.n1 = talloc(TH);   // LN1(x)
+  A.qkv = talloc(3 * TH);
+  A.lse = (float*)c_->arena.alloc((uint64_t)B_ * f_.n_heads * L_ * 4);
+  A.ctx = talloc(TH);
+  A.s1 = talloc(TH);                  // post-LN: x + proj (LN1 input); pre-LN: u = x + proj
+  A.u = talloc(TH);                   // post-LN: LN1(s1); pre-LN: LN2(u)
+  A.pre = talloc(TF);
+  A.act = talloc(TF);
+  if (!f_.pre_ln) A.s2 = talloc(TH);  // post-LN: u + ffn (LN2 input)
+}
+
+void Step::layer_forward(int l, LayerActs& A) {
+  const LayerIdx& p = c_->lidx[l];
+  const int H = f_.hidden, F = f_.ffn, nh = f_.n_heads, d = H / nh;
+  const int gelu = f_.gelu_tanh ? mk::GELU_TANH : mk::GELU_ERF;
+  const void* a = A.x;
+  if (f_.pre_ln) { ln_fwd(A.x, p.ln1g, p.ln1b, A.n1); a = A.n1; }
+  linear(a, H, p.wqkv, p.bqkv, A.qkv, 3 * H, 3 * H);
+  if (!dry_) mk::attention_fwd(dt_, A.qkv, A.ctx, A.lse, B_, L_, nh, d, f_.causal, st_);
+  linear(A.ctx, H, p.wo, p.bo, A.s1, H, H, A.x);
+  if (f_.pre_ln) {
+    ln_fwd(A.s1, p.ln2g, p.ln2b, A.u);
+    linear(A.u, H, p.w1, p.b1, A.pre, F, F, nullptr, A.act, gelu);
+    linear(A.act, F, p.w2, p.b2, A.out, H, H, A.s1);
+  } else {
+    ln_fwd(A.s1, p.ln1g, p.ln1b, A.u);
+    linear(A.u, H, p.w1, p.b1, A.pre, F, F, nullptr, A.act, gelu);
+    linear(A.act, F, p.w2, p.b2, A.s2, H, H, A.u);
+    ln_fwd(A.s2, p.ln2g, p.ln2b, A.out);
+  }
+}
+
+// Gradient of the layer output arrives in dA_; the gradient of its input leaves in dA_.
+void Step::layer_backward(int l, LayerActs& A) {
+  const LayerIdx& p = c_->lidx[l];
+  const int H = f_.hidden, F = f_.ffn, nh = f_.n_heads, d = H / nh;
+  const int64_t TH = (int64_t)T_ * H, TF = (int64_t)T_ * F;
+  Arena& ar = c_->arena;
+  const uint64_t m0 = ar.top();
+  if (!f_.pre_ln) ln_bwd(dA_, A.s2, p.ln2g, p.ln2b, dA_, nullptr);           // dA = d s2
+  wgrad(dA_, H, H, A.act, F, p.w2, p.b2);
+  void* dact = talloc(TF);
+  dgrad(dA_, H, H, p.w2, dact, F);
+  if (!dry_) mk::gelu_bwd(dt_, dact, A.pre, TF, f_.gelu_tanh, st_);          // dact = d pre
+  wgrad(dact, F, F, A.u, H, p.w1, p.b1);
+  if (f_.pre_ln) {
+    dgrad(dact, F, F, p.w1, dB_, H);                                          // dB = d LN2(u)
+    ar.pop_to(m0);
+    ln_bwd(dB_, A.s1, p.ln2g, p.ln2b, dB_, dA_);                              // dB = d u
+  } else {
+    dgrad(dact, F, F, p.w1, dB_, H, dA_);                                     // dB = d u
+    ar.pop_to(m0);
+    ln_bwd(dB_, A.s1, p.ln1g, p.ln1b, dB_, nullptr);                          // dB = d s1
+  }
+  wgrad(dB_, H, H, A.ctx, H, p.wo, p.bo);
+  void* dctx = talloc(TH);
+  dgrad(dB_, H, H, p.wo, dctx, H);
+  void* dqkv = talloc(3 * TH);
+  float* delta = (float*)ar.alloc((uint64_t)B_ * nh * L_ * 4);
+  if (!dry_) mk::attention_bwd(dt_, A.qkv, A.ctx, dctx, A.lse, delta, dqkv, B_, L_, nh, d, f_.causal, st_);
+  const void* a = f_.pre_ln ? A.n1 : A.x;
+  wgrad(dqkv, 3 * H, 3 * H, a, H, p.wqkv, p.bqkv);
+  if (f_.pre_ln) {
+    dgrad(dqkv, 3 * H, 3 * H, p.wqkv, dA_, H);                                // dA = d LN1(x)
+    ar.pop_to(m0);
+    ln_bwd(dA_, A.x, p.ln1g, p.ln1b, dA_, dB_);                               // dA = d x
+  } else {
+    dgrad(dqkv, 3 * H, 3 * H, p.wqkv, dA_, H, dB_);                           // dA = d x
+    ar.pop_to(m0);
+  }
+}
+
+// Head forward, loss, head backward.  Leaves the gradient of the last layer's output in dA_.
+void Step::head(float* loss_dev) {
+  const int H = f_.hidden, V = f_.vocab;
+  const int64_t TH = (int64_t)T_ * H, ldv = c_->ldv();
+  const int gelu = f_.gelu_tanh ? mk::GELU_TANH : mk::GELU_ERF;
+  const void* hlast = f_.n_layers ? c_->acts[f_.n_layers - 1].out : h0_;
+  const void* hs = hlast;
+  void* hs_buf = nullptr;
+  if (f_.pre_ln) { hs_buf = talloc(TH); ln_fwd(hlast, c_->i_fg, c_->i_fb, hs_buf); hs = hs_buf; }
+  void *z = nullptr, *gz = nullptr, *t = nullptr;
+  const void* dec_in = hs;
+  if (f_.head) {
+    z = talloc(TH); gz = talloc(TH); t = talloc(TH);
+    linear(hs, H, c_->i_wt, c_->i_bt, z, H, H, nullptr, gz, gelu);
+    ln_fwd(gz, c_->i_hg, c_->i_hb, t);
+    dec_in = t;
+  }
+  void* logits = talloc((int64_t)T_ * ldv);
+  float* row_loss = (float*)c_->arena.alloc((uint64_t)T_ * 4);
+  {
+    mk::GemmArgs a{dec_in, H, true, w(c_->i_tok), H, true, logits, ldv, false, T_, V, H};
+    a.bias = f_.head ? w(c_->i_bdec) : nullptr;
+    gemm(a);
+  }
+  if (!dry_) mk::softmax_xent(dt_, logits, ldv, labels_, row_loss, loss_dev, T_, V, n_valid_, st_);
+  // tied decoder: its weight gradient overwrites the embedding gradient, the embedding
+  // backward adds onto it later
+  {
+    mk::GemmArgs a{logits, ldv, false, dec_in, H, false, g(c_->i_tok), H, true, V, H, T_};
+    a.a_rowsum = f_.head ? g(c_->i_bdec) : nullptr;
+    gemm(a);
+  }
+  void* dhs = f_.pre_ln ? talloc(TH) : dA_;
+  if (f_.head) {
+    void* dt = talloc(TH);
+    { mk::GemmArgs a{logits, ldv, true, w(c_->i_tok), H, false, dt, H, false, T_, H, V}; gemm(a); }
+    ln_bwd(dt, gz, c_->i_hg, c_->i_hb, dt, nullptr);                          // dt = d gz
+    if (!dry_) mk::gelu_bwd(dt_, dt, z, TH, f_.gelu_tanh, st_);               // dt = d z
+    wgrad(dt, H, H, hs, H, c_->i_wt, c_->i_bt);
+    dgrad(dt, H, H, c_->i_wt, dhs, H);
+  } else {
+    mk::GemmArgs a{logits, ldv, true, w(c_->i_tok), H, false, dhs, H, false, T_, H, V};
+    gemm(a);
+  }
+  if (f_.pre_ln) ln_bwd(dhs, hlast, c_->i_fg, c_->i_fb, dA_, nullptr);
+}
+
+void Step::embed_backward() {
+  const int H = f_.hidden;
+  if (!f_.pre_ln) ln_bwd(dA_, emb_sum_, c_->i_eg, c_->i_eb, dA_, nullptr);
+  if (!dry_)
+    mk::embed_bwd(dt_, dA_, ids_, order_, seg_, n_seg_, g(c_->i_tok), g(c_->i_pos), B_, L_, H, f_.max_seq, st_);
+}
+
+void Step::run(const int32_t* tokens, const int32_t* labels, float* loss_out) {
+  Arena& ar = c_->arena;
+  const int N = f_.n_layers;
+  a_bytes.assign(N, 0); b_bytes.assign(N, 0); w_bytes.assign(N, 0);
+  ar.pop_to(c_->fixed_top);
+  ar.reset_high();
+  if (!dry_) {
+    n_valid_ = 0;
+    for (int t = 0; t < T_; ++t) n_valid_ += labels[t] >= 0;
+  }
+  const uint64_t base = ar.top();
+  float* loss_dev = (float*)ar.alloc(4);
+  embed_stage(tokens, labels);
+  e_bytes = ar.top() - base;
+
+  c_->acts.assign(N, LayerActs());
+  const void* x = h0_;
+  for (int l = 0; l < N; ++l) {
+    LayerActs& A = c_->acts[l];
+    A.x = x;
+    alloc_layer(l, A);
+    layer_forward(l, A);
+    a_bytes[l] = ar.top() - A.mark;
+    b_bytes[l] = A.after_out - A.mark;
+    if ((plan_ >> l) & 1) { ar.pop_to(A.after_out); A.dropped = true; }
+    x = A.out;
+  }
+
+  const uint64_t m_head = ar.top();
+  ar.begin_section();
+  head(loss_dev);
+  g_bytes = ar.section_high() - m_head;
+  ar.pop_to(m_head);
+
+  for (int l = N - 1; l >= 0; --l) {
+    LayerActs& A = c_->acts[l];
+    if (A.dropped) {                      // rebuild: same tensors, same launches
+      alloc_layer(l, A);
+      layer_forward(l, A);
+    }
+    const uint64_t m = ar.top();
+    ar.begin_section();
+    layer_backward(l, A);
+    w_bytes[l] = ar.section_high() - m;
+    ar.pop_to(A.mark);
+  }
+  embed_backward();
+  if (!dry_) {
+    HIPCHK(c_, hipMemcpyAsync(c_->loss_host, loss_dev, 4, hipMemcpyDeviceToHost, st_));
+    HIPCHK(c_, hipStreamSynchronize(st_));
+    HIPCHK(c_, hipGetLastError());
+    *loss_out = *c_->loss_host;
+  }
+}
+
+void flops(const mimose_model_cfg& f, int B, int L, int n_re, double* useful, double* re) {
+  const double T = (double)B * L, H = f.hidden, F = f.ffn, V = f.vocab;
+  const double attn = 4.0 * L * H * (f.causal ? 0.5 : 1.0);
+  const double layer = 8.0 * H * H + 4.0 * H * F + attn;
+  const double head = 2.0 * H * V + (f.head ? 2.0 * H * H : 0.0);
+  *useful = 3.0 * T * (f.n_layers * layer + head);
+  *re = T * layer * n_re;
+}
+
+int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, int32_t B, int32_t L, bool dry,
+            float* loss, uint64_t* peak, uint64_t* plan_id) {
+  const auto& f = c->cfg;
+  if (B < 1 || L < 1 || L > f.max_seq) return fail(c, MIMOSE_ERR_INVALID_ARG, "B >= 1 and 1 <= L <= max_seq required");
+  if ((int64_t)B * L > (int64_t)1 << 28) return fail(c, MIMOSE_ERR_INVALID_ARG, "B*L too large");
+  if (!dry) {
+    if (!c->has_device) return fail(c, MIMOSE_ERR_NOT_READY, "host-only context: no device arena");
+    if (!tokens || !labels) return fail(c, MIMOSE_ERR_INVALID_ARG, "tokens and labels must be given");
+    const int64_t T = (int64_t)B * L;
+    for (int64_t t = 0; t < T; ++t) {
+      if (tokens[t] < 0 || tokens[t] >= f.vocab) return fail(c, MIMOSE_ERR_INVALID_ARG, "token id out of range");
+      if (labels[t] < -1 || labels[t] >= f.vocab) return fail(c, MIMOSE_ERR_INVALID_ARG, "label out of range");
+    }
+  }
+  const int64_t x = (int64_t)B * L;
+  const uint64_t all = f.n_layers >= 64 ? ~(uint64_t)0 : (((uint64_t)1 << f.n_layers) - 1);
+  // ---- plan (host only, on the critical path of every iteration)
+  const auto t0 = std::chrono::steady_clock::now();
+  uint64_t plan = 0;
+  bool collect = false;
+  int64_t predicted = 0;
+  if (c->forced_plan >= 0) {
+    plan = (uint64_t)c->forced_plan & all;
+  } else if (c->planner->sheltered()) {
+    plan = all;
+    collect = true;
+  } else {
+    mimose::PlanOut po;
+    bool hit = false;
+    const int rc = c->planner->query(x, &po, &hit);
+    if (rc == -1) return fail(c, MIMOSE_ERR_NOT_READY, "estimator could not be fitted");
+    predicted = po.predicted_peak;
+    if (rc == -2) {
+      c->stats.predicted_peak_last = (uint64_t)predicted;
+      return fail(c, MIMOSE_ERR_BUDGET_INFEASIBLE, "predicted peak exceeds the budget even with every layer checkpointed");
+    }
+    plan = po.plan;
+  }
+  const uint64_t ns = (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
+                          std::chrono::steady_clock::now() - t0).count();
+  // ---- run
+  c->dry = dry;
+  Step s(c, B, L, plan, collect);
+  float lv = 0.f;
+  try {
+    s.run(tokens, labels, &lv);
+  } catch (const OomError& e) {
+    c->arena.pop_to(c->fixed_top);
+    if (!dry && c->has_device) (void)hipStreamSynchronize(c->stream);
+    char buf[160];
+    snprintf(buf, sizeof buf, "allocation of %llu bytes at %llu exceeds the budget of %llu bytes",
+             (unsigned long long)e.want, (unsigned long long)e.top, (unsigned long long)e.cap);
+    return fail(c, MIMOSE_ERR_OOM_BUDGET, buf);
+  } catch (const StepError& e) {
+    c->arena.pop_to(c->fixed_top);
+    if (!dry && c->has_device) (void)hipStreamSynchronize(c->stream);
+    return fail(c, e.code, e.msg);
+  }
+  const uint64_t pk = c->arena.high();
+  c->arena.pop_to(c->fixed_top);
+  c->last_e = s.e_bytes; c->last_g = s.g_bytes;
+  c->last_a = s.a_bytes; c->last_b = s.b_bytes; c->last_w = s.w_bytes;
+  if (collect) {
+    auto& pl = *c->planner;
+    for (int l = 0; l < f.n_layers; ++l) {
+      pl.feed(x, MIMOSE_Q_LAYER_KEPT, l, s.a_bytes[l]);
+      pl.feed(x, MIMOSE_Q_LAYER_BOUNDARY, l, s.b_bytes[l]);
+      pl.feed(x, MIMOSE_Q_LAYER_BWD, l, s.w_bytes[l]);
+    }
+    pl.feed(x, MIMOSE_Q_EMBED, -1, s.e_bytes);
+    pl.feed(x, MIMOSE_Q_HEAD, -1, s.g_bytes);
+    pl.feed(x, MIMOSE_Q_FIXED, -1, c->fixed_top);
+    pl.end_step(x);
+  }
+  // ---- bookkeeping
+  auto& S = c->stats;
+  const int n_re = __builtin_popcountll(plan);
+  double uf, rf;
+  flops(f, B, L, n_re, &uf, &rf);
+  S.steps++;
+  S.sheltered_steps = c->planner->sheltered_steps_seen();
+  S.cache_hits = c->planner->hits; S.cache_misses = c->planner->misses;
+  S.cache_entries = c->planner->cache_entries();
+  S.planner_ns_last = ns; S.planner_ns_total += ns;
+  S.recomputed_layers_last = n_re; S.recomputed_layers_total += n_re;
+  S.useful_flops_last = uf; S.recompute_flops_last = rf;
+  S.useful_flops_total += uf; S.recompute_flops_total += rf;
+  S.peak_bytes_last = pk; S.peak_bytes_max = std::max(S.peak_bytes_max, pk);
+  S.predicted_peak_last = (uint64_t)predicted;
+  if (loss) *loss = lv;
+  if (peak) *peak = pk;
+  if (plan_id) *plan_id = plan;
+  return MIMOSE_OK;
+}
+
+}  // namespace
+
+// ====================================================================== C ABI
+extern "C" {
+
+int mimose_init(const mimose_model_cfg* cfg, uint64_t mem_budget_bytes, void* arena_dev, uint64_t arena_bytes,
+                void* hip_stream, mimose_ctx** out) {
+  if (!cfg || !out) return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "cfg and out must be given");
+  *out = nullptr;
+  mimose_model_cfg f = *cfg;
+  if (f.n_layers < 0 || f.n_layers > 64 || f.hidden < 1 || f.n_heads < 1 || f.ffn < 1 || f.vocab < 1 || f.max_seq < 1)
+    return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "bad model dimensions");
+  if (f.hidden % f.n_heads) return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "hidden must be a multiple of n_heads");
+  const int d = f.hidden / f.n_heads;
+  if (d != 32 && d != 64 && d != 128) return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "head size must be 32, 64 or 128");
+  if (f.hidden > mk::kMaxRowWidth) return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "hidden larger than 1024 is not supported");
+  if (f.dtype != 0 && f.dtype != 1) return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "dtype must be 0 (fp32) or 1 (bf16)");
+  if (f.dtype == 1 && (f.hidden % 8 || f.ffn % 8)) return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "bf16 needs hidden and ffn multiples of 8");
+  if (f.ln_eps <= 0.f) f.ln_eps = 1e-5f;
+  if (f.sheltered_steps <= 0) f.sheltered_steps = 10;
+  if (f.bucket_tol_permille <= 0) f.bucket_tol_permille = 100;
+  if (f.poly_order <= 0) f.poly_order = 2;
+  if (f.size_quantum <= 0) f.size_quantum = 1;
+  if (f.guard_bytes == 0) f.guard_bytes = 4096;
+  if (arena_dev && mem_budget_bytes && arena_bytes < mem_budget_bytes)
+    return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "arena smaller than the budget");
+  if (arena_dev && (((uintptr_t)arena_dev) & 255)) return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "arena must be 256-byte aligned");
+
+  std::unique_ptr<mimose_ctx> c(new mimose_ctx());
+  c->cfg = f;
+  c->budget = mem_budget_bytes;
+  c->has_device = arena_dev != nullptr;
+  c->stream = (hipStream_t)hip_stream;
+  std::memset(&c->stats, 0, sizeof c->stats);
+  const uint64_t cap = mem_budget_bytes ? mem_budget_bytes : (arena_dev ? arena_bytes : ~(uint64_t)0 >> 1);
+  c->arena.init((char*)arena_dev, cap);
+  build_params(c.get());
+  try {
+    for (auto& p : c->params) p.w = c->arena.alloc((uint64_t)p.n * c->elt());
+    for (auto& p : c->params) p.g = (float*)c->arena.alloc((uint64_t)p.n * 4);
+  } catch (const OomError&) {
+    return fail(nullptr, MIMOSE_ERR_OOM_BUDGET, "parameters and gradients do not fit in the budget");
+  }
+  c->fixed_top = c->arena.top();
+  c->stats.fixed_bytes = c->fixed_top;
+  c->stats.budget_bytes = mem_budget_bytes;
+  c->planner.reset(new mimose::Planner(f.n_layers, mem_budget_bytes, f.sheltered_steps, f.bucket_tol_permille,
+                                       f.poly_order, f.size_quantum, f.reserve_bytes, f.guard_bytes));
+  if (c->has_device) {
+    if (hipHostMalloc((void**)&c->loss_host, 256, hipHostMallocDefault) != hipSuccess)
+      return fail(nullptr, MIMOSE_ERR_HIP, "hipHostMalloc failed");
+    // gradients start at zero so that a read before the first step is defined
+    mk::fill_zero(c->params.front().g, (int64_t)((char*)c->arena.alloc(0) - (char*)c->params.front().g), c->stream);
+    if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(nullptr, MIMOSE_ERR_HIP, "device initialisation failed");
+  }
+  *out = c.release();
+  return MIMOSE_OK;
+}
+
+int mimose_param_count(mimose_ctx* c, int32_t* n) {
+  if (!c || !n) return MIMOSE_ERR_INVALID_ARG;
+  *n = (int32_t)c->params.size();
+  return MIMOSE_OK;
+}
+
+int mimose_param_info(mimose_ctx* c, int32_t i, const char** name, int64_t shape[4], int32_t* ndim) {
+  if (!c || i < 0 || i >= (int)c->params.size()) return fail(c, MIMOSE_ERR_INVALID_ARG, "parameter index out of range");
+  const Param& p = c->params[i];
+  if (name) *name = p.name.c_str();
+  if (shape) for (int k = 0; k < 4; ++k) shape[k] = p.shape[k];
+  if (ndim) *ndim = p.ndim;
+  return MIMOSE_OK;
+}
+
+int mimose_load_param(mimose_ctx* c, int32_t i, const float* host, uint64_t n) {
+  if (!c || i < 0 || i >= (int)c->params.size() || !host) return fail(c, MIMOSE_ERR_INVALID_ARG, "bad parameter index or pointer");
+  if (!c->has_device) return fail(c, MIMOSE_ERR_NOT_READY, "host-only context");
+  Param& p = c->params[i];
+  if ((int64_t)n != p.n) return fail(c, MIMOSE_ERR_INVALID_ARG, "element count does not match " + p.name);
+  // stage through the gradient buffer of the same parameter (fp32, same element count)
+  if (hipMemcpyAsync(p.g, host, n * 4, hipMemcpyHostToDevice, c->stream) != hipSuccess)
+    return fail(c, MIMOSE_ERR_HIP, "copy of " + p.name + " failed");
+  mk::convert_from_f32(c->cfg.dtype, p.g, p.w, p.n, c->stream);
+  mk::fill_zero(p.g, p.n * 4, c->stream);
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(c, MIMOSE_ERR_HIP, "load of " + p.name + " failed");
+  return MIMOSE_OK;
+}
+
+int mimose_train_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, int32_t B, int32_t L,
+                      float* loss, uint64_t* peak, uint64_t* plan_id) {
+  if (!c) return MIMOSE_ERR_INVALID_ARG;
+  return do_step(c, tokens, labels, B, L, false, loss, peak, plan_id);
+}
+
+int mimose_dry_step(mimose_ctx* c, int32_t B, int32_t L, uint64_t* peak, uint64_t* plan_id) {
+  if (!c) return MIMOSE_ERR_INVALID_ARG;
+  return do_step(c, nullptr, nullptr, B, L, true, nullptr, peak, plan_id);
+}
+
+int mimose_get_grad(mimose_ctx* c, int32_t i, float* host, uint64_t n) {
+  if (!c || i < 0 || i >= (int)c->params.size() || !host) return fail(c, MIMOSE_ERR_INVALID_ARG, "bad parameter index or pointer");
+  if (!c->has_device) return fail(c, MIMOSE_ERR_NOT_READY, "host-only context");
+  const Param& p = c->params[i];
+  if ((int64_t)n != p.n) return fail(c, MIMOSE_ERR_INVALID_ARG, "element count does not match " + p.name);
+  if (hipMemcpyAsync(host, p.g, n * 4, hipMemcpyDeviceToHost, c->stream) != hipSuccess ||
+      hipStreamSynchronize(c->stream) != hipSuccess)
+    return fail(c, MIMOSE_ERR_HIP, "copy of gradient " + p.name + " failed");
+  return MIMOSE_OK;
+}
+
+int mimose_force_plan(mimose_ctx* c, int64_t plan) {
+  if (!c || plan < -1) return fail(c, MIMOSE_ERR_INVALID_ARG, "plan must be -1 or a bitmask");
+  c->forced_plan = plan;
+  return MIMOSE_OK;
+}
+
+int mimose_planner_feed(mimose_ctx* c, int32_t B, int32_t L, int32_t quantity, int32_t layer, uint64_t bytes) {
+  if (!c || B < 1 || L < 1 || quantity < 0 || quantity > 5) return fail(c, MIMOSE_ERR_INVALID_ARG, "bad sample");
+  if (quantity <= 2 && (layer < 0 || layer >= c->cfg.n_layers)) return fail(c, MIMOSE_ERR_INVALID_ARG, "layer out of range");
+  c->planner->feed((int64_t)B * L, quantity, layer, bytes);
+  return MIMOSE_OK;
+}
+
+int mimose_planner_end_step(mimose_ctx* c, int32_t B, int32_t L) {
+  if (!c || B < 1 || L < 1) return fail(c, MIMOSE_ERR_INVALID_ARG, "bad size");
+  c->planner->end_step((int64_t)B * L);
+  return MIMOSE_OK;
+}
+
+int mimose_planner_query(mimose_ctx* c, int32_t B, int32_t L, uint64_t* plan, uint64_t* predicted_peak) {
+  if (!c || B < 1 || L < 1) return fail(c, MIMOSE_ERR_INVALID_ARG, "bad size");
+  if (c->planner->sheltered()) return fail(c, MIMOSE_ERR_NOT_READY, "still in the sheltered phase");
+  mimose::PlanOut po;
+  const int rc = c->planner->query((int64_t)B * L, &po, nullptr);
+  if (rc == -1) return fail(c, MIMOSE_ERR_NOT_READY, "estimator could not be fitted");
+  if (plan) *plan = po.plan;
+  if (predicted_peak) *predicted_peak = (uint64_t)po.predicted_peak;
+  if (rc == -2) return fail(c, MIMOSE_ERR_BUDGET_INFEASIBLE, "no plan fits the budget");
+  return MIMOSE_OK;
+}
+
+int mimose_get_step_memory(mimose_ctx* c, uint64_t* fixed, uint64_t* embed, uint64_t* head, uint64_t* kept,
+                           uint64_t* boundary, uint64_t* bwd) {
+  if (!c) return MIMOSE_ERR_INVALID_ARG;
+  if (c->last_a.size() != (size_t)c->cfg.n_layers) return fail(c, MIMOSE_ERR_NOT_READY, "no step has completed yet");
+  if (fixed) *fixed = c->fixed_top;
+  if (embed) *embed = c->last_e;
+  if (head) *head = c->last_g;
+  for (int l = 0; l < c->cfg.n_layers; ++l) {
+    if (kept) kept[l] = c->last_a[l];
+    if (boundary) boundary[l] = c->last_b[l];
+    if (bwd) bwd[l] = c->last_w[l];
+  }
+  return MIMOSE_OK;
+}
+
+int mimose_get_stats(mimose_ctx* c, mimose_stats* out) {
+  if (!c || !out) return MIMOSE_ERR_INVALID_ARG;
+  c->stats.cache_hits = c->planner->hits;
+  c->stats.cache_misses = c->planner->misses;
+  c->stats.cache_entries = c->planner->cache_entries();
+  *out = c->stats;
+  return MIMOSE_OK;
+}
+
+const char* mimose_last_error(mimose_ctx* c) { return c ? c->err.c_str() : g_init_error.c_str(); }
+
+void mimose_destroy(mimose_ctx* c) {
+  if (!c) return;
+  if (c->has_device) {
+    (void)hipStreamSynchronize(c->stream);
+    if (c->stage) (void)hipHostFree(c->stage);
+    if (c->loss_host) (void)hipHostFree(c->loss_host);
+  }
+  delete c;
+}
+
+}  // extern "C"

@@ -1,0 +1,420 @@
+// Row-wise, HBM-bound kernels: LayerNorm forward/backward, GELU backward, softmax
+// cross-entropy, embedding forward/backward, dtype conversion.
+//
+// One 64-lane wave owns one row; lane i holds columns i, i+64, ... in registers, so a
+// wave load touches one contiguous run of the row and reductions are wave shuffles.
+// Column reductions over rows (LayerNorm's dgamma/dbeta) are two-stage with a row ->
+// chunk mapping fixed by the shape, so they are reproducible bit for bit (no atomics).
+#include "device_common.h"
+#include "kernels.h"
+
+namespace mk {
+
+constexpr int kRowsPerChunk = 16;   // rows summed by one block of a two-stage column reduction
+constexpr int kMaxNPL = 16;         // columns per lane: supports rows up to 1024 wide
+
+// ---------------------------------------------------------------- LayerNorm forward
+template <typename T, int NPL>
+__device__ __forceinline__ void row_stats(const float (&v)[NPL], int H, int lane, float& mean, float& rstd,
+                                          float eps) {
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NPL; ++i) if (lane + 64 * i < H) s += v[i];
+  mean = wave_sum(s) / (float)H;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < NPL; ++i) if (lane + 64 * i < H) { float d = v[i] - mean; q += d * d; }
+  rstd = rsqrtf(wave_sum(q) / (float)H + eps);
+}
+
+template <typename T, int NPL>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
+                                                     const T* __restrict__ beta, T* __restrict__ y, int Trows,
+                                                     int H, float eps) {
+  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= Trows) return;
+  const T* xr = x + (int64_t)row * H;
+  float v[NPL];
+#pragma unroll
+  for (int i = 0; i < NPL; ++i) { int c = lane + 64 * i; v[i] = c < H ? ld<T>(xr + c) : 0.f; }
+  float mean, rstd;
+  row_stats<T, NPL>(v, H, lane, mean, rstd, eps);
+  T* yr = y + (int64_t)row * H;
+#pragma unroll
+  for (int i = 0; i < NPL; ++i) {
+    int c = lane + 64 * i;
+    if (c < H) st<T>(yr + c, (v[i] - mean) * rstd * ld<T>(gamma + c) + ld<T>(beta + c));
+  }
+}
+
+// ---------------------------------------------------------------- LayerNorm backward
+// Block = 4 waves = kRowsPerChunk rows.  Statistics are recomputed from x; `add` (optional) is a
+// residual-path gradient added to the result.  dx may alias dy; add must not alias dx.  Each wave keeps
+// per-column sums of dy*xhat and dy over its rows; the four waves are combined through LDS
+// in wave order and written as one partial row.
+template <typename T, int NPL>
+__global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                     const T* __restrict__ gamma, T* __restrict__ dx,
+                                                     const T* __restrict__ add, float* __restrict__ partial,
+                                                     int Trows, int H, float eps) {
+  __shared__ float red[4][2][64 * NPL];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float g[NPL], sg[NPL], sb[NPL];
+#pragma unroll
+  for (int i = 0; i < NPL; ++i) {
+    int c = lane + 64 * i;
+    g[i] = c < H ? ld<T>(gamma + c) : 0.f;
+    sg[i] = 0.f; sb[i] = 0.f;
+  }
+  for (int rr = 0; rr < kRowsPerChunk / 4; ++rr) {
+    int row = blockIdx.x * kRowsPerChunk + rr * 4 + wave;
+    if (row >= Trows) break;
+    const T* xr = x + (int64_t)row * H;
+    const T* dr = dy + (int64_t)row * H;
+    float v[NPL], d[NPL];
+#pragma unroll
+    for (int i = 0; i < NPL; ++i) {
+      int c = lane + 64 * i;
+      v[i] = c < H ? ld<T>(xr + c) : 0.f;
+      d[i] = c < H ? ld<T>(dr + c) : 0.f;
+    }
+    float mean, rstd;
+    row_stats<T, NPL>(v, H, lane, mean, rstd, eps);
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NPL; ++i) {
+      float xh = (v[i] - mean) * rstd;
+      v[i] = xh;
+      sg[i] += d[i] * xh;
+      sb[i] += d[i];
+      float dxh = d[i] * g[i];
+      d[i] = dxh;
+      s1 += dxh;
+      s2 += dxh * xh;
+    }
+    s1 = wave_sum(s1) / (float)H;
+    s2 = wave_sum(s2) / (float)H;
+    T* or_ = dx + (int64_t)row * H;
+    const T* ar = add ? add + (int64_t)row * H : nullptr;
+#pragma unroll
+    for (int i = 0; i < NPL; ++i) {
+      int c = lane + 64 * i;
+      if (c < H) st<T>(or_ + c, rstd * (d[i] - s1 - v[i] * s2) + (ar ? ld<T>(ar + c) : 0.f));
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NPL; ++i) { red[wave][0][lane + 64 * i] = sg[i]; red[wave][1][lane + 64 * i] = sb[i]; }
+  __syncthreads();
+  float* prow = partial + (int64_t)blockIdx.x * 2 * H;
+  for (int c = threadIdx.x; c < 2 * H; c += 256) {
+    int which = c / H, col = c - which * H;
+    float s = red[0][which][col];
+    s += red[1][which][col];
+    s += red[2][which][col];
+    s += red[3][which][col];
+    prow[c] = s;
+  }
+}
+
+// out[c] = sum over partial rows, c in [0, ncols): 16 row groups x 16 columns per block,
+// each group adds its rows in order, groups are combined in order.
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int P,
+                                                              int ncols, float* __restrict__ out0,
+                                                              float* __restrict__ out1, int split) {
+  __shared__ float red[16][17];
+  const int cg = threadIdx.x & 15, rg = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + cg;
+  float s = 0.f;
+  if (c < ncols)
+    for (int r = rg; r < P; r += 16) s += partial[(int64_t)r * ncols + c];
+  red[rg][cg] = s;
+  __syncthreads();
+  if (rg == 0 && c < ncols) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) t += red[i][cg];
+    if (c < split) out0[c] = t; else out1[c - split] = t;
+  }
+}
+
+// ---------------------------------------------------------------- GELU backward (in place)
+template <typename T>
+__global__ __launch_bounds__(256) void gelu_bwd_scalar_kernel(T* __restrict__ d, const T* __restrict__ pre,
+                                                              int64_t n, int tanh_form) {
+  int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i >= n) return;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    if (i + e < n) {
+      float x = ld<T>(pre + i + e);
+      float gp = tanh_form ? gelu_tanh_grad(x) : gelu_erf_grad(x);
+      st<T>(d + i + e, ld<T>(d + i + e) * gp);
+    }
+  }
+}
+__global__ __launch_bounds__(256) void gelu_bwd_bf16_kernel(bf16_t* __restrict__ d,
+                                                            const bf16_t* __restrict__ pre, int64_t n,
+                                                            int tanh_form) {
+  int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i >= n) return;
+  if (i + 8 <= n) {
+    uint4 dv = *(const uint4*)(d + i), pv = *(const uint4*)(pre + i);
+    bf16_t* dp = (bf16_t*)&dv;
+    const bf16_t* pp = (const bf16_t*)&pv;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float x = bf16_to_f32(pp[e]);
+      float gp = tanh_form ? gelu_tanh_grad(x) : gelu_erf_grad(x);
+      dp[e] = f32_to_bf16(bf16_to_f32(dp[e]) * gp);
+    }
+    *(uint4*)(d + i) = dv;
+  } else {
+    for (int e = 0; i + e < n; ++e) {
+      float x = bf16_to_f32(pre[i + e]);
+      float gp = tanh_form ? gelu_tanh_grad(x) : gelu_erf_grad(x);
+      d[i + e] = f32_to_bf16(bf16_to_f32(d[i + e]) * gp);
+    }
+  }
+}
+
+// ---------------------------------------------------------------- softmax cross-entropy
+// One block per row.  Pass 1: running (max, sum of exp) per thread, merged in a fixed tree.
+// Pass 2: the row is overwritten with (softmax - onehot)/n_valid, zero for unscored rows and
+// for the padding columns [V, ld).
+template <typename T>
+__global__ __launch_bounds__(256) void xent_kernel(T* __restrict__ logits, int64_t ldl,
+                                                   const int32_t* __restrict__ labels,
+                                                   float* __restrict__ row_loss, int V, float inv_n) {
+  __shared__ float sm[4], ss[4];
+  const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  T* lr = logits + (int64_t)row * ldl;
+  const int label = labels[row];
+  float m = -INFINITY, s = 0.f;
+  for (int c = tid; c < V; c += 256) {
+    float v = ld<T>(lr + c);
+    if (v > m) { s = s * __expf(m - v) + 1.f; m = v; } else { s += __expf(v - m); }
+  }
+  float wm = wave_max(m);
+  s = wave_sum(m == -INFINITY ? 0.f : s * __expf(m - wm));   // threads or waves past a short row hold nothing
+  if (lane == 0) { sm[wave] = wm; ss[wave] = s; }
+  __syncthreads();
+  float bm = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
+  float bs = 0.f;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) bs += sm[w] == -INFINITY ? 0.f : ss[w] * __expf(sm[w] - bm);
+  const float lse = bm + __logf(bs);
+  if (tid == 0) row_loss[row] = label >= 0 ? lse - ld<T>(lr + label) : 0.f;
+  __syncthreads();   // the label's logit is read before the row is overwritten
+  const float scale = label >= 0 ? inv_n : 0.f;
+  for (int c = tid; c < ldl; c += 256) {
+    float g = 0.f;
+    if (c < V) g = (__expf(ld<T>(lr + c) - lse) - (c == label ? 1.f : 0.f)) * scale;
+    st<T>(lr + c, g);
+  }
+}
+
+__global__ __launch_bounds__(256) void loss_reduce_kernel(const float* __restrict__ row_loss, int n, float inv_n,
+                                                          float* __restrict__ loss) {
+  __shared__ float red[256];
+  float s = 0.f;
+  for (int i = threadIdx.x; i < n; i += 256) s += row_loss[i];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *loss = red[0] * inv_n;
+}
+
+// ---------------------------------------------------------------- embedding
+template <typename T, int NPL>
+__global__ __launch_bounds__(256) void embed_fwd_kernel(const int32_t* __restrict__ ids, const T* __restrict__ tok,
+                                                        const T* __restrict__ pos, const T* __restrict__ gamma,
+                                                        const T* __restrict__ beta, T* __restrict__ sum_out,
+                                                        T* __restrict__ y, int Trows, int L, int H, float eps,
+                                                        int has_ln) {
+  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= Trows) return;
+  const T* tr = tok + (int64_t)ids[row] * H;
+  const T* pr = pos + (int64_t)(row % L) * H;
+  float v[NPL];
+#pragma unroll
+  for (int i = 0; i < NPL; ++i) {
+    int c = lane + 64 * i;
+    // the sum is formed in the storage type so LayerNorm sees exactly what is saved
+    v[i] = c < H ? rnd<T>(ld<T>(tr + c) + ld<T>(pr + c)) : 0.f;
+  }
+  if (sum_out) {
+    T* sr = sum_out + (int64_t)row * H;
+#pragma unroll
+    for (int i = 0; i < NPL; ++i) { int c = lane + 64 * i; if (c < H) st<T>(sr + c, v[i]); }
+  }
+  T* yr = y + (int64_t)row * H;
+  if (!has_ln) {
+#pragma unroll
+    for (int i = 0; i < NPL; ++i) { int c = lane + 64 * i; if (c < H) st<T>(yr + c, v[i]); }
+    return;
+  }
+  float mean, rstd;
+  row_stats<T, NPL>(v, H, lane, mean, rstd, eps);
+#pragma unroll
+  for (int i = 0; i < NPL; ++i) {
+    int c = lane + 64 * i;
+    if (c < H) st<T>(yr + c, (v[i] - mean) * rstd * ld<T>(gamma + c) + ld<T>(beta + c));
+  }
+}
+
+// dpos[p][c] = sum over samples b (in order) of d[b*L+p][c]; rows p >= L are cleared.
+template <typename T>
+__global__ __launch_bounds__(256) void embed_bwd_pos_kernel(const T* __restrict__ d, float* __restrict__ dpos,
+                                                            int B, int L, int H, int max_seq) {
+  int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)max_seq * H) return;
+  int p = (int)(idx / H), c = (int)(idx - (int64_t)p * H);
+  float s = 0.f;
+  if (p < L)
+    for (int b = 0; b < B; ++b) s += ld<T>(d + ((int64_t)b * L + p) * H + c);
+  dpos[idx] = s;
+}
+
+// One wave per distinct token id: rows of d at that id's positions (ascending) are summed
+// and added onto the id's gradient row.
+template <typename T>
+__global__ __launch_bounds__(256) void embed_bwd_tok_kernel(const T* __restrict__ d, const int32_t* __restrict__ ids,
+                                                            const int32_t* __restrict__ order,
+                                                            const int32_t* __restrict__ seg, int n_seg,
+                                                            float* __restrict__ dtok, int H) {
+  const int lane = threadIdx.x & 63, sidx = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (sidx >= n_seg) return;
+  const int beg = seg[sidx], end = seg[sidx + 1];
+  const int id = ids[order[beg]];
+  float* out = dtok + (int64_t)id * H;
+  for (int c = lane; c < H; c += 64) {
+    float s = 0.f;
+    for (int k = beg; k < end; ++k) s += ld<T>(d + (int64_t)order[k] * H + c);
+    out[c] += s;
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void convert_kernel(const float* __restrict__ src, T* __restrict__ dst, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) st<T>(dst + i, src[i]);
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* __restrict__ p, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
+// ---------------------------------------------------------------- launchers
+#define DISPATCH_NPL(H, M)                      \
+  do {                                          \
+    int npl_ = ((H) + 63) / 64;                 \
+    if (npl_ <= 1) { M(1); }                    \
+    else if (npl_ <= 2) { M(2); }               \
+    else if (npl_ <= 4) { M(4); }               \
+    else if (npl_ <= 8) { M(8); }               \
+    else if (npl_ <= 12) { M(12); }             \
+    else { M(16); }                             \
+  } while (0)
+
+template <typename T>
+static void ln_fwd_t(const void* x, const void* g, const void* b, void* y, int T_, int H, float eps,
+                     hipStream_t st) {
+  dim3 grid((T_ + 3) / 4);
+#define M_(NPL) hipLaunchKernelGGL((ln_fwd_kernel<T, NPL>), grid, dim3(256), 0, st, (const T*)x, (const T*)g, \
+                                   (const T*)b, (T*)y, T_, H, eps)
+  DISPATCH_NPL(H, M_);
+#undef M_
+}
+void layernorm_fwd(int dtype, const void* x, const void* gamma, const void* beta, void* y, int T_, int H,
+                   float eps, hipStream_t st) {
+  if (T_ <= 0) return;
+  if (dtype == BF16) ln_fwd_t<bf16_t>(x, gamma, beta, y, T_, H, eps, st);
+  else ln_fwd_t<float>(x, gamma, beta, y, T_, H, eps, st);
+}
+
+template <typename T>
+static void ln_bwd_t(const void* dy, const void* x, const void* g, void* dx, const void* add, float* partial,
+                     int T_, int H, float eps, hipStream_t st) {
+  dim3 grid((T_ + kRowsPerChunk - 1) / kRowsPerChunk);
+#define M_(NPL) hipLaunchKernelGGL((ln_bwd_kernel<T, NPL>), grid, dim3(256), 0, st, (const T*)dy, (const T*)x, \
+                                   (const T*)g, (T*)dx, (const T*)add, partial, T_, H, eps)
+  DISPATCH_NPL(H, M_);
+#undef M_
+}
+void layernorm_bwd(int dtype, const void* dy, const void* x, const void* gamma, void* dx, const void* add,
+                   float* dgamma, float* dbeta, float* partial, int T_, int H, float eps, hipStream_t st) {
+  if (T_ <= 0) return;
+  if (dtype == BF16) ln_bwd_t<bf16_t>(dy, x, gamma, dx, add, partial, T_, H, eps, st);
+  else ln_bwd_t<float>(dy, x, gamma, dx, add, partial, T_, H, eps, st);
+  int P = (T_ + kRowsPerChunk - 1) / kRowsPerChunk;
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((2 * H + 15) / 16), dim3(256), 0, st, partial, P, 2 * H,
+                     dgamma, dbeta, H);
+}
+int partial_rows(int T_) { return (T_ + kRowsPerChunk - 1) / kRowsPerChunk; }
+
+void gelu_bwd(int dtype, void* d, const void* pre, int64_t n, int tanh_form, hipStream_t st) {
+  if (n <= 0) return;
+  dim3 grid((unsigned)((n + 2047) / 2048));
+  if (dtype == BF16) hipLaunchKernelGGL(gelu_bwd_bf16_kernel, grid, dim3(256), 0, st, (bf16_t*)d, (const bf16_t*)pre, n, tanh_form);
+  else hipLaunchKernelGGL(gelu_bwd_scalar_kernel<float>, grid, dim3(256), 0, st, (float*)d, (const float*)pre, n, tanh_form);
+}
+
+void softmax_xent(int dtype, void* logits, int64_t ldl, const int32_t* labels, float* row_loss, float* loss,
+                  int T_, int V, int n_valid, hipStream_t st) {
+  if (T_ <= 0) return;
+  float inv_n = 1.0f / (float)(n_valid > 0 ? n_valid : 1);
+  if (dtype == BF16) hipLaunchKernelGGL(xent_kernel<bf16_t>, dim3(T_), dim3(256), 0, st, (bf16_t*)logits, ldl, labels, row_loss, V, inv_n);
+  else hipLaunchKernelGGL(xent_kernel<float>, dim3(T_), dim3(256), 0, st, (float*)logits, ldl, labels, row_loss, V, inv_n);
+  hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(256), 0, st, row_loss, T_, inv_n, loss);
+}
+
+template <typename T>
+static void embed_fwd_t(const int32_t* ids, const void* tok, const void* pos, const void* g, const void* b,
+                        void* sum_out, void* y, int B, int L, int H, float eps, int has_ln, hipStream_t st) {
+  int T_ = B * L;
+  dim3 grid((T_ + 3) / 4);
+#define M_(NPL) hipLaunchKernelGGL((embed_fwd_kernel<T, NPL>), grid, dim3(256), 0, st, ids, (const T*)tok,     \
+                                   (const T*)pos, (const T*)g, (const T*)b, (T*)sum_out, (T*)y, T_, L, H, eps, \
+                                   has_ln)
+  DISPATCH_NPL(H, M_);
+#undef M_
+}
+void embed_fwd(int dtype, const int32_t* ids, const void* tok, const void* pos, const void* gamma,
+               const void* beta, void* sum_out, void* y, int B, int L, int H, float eps, int has_ln,
+               hipStream_t st) {
+  if (B * L <= 0) return;
+  if (dtype == BF16) embed_fwd_t<bf16_t>(ids, tok, pos, gamma, beta, sum_out, y, B, L, H, eps, has_ln, st);
+  else embed_fwd_t<float>(ids, tok, pos, gamma, beta, sum_out, y, B, L, H, eps, has_ln, st);
+}
+
+void embed_bwd(int dtype, const void* d, const int32_t* ids, const int32_t* order, const int32_t* seg,
+               int n_seg, float* dtok, float* dpos, int B, int L, int H, int max_seq, hipStream_t st) {
+  if (B * L <= 0) return;
+  dim3 gp((unsigned)(((int64_t)max_seq * H + 255) / 256)), gt((n_seg + 3) / 4);
+  if (dtype == BF16) {
+    hipLaunchKernelGGL(embed_bwd_pos_kernel<bf16_t>, gp, dim3(256), 0, st, (const bf16_t*)d, dpos, B, L, H, max_seq);
+    hipLaunchKernelGGL(embed_bwd_tok_kernel<bf16_t>, gt, dim3(256), 0, st, (const bf16_t*)d, ids, order, seg, n_seg, dtok, H);
+  } else {
+    hipLaunchKernelGGL(embed_bwd_pos_kernel<float>, gp, dim3(256), 0, st, (const float*)d, dpos, B, L, H, max_seq);
+    hipLaunchKernelGGL(embed_bwd_tok_kernel<float>, gt, dim3(256), 0, st, (const float*)d, ids, order, seg, n_seg, dtok, H);
+  }
+}
+
+void convert_from_f32(int dtype, const float* src, void* dst, int64_t n, hipStream_t st) {
+  if (n <= 0) return;
+  dim3 grid((unsigned)((n + 255) / 256));
+  if (dtype == BF16) hipLaunchKernelGGL(convert_kernel<bf16_t>, grid, dim3(256), 0, st, src, (bf16_t*)dst, n);
+  else hipLaunchKernelGGL(convert_kernel<float>, grid, dim3(256), 0, st, src, (float*)dst, n);
+}
+
+void fill_zero(void* p, int64_t bytes, hipStream_t st) {
+  int64_t n = bytes / 4;
+  if (n <= 0) return;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (uint32_t*)p, n);
+}
+
+}  // namespace mk
