@@ -87,7 +87,7 @@ typedef struct {
  *                    mimose_train_step returns MIMOSE_ERR_NOT_READY.
  *   arena_bytes      its size; must be >= mem_budget_bytes when both are non-zero
  *   hip_stream       hipStream_t (as void*) all work is enqueued on; NULL = default
- * Errors: INVALID_ARG (bad shapes, hidden % n_heads, head_dim not 32/64/128,
+ * Errors: INVALID_ARG (bad shapes, hidden % n_heads, head_dim not 32/64,
  * n_layers > 64), OOM_BUDGET (parameters and gradients do not fit).
  */
 int mimose_init(const mimose_model_cfg* cfg, uint64_t mem_budget_bytes, void* arena_dev,
@@ -177,7 +177,7 @@ int32_t mimose_op_partial_rows(int32_t T);
 int mimose_op_gelu_bwd(int32_t dtype, void* d, const void* pre, int64_t n, int32_t tanh_form,
                        void* stream);
 /* qkv [B*L, 3*H] (q | k | v, heads contiguous inside each) -> ctx [B*L, H], lse fp32 [B, h, L].
- * head_dim must be 32, 64 or 128. */
+ * head_dim must be 32 or 64. */
 int mimose_op_attention_fwd(int32_t dtype, const void* qkv, void* ctx, float* lse, int32_t B,
                             int32_t L, int32_t n_heads, int32_t head_dim, int32_t causal,
                             void* stream);

@@ -1,6 +1,6 @@
 // Fused attention, forward and backward, without materialising the L x L matrices.
 //
-// Wave-per-row kernels in fp32 arithmetic for any head size up to 128.  One wave owns one
+// Wave-per-row kernels in fp32 arithmetic for head sizes 32 and 64.  One wave owns one
 // query row (forward, dQ) or one key row (dK/dV): its 64 lanes first each take one
 // opposite-side row to form a score, then each take one head-dimension column to
 // accumulate the output, with the scores broadcast lane by lane.  Every output element is
@@ -202,9 +202,9 @@ static void bwd_t(const void* qkv, const void* ctx, const void* dctx, const floa
 
 #define DISPATCH_TD(CALL_F32, CALL_BF16)                         \
   if (dtype == BF16) {                                           \
-    if (d == 32) { CALL_BF16(32); } else if (d == 64) { CALL_BF16(64); } else { CALL_BF16(128); } \
+    if (d == 32) { CALL_BF16(32); } else { CALL_BF16(64); } \
   } else {                                                       \
-    if (d == 32) { CALL_F32(32); } else if (d == 64) { CALL_F32(64); } else { CALL_F32(128); }    \
+    if (d == 32) { CALL_F32(32); } else { CALL_F32(64); } \
   }
 
 void attention_fwd(int dtype, const void* qkv, void* ctx, float* lse, int B, int L, int nh, int d, int causal,

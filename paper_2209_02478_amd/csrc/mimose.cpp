@@ -571,7 +571,7 @@ int mimose_init(const mimose_model_cfg* cfg, uint64_t mem_budget_bytes, void* ar
     return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "bad model dimensions");
   if (f.hidden % f.n_heads) return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "hidden must be a multiple of n_heads");
   const int d = f.hidden / f.n_heads;
-  if (d != 32 && d != 64 && d != 128) return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "head size must be 32, 64 or 128");
+  if (d != 32 && d != 64) return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "head size must be 32 or 64");
   if (f.hidden > mk::kMaxRowWidth) return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "hidden larger than 1024 is not supported");
   if (f.dtype != 0 && f.dtype != 1) return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "dtype must be 0 (fp32) or 1 (bf16)");
   if (f.dtype == 1 && (f.hidden % 8 || f.ffn % 8)) return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "bf16 needs hidden and ffn multiples of 8");

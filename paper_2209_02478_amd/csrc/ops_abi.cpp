@@ -7,7 +7,7 @@
 namespace {
 inline bool bad_dtype(int d) { return d != 0 && d != 1; }
 inline int done() { return hipGetLastError() == hipSuccess ? MIMOSE_OK : MIMOSE_ERR_HIP; }
-inline bool bad_head(int d) { return d != 32 && d != 64 && d != 128; }
+inline bool bad_head(int d) { return d != 32 && d != 64; }
 }  // namespace
 
 extern "C" {

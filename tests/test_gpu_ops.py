@@ -1,0 +1,257 @@
+"""Kernel-level parity: each HIP kernel against the oracle's matching operation, element by
+element, on shapes that span several tiles and end in ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2209_02478_amd as mi
+from oracle import model as om
+from gpu_util import DEV, dev, host, quant, rel_l2, sync
+
+pytestmark = pytest.mark.gpu
+
+# elementwise bound of one rounding to the storage type (bf16: 8 significand bits)
+EPS = {0: 1e-5, 1: 2.0 ** -8}
+
+
+def close(got, ref, dtype, scale=None, k=1.0):
+    ref = np.asarray(ref, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    scale = np.abs(ref).max() if scale is None else scale
+    err = np.abs(got - ref)
+    bound = k * EPS[dtype] * (np.abs(ref) + 0.1 * scale) + 1e-30
+    assert np.all(err <= bound), f"max err {err.max():.3e} vs bound {bound.flat[err.argmax()]:.3e} at {np.unravel_index(err.argmax(), err.shape)}"
+
+
+# ---------------------------------------------------------------- GEMM
+GEMM_SHAPES = [(130, 70, 40), (257, 129, 96), (64, 64, 64), (1, 8, 8), (300, 200, 136), (128, 256, 520)]
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("a_k,b_k", [(1, 1), (1, 0), (0, 0), (0, 1)])
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_layouts(dtype, a_k, b_k, M, N, K):
+    rng = np.random.default_rng(M * 7 + N * 3 + K + a_k * 2 + b_k)
+    pad = 8
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    B = rng.standard_normal((N, K)).astype(np.float32)
+    ref = quant(A, dtype) @ quant(B, dtype).T
+    # device layouts with a padded leading dimension
+    def lay(X, kmajor):
+        R, Kk = X.shape
+        up = lambda v: (v + 7) // 8 * 8 + pad                  # bf16 needs leading dimensions in multiples of 8
+        if kmajor:
+            buf = np.zeros((R, up(Kk)), np.float32); buf[:, :Kk] = X
+            return buf, up(Kk)
+        buf = np.zeros((Kk, up(R)), np.float32); buf[:, :R] = X.T
+        return buf, up(R)
+    Ab, lda = lay(A, a_k)
+    Bb, ldb = lay(B, b_k)
+    dA, dB = dev(Ab, dtype), dev(Bb, dtype)
+    ldc = N + 8
+    C = torch.full((M, ldc), 7.0, dtype=dA.dtype, device=DEV)
+    mi.mimose_op_gemm(dtype, dA, lda, a_k, dB, ldb, b_k, C, ldc, 0, M, N, K)
+    sync()
+    got = host(C)
+    assert np.all(got[:, N:] == 7.0), "wrote outside the N columns"
+    close(got[:, :N], ref, dtype, k=2.0)
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_gemm_epilogues(dtype):
+    rng = np.random.default_rng(5)
+    M, N, K = 200, 136, 72
+    A = rng.standard_normal((M, K)).astype(np.float32) * 0.5
+    B = rng.standard_normal((N, K)).astype(np.float32) * 0.5
+    bias = rng.standard_normal(N).astype(np.float32)
+    resid = rng.standard_normal((M, N)).astype(np.float32)
+    base = quant(A, dtype) @ quant(B, dtype).T
+    dA, dB, dbias, dres = dev(A, dtype), dev(B, dtype), dev(bias, dtype), dev(resid, dtype)
+    # bias + residual
+    C = torch.zeros((M, N), dtype=dA.dtype, device=DEV)
+    mi.mimose_op_gemm(dtype, dA, K, 1, dB, K, 1, C, N, 0, M, N, K, bias=dbias, resid=dres, ldr=N)
+    sync()
+    close(host(C), base + quant(bias, dtype) + quant(resid, dtype), dtype, k=2.0)
+    # bias + GELU (both forms): C gets the pre-activation, gelu_out the activation
+    for form in (1, 2):
+        C = torch.zeros((M, N), dtype=dA.dtype, device=DEV)
+        Gt = torch.zeros((M, N), dtype=dA.dtype, device=DEV)
+        mi.mimose_op_gemm(dtype, dA, K, 1, dB, K, 1, C, N, 0, M, N, K, bias=dbias, gelu_out=Gt, gelu=form)
+        sync()
+        pre = base + quant(bias, dtype)
+        close(host(C), pre, dtype, k=2.0)
+        close(host(Gt), om.gelu_fwd(pre, form == 2), dtype, scale=np.abs(pre).max(), k=3.0)
+    # weight-gradient form: fp32 output and row sums of the A operand
+    T = 333
+    dY = rng.standard_normal((T, M)).astype(np.float32)
+    X = rng.standard_normal((T, N)).astype(np.float32)
+    ddY, dX = dev(dY, dtype), dev(X, dtype)
+    W = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    rs = torch.zeros(M, dtype=torch.float32, device=DEV)
+    mi.mimose_op_gemm(dtype, ddY, M, 0, dX, N, 0, W, N, 1, M, N, T, a_rowsum=rs)
+    sync()
+    close(host(W), quant(dY, dtype).T @ quant(X, dtype), 0, k=20.0)
+    close(host(rs), quant(dY, dtype).sum(0), 0, k=20.0)
+
+
+def test_gemm_rejects_misaligned_bf16():
+    a = torch.zeros(64 * 20, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(mi.MimoseError):
+        mi.mimose_op_gemm(1, a, 12, 1, a, 12, 1, a, 16, 0, 4, 4, 12)
+
+
+# ---------------------------------------------------------------- LayerNorm
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("T,H", [(37, 64), (130, 768), (5, 1024), (64, 24)])
+def test_layernorm_fwd_bwd(dtype, T, H):
+    rng = np.random.default_rng(T + H)
+    x = (rng.standard_normal((T, H)) * 2 + 0.5).astype(np.float32)
+    g = (1 + 0.2 * rng.standard_normal(H)).astype(np.float32)
+    b = (0.1 * rng.standard_normal(H)).astype(np.float32)
+    dy = rng.standard_normal((T, H)).astype(np.float32)
+    add = rng.standard_normal((T, H)).astype(np.float32)
+    xq, gq, bq, dyq, addq = (quant(v, dtype) for v in (x, g, b, dy, add))
+    y_ref, saved = om.layernorm_fwd(xq, gq, bq, 1e-5)
+    dx_ref, dg_ref, db_ref = om.layernorm_bwd(dyq, saved, gq)
+    dx_, dg_, db_, ddy, dadd = dev(x, dtype), dev(g, dtype), dev(b, dtype), dev(dy, dtype), dev(add, dtype)
+    y = torch.zeros_like(dx_)
+    mi.mimose_op_layernorm_fwd(dtype, dx_, dg_, db_, y, T, H, 1e-5)
+    sync()
+    close(host(y), y_ref, dtype, k=2.0)
+    P = mi.mimose_op_partial_rows(T)
+    partial = torch.zeros(P * 2 * H, dtype=torch.float32, device=DEV)
+    dgam = torch.zeros(H, dtype=torch.float32, device=DEV)
+    dbet = torch.zeros(H, dtype=torch.float32, device=DEV)
+    out = torch.zeros_like(dx_)
+    mi.mimose_op_layernorm_bwd(dtype, ddy, dx_, dg_, out, dadd, dgam, dbet, partial, T, H, 1e-5)
+    sync()
+    close(host(out), dx_ref + addq, dtype, k=3.0)
+    close(host(dgam), dg_ref, 0, k=50.0)
+    close(host(dbet), db_ref, 0, k=50.0)
+    # in place, no residual input
+    mi.mimose_op_layernorm_bwd(dtype, ddy, dx_, dg_, ddy, None, dgam, dbet, partial, T, H, 1e-5)
+    sync()
+    close(host(ddy), dx_ref, dtype, k=3.0)
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("form", [0, 1])
+def test_gelu_bwd(dtype, form):
+    rng = np.random.default_rng(9)
+    n = 8 * 1000 + 5
+    pre = (rng.standard_normal(n) * 2).astype(np.float32)
+    d = rng.standard_normal(n).astype(np.float32)
+    ref = quant(d, dtype) * om.gelu_grad(quant(pre, dtype), form)
+    dd, dp = dev(d, dtype), dev(pre, dtype)
+    mi.mimose_op_gelu_bwd(dtype, dd, dp, n, form)
+    sync()
+    close(host(dd), ref, dtype, k=2.0)
+
+
+# ---------------------------------------------------------------- attention
+def attention_case(dtype, B, L, nh, d, causal, seed):
+    rng = np.random.default_rng(seed)
+    H = nh * d
+    qkv = rng.standard_normal((B * L, 3 * H)).astype(np.float32)
+    dctx = rng.standard_normal((B * L, H)).astype(np.float32)
+    qq = quant(qkv, dtype)
+    q, k, v = (om.split_heads(qq[:, i * H:(i + 1) * H], B, L, nh) for i in range(3))
+    o, p = om.attention_fwd(q, k, v, causal)
+    ctx_ref = om.merge_heads(o)
+    s = (q @ k.transpose(0, 1, 3, 2)) / np.sqrt(d)
+    if causal:
+        s = np.where(np.triu(np.ones((L, L), bool), 1), -np.inf, s)
+    lse_ref = np.log(np.exp(s - s.max(-1, keepdims=True)).sum(-1)) + s.max(-1)
+    dqkv_dev = dev(qkv, dtype)
+    ctx = torch.zeros((B * L, H), dtype=dqkv_dev.dtype, device=DEV)
+    lse = torch.zeros(B * nh * L, dtype=torch.float32, device=DEV)
+    mi.mimose_op_attention_fwd(dtype, dqkv_dev, ctx, lse, B, L, nh, d, causal)
+    sync()
+    close(host(ctx), ctx_ref, dtype, k=3.0)
+    assert np.abs(host(lse).reshape(B, nh, L) - lse_ref).max() < (1e-4 if dtype == 0 else 2e-2)
+    # backward consumes the stored (rounded) forward output, like the training step does
+    ctx_q = host(ctx)
+    do = om.split_heads(quant(dctx, dtype), B, L, nh)
+    dq, dk, dv = om.attention_bwd(do, q, k, v, p)
+    ref = np.concatenate([om.merge_heads(dq), om.merge_heads(dk), om.merge_heads(dv)], axis=1)
+    ddctx = dev(dctx, dtype)
+    delta = torch.zeros(B * nh * L, dtype=torch.float32, device=DEV)
+    out = torch.zeros_like(dqkv_dev)
+    mi.mimose_op_attention_bwd(dtype, dqkv_dev, ctx, ddctx, lse, delta, out, B, L, nh, d, causal)
+    sync()
+    got = host(out)
+    for i, name in enumerate("qkv"):
+        e = rel_l2(got[:, i * H:(i + 1) * H], ref[:, i * H:(i + 1) * H])
+        assert e < (2e-5 if dtype == 0 else 1.5e-2), (name, e)
+    assert ctx_q.shape == ctx_ref.shape
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("causal", [0, 1])
+@pytest.mark.parametrize("B,L,nh,d", [(2, 70, 2, 32), (1, 200, 3, 64), (3, 1, 2, 64), (2, 17, 1, 32), (1, 129, 2, 64)])
+def test_attention(dtype, causal, B, L, nh, d):
+    attention_case(dtype, B, L, nh, d, causal, seed=B * 100 + L)
+
+
+# ---------------------------------------------------------------- softmax cross-entropy
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("T,V", [(50, 1000), (9, 37), (20, 30522)])
+def test_softmax_xent(dtype, T, V):
+    rng = np.random.default_rng(V)
+    ld = (V + 63) // 64 * 64
+    logits = (rng.standard_normal((T, V)) * 3).astype(np.float32)
+    labels = rng.integers(0, V, T).astype(np.int32)
+    labels[1] = -1
+    n_valid = int((labels >= 0).sum())
+    loss_ref, d_ref = om.cross_entropy(quant(logits, dtype), labels)
+    buf = np.full((T, ld), 3.0, np.float32)
+    buf[:, :V] = logits
+    dl = dev(buf, dtype)
+    row_loss = torch.zeros(T, dtype=torch.float32, device=DEV)
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+    mi.mimose_op_softmax_xent(dtype, dl, ld, torch.tensor(labels, device=DEV), row_loss, loss, T, V, n_valid)
+    sync()
+    got = host(dl)
+    assert np.all(got[:, V:] == 0.0)
+    assert abs(float(loss.item()) - loss_ref) <= 2e-6 * abs(loss_ref) * (1 if dtype == 0 else 10)
+    close(got[:, :V], d_ref, dtype, scale=np.abs(d_ref).max(), k=3.0)
+    assert np.all(got[1] == 0.0)
+
+
+# ---------------------------------------------------------------- embedding
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("has_ln", [0, 1])
+def test_embedding_fwd_bwd(dtype, has_ln):
+    rng = np.random.default_rng(3)
+    B, L, H, V, max_seq = 3, 21, 192, 50, 32
+    tok = rng.standard_normal((V, H)).astype(np.float32)
+    pos = rng.standard_normal((max_seq, H)).astype(np.float32)
+    g = (1 + 0.1 * rng.standard_normal(H)).astype(np.float32)
+    b = (0.1 * rng.standard_normal(H)).astype(np.float32)
+    ids = rng.integers(0, V, B * L).astype(np.int32)
+    p = np.tile(np.arange(L), B)
+    s_ref = quant(quant(tok, dtype)[ids] + quant(pos, dtype)[p], dtype)
+    y_ref = om.layernorm_fwd(s_ref, quant(g, dtype), quant(b, dtype), 1e-5)[0] if has_ln else s_ref
+    dtok, dpos, dg, db_ = dev(tok, dtype), dev(pos, dtype), dev(g, dtype), dev(b, dtype)
+    dids = torch.tensor(ids, device=DEV)
+    ssum = torch.zeros((B * L, H), dtype=dtok.dtype, device=DEV)
+    y = torch.zeros_like(ssum)
+    mi.mimose_op_embed_fwd(dtype, dids, dtok, dpos, dg, db_, ssum, y, B, L, H, 1e-5, has_ln)
+    sync()
+    assert np.array_equal(host(ssum), s_ref)
+    close(host(y), y_ref, dtype, k=2.0)
+    # backward: deterministic scatter-add
+    d = rng.standard_normal((B * L, H)).astype(np.float32)
+    order = np.argsort(ids, kind="stable").astype(np.int32)
+    sorted_ids = ids[order]
+    starts = np.flatnonzero(np.r_[True, sorted_ids[1:] != sorted_ids[:-1]]).astype(np.int32)
+    seg = np.r_[starts, B * L].astype(np.int32)
+    gtok = torch.ones((V, H), dtype=torch.float32, device=DEV)
+    gpos = torch.full((max_seq, H), 5.0, dtype=torch.float32, device=DEV)
+    mi.mimose_op_embed_bwd(dtype, dev(d, dtype), dids, torch.tensor(order, device=DEV), torch.tensor(seg, device=DEV),
+                           len(starts), gtok, gpos, B, L, H, max_seq)
+    sync()
+    ref_tok = np.ones((V, H)); np.add.at(ref_tok, ids, quant(d, dtype))
+    ref_pos = np.zeros((max_seq, H)); np.add.at(ref_pos, p, quant(d, dtype))
+    close(host(gtok), ref_tok, 0, k=20.0)
+    close(host(gpos), ref_pos, 0, k=20.0)

@@ -1,0 +1,187 @@
+"""Whole-step parity of the HIP path against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+import synthdata
+import paper_2209_02478_amd as mi
+from oracle import model as om
+from oracle import planner as op
+from gpu_util import rel_l2
+
+pytestmark = pytest.mark.gpu
+
+MiB = 1 << 20
+
+
+def oracle_step(shape, params, tokens, labels, dtype=np.float64):
+    cfg = om.Cfg.from_shape(synthdata.shape_dict(shape))
+    if shape.dtype == "bf16":
+        params = {k: om.round_to_bf16(v) for k, v in params.items()}
+    return om.train_step(cfg, params, tokens, labels, dtype=dtype)
+
+
+def check_against_oracle(shape, m, params, tokens, labels, loss_tol, grad_tol, oracle_dtype=np.float64):
+    loss, peak, plan = m.train_step(tokens, labels)
+    G = m.grads()
+    ref_loss, RG = oracle_step(shape, params, tokens, labels, oracle_dtype)
+    assert abs(loss - ref_loss) <= loss_tol * abs(ref_loss), (loss, ref_loss)
+    worst = ("", 0.0)
+    for k, ref in RG.items():
+        e = rel_l2(G[k], ref)
+        if e > worst[1]:
+            worst = (k, e)
+        assert e <= grad_tol, (k, e)
+    return loss, peak, plan, worst
+
+
+SMALL = {
+    "fp32_postln": synthdata.ModelShape(2, 64, 2, 256, 1000, 64, "fp32"),
+    "fp32_preln_causal": synthdata.ModelShape(3, 64, 2, 128, 300, 48, "fp32", causal=1, pre_ln=1, gelu_tanh=1, head=0),
+    "fp32_preln_head": synthdata.ModelShape(2, 128, 2, 256, 200, 40, "fp32", pre_ln=1, head=1),
+    "bf16_postln": synthdata.ModelShape(3, 128, 2, 512, 1000, 96, "bf16"),
+    "bf16_preln_causal": synthdata.ModelShape(2, 256, 4, 512, 777, 80, "bf16", causal=1, pre_ln=1, gelu_tanh=1, head=0),
+}
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+@pytest.mark.parametrize("B,L", [(4, 33), (2, 7)])
+def test_step_parity_small_models(name, B, L):
+    shape = SMALL[name]
+    params = synthdata.make_params(shape, 11, perturb=True)
+    tokens, labels = synthdata.make_batch(shape, B, L, 12)
+    if not shape.causal:
+        labels = labels.copy(); labels[0, 1] = -1
+    m = mi.Mimose(synthdata.shape_dict(shape), 0, arena_bytes=256 * MiB)
+    m.load_params(params)
+    m.force_plan(0)
+    fp32 = shape.dtype == "fp32"
+    check_against_oracle(shape, m, params, tokens, labels, 1e-4 if fp32 else 1e-2, 1e-3 if fp32 else 2e-2)
+    m.close()
+
+
+@pytest.mark.parametrize("name", ["fp32_postln", "bf16_postln", "bf16_preln_causal"])
+def test_checkpointed_gradients_bit_identical(name):
+    shape = SMALL[name]
+    n = shape.n_layers
+    params = synthdata.make_params(shape, 21, perturb=True)
+    tokens, labels = synthdata.make_batch(shape, 4, 40, 22)
+    m = mi.Mimose(synthdata.shape_dict(shape), 0, arena_bytes=256 * MiB)
+    m.load_params(params)
+    m.force_plan(0)
+    loss0, peak0, _ = m.train_step(tokens, labels)
+    G0 = m.grads()
+    peaks = {0: peak0}
+    for plan in range(1, 1 << n):
+        m.force_plan(plan)
+        loss, peak, got = m.train_step(tokens, labels)
+        assert got == plan and loss == loss0
+        peaks[plan] = peak
+        G = m.grads()
+        for k in G0:
+            assert np.array_equal(G0[k], G[k]), (plan, k)
+    assert peaks[(1 << n) - 1] == min(peaks.values()) < peak0
+    m.close()
+
+
+def test_tiny_workload_every_step():
+    """The small fp32 configuration end to end: sheltered then responsive steps under the
+    budget, every step checked against the oracle and the oracle planner."""
+    wl = synthdata.WORKLOADS["tiny"]
+    shape, B, n = wl.shape, wl.batch, wl.shape.n_layers
+    d = synthdata.shape_dict(shape)
+    cal = mi.Mimose(d, 0, device=None)
+    cal.force_plan(0)
+    peak0, _ = cal.dry_step(B, shape.max_seq)
+    cal.close()
+    budget = int(wl.budget_frac * peak0)
+    params = synthdata.make_params(shape, wl.seed)
+    m = mi.Mimose(d, budget)
+    m.load_params(params)
+    ref = op.Planner(n, budget, guard=4096)
+    lens = synthdata.seq_lengths(wl.length_recipe, wl.steps, wl.seed)
+    plans = []
+    for i, L in enumerate(lens):
+        tokens, labels = synthdata.make_batch(shape, B, L, synthdata.step_seed(wl.seed, i))
+        sheltered = ref.sheltered()
+        loss, peak, plan, worst = check_against_oracle(shape, m, params, tokens, labels, 1e-4, 1e-3)
+        assert peak <= budget
+        mem = m.step_memory()
+        c = op.Components(F=mem["F"], e=mem["e"], g=mem["g"], a=mem["a"], b=mem["b"], w=mem["w"])
+        assert peak == op.simulate_peak(c, plan)
+        x = B * L
+        if sheltered:
+            assert plan == (1 << n) - 1
+            for l in range(n):
+                ref.feed(x, op.Q_A, l, c.a[l]); ref.feed(x, op.Q_B, l, c.b[l]); ref.feed(x, op.Q_W, l, c.w[l])
+            ref.feed(x, op.Q_E, -1, c.e); ref.feed(x, op.Q_G, -1, c.g); ref.feed(x, op.Q_F, -1, c.F)
+            ref.end_sheltered_step(x)
+        else:
+            assert plan == ref.query(x).plan
+        plans.append(plan)
+    st = m.stats()
+    assert st["steps"] == wl.steps and st["sheltered_steps"] == 10
+    assert st["cache_hits"] == ref.hits and st["cache_misses"] == ref.misses
+    m.close()
+
+
+def test_bert_base_shape_step():
+    """BERT-base shape, bf16, full batch of 32 at the shortest length: parity with the oracle
+    (float32 build, bf16-rounded weights)."""
+    wl = synthdata.WORKLOADS["bert_base"]
+    shape = wl.shape
+    params = synthdata.make_params(shape, wl.seed)
+    tokens, labels = synthdata.make_batch(shape, wl.batch, 64, 5)
+    m = mi.Mimose(synthdata.shape_dict(shape), 0, arena_bytes=4096 * MiB)
+    m.load_params(params)
+    m.force_plan(0)
+    loss, peak, plan, worst = check_against_oracle(shape, m, params, tokens, labels, 1e-2, 2e-2, np.float32)
+    print("bert_base L=64: loss", loss, "worst grad", worst)
+    # same batch with half the layers dropped: identical bits
+    G0 = m.grads()
+    m.force_plan(0b010101010101)
+    loss2, peak2, _ = m.train_step(tokens, labels)
+    assert loss2 == loss and peak2 < peak
+    G1 = m.grads()
+    for k in G0:
+        assert np.array_equal(G0[k], G1[k]), k
+    m.close()
+
+
+def test_bert_base_full_length_under_budget():
+    """Launch configuration of the benchmark at the longest length (B=32, L=512): the planner
+    keeps the measured peak under 60 % of the no-checkpoint peak, the loss sits at its
+    closed-form initial value and checkpointed gradients equal the unconstrained ones bit for bit."""
+    wl = synthdata.WORKLOADS["bert_base"]
+    shape, B = wl.shape, wl.batch
+    d = synthdata.shape_dict(shape)
+    cal = mi.Mimose(d, 0, device=None)
+    cal.force_plan(0)
+    peak0, _ = cal.dry_step(B, 512)
+    cal.close()
+    budget = int(wl.budget_frac * peak0)
+    params = synthdata.make_params(shape, wl.seed)
+    m = mi.Mimose(d, budget, arena_bytes=peak0 + MiB)
+    m.load_params(params)
+    lens = [64, 128, 200, 264, 320, 400, 448, 512, 96, 160]
+    for i, L in enumerate(lens):                          # sheltered phase
+        tokens, labels = synthdata.make_batch(shape, B, L, 100 + i)
+        loss, peak, plan = m.train_step(tokens, labels)
+        assert plan == (1 << 12) - 1 and peak <= budget
+    tokens, labels = synthdata.make_batch(shape, B, 512, 999)
+    loss, peak, plan = m.train_step(tokens, labels)
+    assert plan != 0 and peak <= budget
+    expect = np.log(shape.vocab) + 0.5 * 0.02 ** 2 * shape.hidden
+    assert abs(loss - expect) < 0.02 * expect
+    G1 = m.grads()
+    short = m.train_step(*synthdata.make_batch(shape, B, 64, 998))
+    assert short[2] == 0 and short[1] <= budget
+    m.close()
+    big = mi.Mimose(d, 0, arena_bytes=peak0 + MiB)
+    big.load_params(params)
+    big.force_plan(0)
+    loss0, peak_full, _ = big.train_step(tokens, labels)
+    assert loss0 == loss and peak_full == peak0 and peak_full > budget
+    G0 = big.grads()
+    for k in G0:
+        assert np.array_equal(G0[k], G1[k]), k
+    big.close()
