@@ -1,0 +1,147 @@
+"""Throughput of the checkpointed variable-length training step on one MI355X.
+
+One step = one call of mimose_train_step: plan lookup, embedding, all layers forward with the
+plan's drops, head + loss, backward with recomputation, embedding backward.  Prints one JSON
+line: samples/s, the bf16 MFMA roofline of the GEMM kernel measured with events on the work
+stream, and the CPU oracle timed on the host cores as a reported baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0
+PEAK_HBM_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="bert_base")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
+                         "(no collectives or sharding exist in this library)\n")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synthdata
+    import paper_2209_02478_amd as mi
+
+    if not os.path.exists(mi.LIB_PATH):
+        from paper_2209_02478_amd import build as b
+        b.build(verbose=False)
+    wl = synthdata.WORKLOADS[args.workload]
+    shape, B, N = wl.shape, wl.batch, wl.shape.n_layers
+    d = synthdata.shape_dict(shape)
+
+    cal = mi.Mimose(d, 0, device=None)
+    cal.force_plan(0)
+    peak0, _ = cal.dry_step(B, shape.max_seq)
+    cal.close()
+    budget = int(wl.budget_frac * peak0)
+
+    m = mi.Mimose(d, budget)
+    m.load_params(synthdata.make_params(shape, wl.seed))
+    sheltered = 10
+    total = sheltered + args.warmup + args.steps
+    lens = synthdata.seq_lengths(wl.length_recipe, total, wl.seed)
+    batches = [synthdata.make_batch(shape, B, L, synthdata.step_seed(wl.seed, i)) for i, L in enumerate(lens)]
+
+    for t, l in batches[:sheltered + args.warmup]:
+        m.train_step(t, l)
+    timed = batches[sheltered + args.warmup:]
+    s0 = m.stats()
+    max_peak = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t, l in timed:
+        _, pk, _ = m.train_step(t, l)
+        max_peak = max(max_peak, pk)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    s1 = m.stats()
+
+    # same steps again with per-kernel events on the work stream
+    mi.mimose_profile_enable(m.ctx, 1)
+    for t, l in timed:
+        m.train_step(t, l)
+    torch.cuda.synchronize()
+    kernels = {}
+    for i, name in enumerate(mi.KERNEL_CLASSES):
+        n, ms, work = mi.mimose_profile_read(m.ctx, i)
+        if n:
+            rate = work / (ms * 1e-3)
+            kernels[name] = {"launches": n, "avg_us": round(1e3 * ms / n, 3),
+                             ("tflops" if i < 3 else "gbs"): round(rate / (1e12 if i < 3 else 1e9), 2)}
+    mi.mimose_profile_enable(m.ctx, 0)
+    m.close()
+
+    K = len(timed)
+    useful = s1["useful_flops_total"] - s0["useful_flops_total"]
+    recompute = s1["recompute_flops_total"] - s0["recompute_flops_total"]
+    hits = s1["cache_hits"] - s0["cache_hits"]
+    misses = s1["cache_misses"] - s0["cache_misses"]
+    gemm_tflops = kernels.get("gemm", {}).get("tflops", 0.0)
+    out = {
+        "metric": "train samples/s under fixed mem budget, BERT-base var seq len",
+        "value": round(K * B / dt, 2), "unit": "samples/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": round(1e3 * dt / K, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {N} layers, hidden {shape.hidden}, {shape.n_heads} heads, ffn {shape.ffn}, "
+                               f"vocab {shape.vocab}, batch {B}, per-batch length {wl.length_recipe}, "
+                               f"budget {wl.budget_frac:.2f} x no-checkpoint peak at L={shape.max_seq}",
+                   "global_batch": B, "mean_seq_len": round(float(np.mean([t.shape[1] for t, _ in timed])), 1),
+                   "budget_bytes": budget, "sheltered_steps": sheltered},
+        "tokens_per_s": round(sum(t.size for t, _ in timed) / dt, 1),
+        "useful_tflops": round(useful / dt / 1e12, 2), "recompute_tflops": round(recompute / dt / 1e12, 2),
+        "mfma_frac_useful": round(useful / dt / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "mfma_frac_useful_plus_recompute": round((useful + recompute) / dt / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "recompute_overhead": round(recompute / useful, 4),
+        "mean_recomputed_layers": round((s1["recomputed_layers_total"] - s0["recomputed_layers_total"]) / K, 2),
+        "plan_cache_hit_rate": round(hits / max(hits + misses, 1), 4),
+        "planner_us_per_step": round((s1["planner_ns_total"] - s0["planner_ns_total"]) / K / 1e3, 2),
+        "max_peak_over_budget": round(max_peak / budget, 4),
+        "kernels": kernels,
+        "roofline": {"bound": "mfma", "kernel": "bgemm_kernel (all GEMM launches of the timed steps)",
+                     "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+
+
+def cpu_baseline(wl):
+    """The oracle as it stands, timed on this host: one step on a reduced batch."""
+    import numpy as np
+    import synthdata
+    from oracle import model as om
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    shape = wl.shape
+    Bs, L = 8, 200
+    cfg = om.Cfg.from_shape(synthdata.shape_dict(shape))
+    params = synthdata.make_params(shape, wl.seed)
+    tokens, labels = synthdata.make_batch(shape, Bs, L, 1)
+    t0 = time.perf_counter()
+    om.train_step(cfg, params, tokens, labels)
+    dt = time.perf_counter() - t0
+    return {"value": round(Bs / dt, 3), "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"one fp64 oracle step (forward, loss, backward) of the same model at batch {Bs}, L={L}: "
+                      f"{dt:.1f} s"}
+
+
+if __name__ == "__main__":
+    main()

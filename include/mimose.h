@@ -138,6 +138,22 @@ int mimose_planner_end_step(mimose_ctx* ctx, int32_t B, int32_t L);
 int mimose_planner_query(mimose_ctx* ctx, int32_t B, int32_t L, uint64_t* plan,
                          uint64_t* predicted_peak);
 
+/* Per-kernel-class timing with events on the work stream (measurement aid; adds two event
+ * records per launch while enabled).  Enabling or disabling clears the totals.  work is
+ * algorithmic: floating-point operations for GEMM and attention, bytes for the others. */
+#define MIMOSE_K_GEMM 0
+#define MIMOSE_K_ATTN_FWD 1
+#define MIMOSE_K_ATTN_BWD 2
+#define MIMOSE_K_LN_FWD 3
+#define MIMOSE_K_LN_BWD 4
+#define MIMOSE_K_GELU_BWD 5
+#define MIMOSE_K_XENT 6
+#define MIMOSE_K_EMBED_FWD 7
+#define MIMOSE_K_COUNT 8
+int mimose_profile_enable(mimose_ctx* ctx, int32_t on);
+int mimose_profile_read(mimose_ctx* ctx, int32_t kernel_class, uint64_t* launches, double* total_ms,
+                        double* total_work);
+
 /* What the collector measured in the last completed step (Section 4.2), in bytes: fixed F,
  * embedding stage e, head transient g, and per layer (arrays of n_layers, may be NULL) the
  * bytes kept (a_l), kept when checkpointed (b_l) and the backward transient (w_l). */

@@ -65,6 +65,8 @@ SIGNATURES = {
     "mimose_planner_feed": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _u64]),
     "mimose_planner_end_step": (C.c_int, [_vp, _i32, _i32]),
     "mimose_planner_query": (C.c_int, [_vp, _i32, _i32, C.POINTER(_u64), C.POINTER(_u64)]),
+    "mimose_profile_enable": (C.c_int, [_vp, _i32]),
+    "mimose_profile_read": (C.c_int, [_vp, _i32, C.POINTER(_u64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "mimose_get_step_memory": (C.c_int, [_vp, C.POINTER(_u64), C.POINTER(_u64), C.POINTER(_u64), _vp, _vp, _vp]),
     "mimose_get_stats": (C.c_int, [_vp, C.POINTER(mimose_stats)]),
     "mimose_last_error": (C.c_char_p, [_vp]),
@@ -196,6 +198,20 @@ def mimose_planner_query(ctx, B: int, L: int) -> Tuple[int, int]:
     plan, peak = _u64(), _u64()
     _check(load_library().mimose_planner_query(ctx, B, L, C.byref(plan), C.byref(peak)), ctx)
     return plan.value, peak.value
+
+
+KERNEL_CLASSES = ("gemm", "attention_fwd", "attention_bwd", "layernorm_fwd", "layernorm_bwd", "gelu_bwd",
+                  "softmax_xent", "embed_fwd")
+
+
+def mimose_profile_enable(ctx, on: int):
+    _check(load_library().mimose_profile_enable(ctx, on), ctx)
+
+
+def mimose_profile_read(ctx, kernel_class: int) -> Tuple[int, float, float]:
+    n, ms, work = _u64(), C.c_double(), C.c_double()
+    _check(load_library().mimose_profile_read(ctx, kernel_class, C.byref(n), C.byref(ms), C.byref(work)), ctx)
+    return n.value, ms.value, work.value
 
 
 def mimose_get_step_memory(ctx, n_layers: int) -> dict:
@@ -341,4 +357,4 @@ class Mimose:
 
 
 __all__ = [n for n in dir() if n.startswith("mimose_") or n.startswith("MIMOSE_") or n.startswith("Q_")] + \
-          ["Mimose", "MimoseError", "make_cfg", "load_library", "LIB_PATH", "SIGNATURES", "ERR_NAMES"]
+          ["Mimose", "MimoseError", "make_cfg", "load_library", "LIB_PATH", "SIGNATURES", "ERR_NAMES", "KERNEL_CLASSES"]

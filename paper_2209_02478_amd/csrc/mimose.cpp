@@ -99,6 +99,21 @@ struct mimose_ctx {
   // memory components measured in the last completed step
   uint64_t last_e = 0, last_g = 0;
   std::vector<uint64_t> last_a, last_b, last_w;
+  // optional per-kernel-class timing with events on the work stream
+  bool prof_on = false;
+  struct ProfPending { int cls; double work; hipEvent_t a, b; };
+  std::vector<hipEvent_t> ev_pool;
+  size_t ev_used = 0;
+  std::vector<ProfPending> prof_pending;
+  struct ProfClass { uint64_t launches = 0; double ms = 0, work = 0; } prof[MIMOSE_K_COUNT];
+  hipEvent_t prof_event() {
+    if (ev_used == ev_pool.size()) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) return nullptr;
+      ev_pool.push_back(e);
+    }
+    return ev_pool[ev_used++];
+  }
 
   int elt() const { return cfg.dtype == mk::BF16 ? 2 : 4; }
   int64_t ldv() const { return (cfg.vocab + 63) / 64 * 64; }
@@ -179,12 +194,28 @@ class Step {
   void *dA_ = nullptr, *dB_ = nullptr, *emb_sum_ = nullptr, *h0_ = nullptr;
   int n_seg_ = 0, n_valid_ = 0;
 
+  // times everything enqueued during its lifetime as one launch of kernel class `cls`
+  struct Timed {
+    mimose_ctx* c; hipEvent_t b = nullptr;
+    Timed(Step* s, int cls, double work) : c(s->c_) {
+      if (!c->prof_on || s->dry_) { c = nullptr; return; }
+      hipEvent_t a = c->prof_event();
+      b = c->prof_event();
+      if (!a || !b) { c = nullptr; return; }
+      (void)hipEventRecord(a, s->st_);
+      c->prof_pending.push_back({cls, work, a, b});
+    }
+    ~Timed() { if (c) (void)hipEventRecord(b, c->stream); }
+  };
+  double es_d() const { return (double)es_; }
+
   void* w(int i) const { return c_->params[i].w; }
   float* g(int i) const { return c_->params[i].g; }
   void* talloc(int64_t elems) { return c_->arena.alloc((uint64_t)elems * es_); }
 
   void gemm(const mk::GemmArgs& a) {
     if (dry_) return;
+    Timed t(this, MIMOSE_K_GEMM, 2.0 * a.M * a.N * a.K);
     if (!mk::gemm(dt_, a, st_)) throw StepError{MIMOSE_ERR_INVALID_ARG, "gemm: unsupported alignment"};
   }
   // Y[T,out] = X[T,in] W[out,in]^T + bias (+ resid) (GELU: Y = pre-activation, act = GELU(Y))
@@ -209,11 +240,13 @@ class Step {
     gemm(a);
   }
   void ln_fwd(const void* x, int gi, int bi, void* y) {
+    Timed t(this, MIMOSE_K_LN_FWD, 2.0 * T_ * f_.hidden * es_d());
     if (!dry_) mk::layernorm_fwd(dt_, x, w(gi), w(bi), y, T_, f_.hidden, f_.ln_eps, st_);
   }
   void ln_bwd(const void* dy, const void* x, int gi, int bi, void* dx, const void* add) {
     const uint64_t m = c_->arena.top();
     float* partial = (float*)c_->arena.alloc((uint64_t)mk::partial_rows(T_) * 2 * f_.hidden * 4);
+    Timed t(this, MIMOSE_K_LN_BWD, (add ? 4.0 : 3.0) * T_ * f_.hidden * es_d());
     if (!dry_) mk::layernorm_bwd(dt_, dy, x, w(gi), dx, add, g(gi), g(bi), partial, T_, f_.hidden, f_.ln_eps, st_);
     c_->arena.pop_to(m);
   }
@@ -260,6 +293,7 @@ void Step::embed_stage(const int32_t* tokens, const int32_t* labels) {
   int32_t* order = s + 2 * (size_t)T_;
   for (int t = 0; t < T_; ++t) order[count[tokens[t]]++] = t;
   HIPCHK(c_, hipMemcpyAsync(ints, s, need * 4, hipMemcpyHostToDevice, st_));
+  Timed t(this, MIMOSE_K_EMBED_FWD, (f_.pre_ln ? 3.0 : 4.0) * T_ * H * es_d());
   mk::embed_fwd(dt_, ids_, w(c_->i_tok), w(c_->i_pos), f_.pre_ln ? nullptr : w(c_->i_eg),
                 f_.pre_ln ? nullptr : w(c_->i_eb), emb_sum_, h0_, B_, L_, H, f_.ln_eps, !f_.pre_ln, st_);
 }
@@ -290,7 +324,10 @@ void Step::layer_forward(int l, LayerActs& A) {
   const void* a = A.x;
   if (f_.pre_ln) { ln_fwd(A.x, p.ln1g, p.ln1b, A.n1); a = A.n1; }
   linear(a, H, p.wqkv, p.bqkv, A.qkv, 3 * H, 3 * H);
-  if (!dry_) mk::attention_fwd(dt_, A.qkv, A.ctx, A.lse, B_, L_, nh, d, f_.causal, st_);
+  {
+    Timed t(this, MIMOSE_K_ATTN_FWD, 4.0 * T_ * L_ * H * (f_.causal ? 0.5 : 1.0));
+    if (!dry_) mk::attention_fwd(dt_, A.qkv, A.ctx, A.lse, B_, L_, nh, d, f_.causal, st_);
+  }
   linear(A.ctx, H, p.wo, p.bo, A.s1, H, H, A.x);
   if (f_.pre_ln) {
     ln_fwd(A.s1, p.ln2g, p.ln2b, A.u);
@@ -315,7 +352,10 @@ void Step::layer_backward(int l, LayerActs& A) {
   wgrad(dA_, H, H, A.act, F, p.w2, p.b2);
   void* dact = talloc(TF);
   dgrad(dA_, H, H, p.w2, dact, F);
-  if (!dry_) mk::gelu_bwd(dt_, dact, A.pre, TF, f_.gelu_tanh, st_);          // dact = d pre
+  {
+    Timed t(this, MIMOSE_K_GELU_BWD, 3.0 * TF * es_d());
+    if (!dry_) mk::gelu_bwd(dt_, dact, A.pre, TF, f_.gelu_tanh, st_);        // dact = d pre
+  }
   wgrad(dact, F, F, A.u, H, p.w1, p.b1);
   if (f_.pre_ln) {
     dgrad(dact, F, F, p.w1, dB_, H);                                          // dB = d LN2(u)
@@ -331,7 +371,10 @@ void Step::layer_backward(int l, LayerActs& A) {
   dgrad(dB_, H, H, p.wo, dctx, H);
   void* dqkv = talloc(3 * TH);
   float* delta = (float*)ar.alloc((uint64_t)B_ * nh * L_ * 4);
-  if (!dry_) mk::attention_bwd(dt_, A.qkv, A.ctx, dctx, A.lse, delta, dqkv, B_, L_, nh, d, f_.causal, st_);
+  {
+    Timed t(this, MIMOSE_K_ATTN_BWD, 8.0 * T_ * L_ * H * (f_.causal ? 0.5 : 1.0));
+    if (!dry_) mk::attention_bwd(dt_, A.qkv, A.ctx, dctx, A.lse, delta, dqkv, B_, L_, nh, d, f_.causal, st_);
+  }
   const void* a = f_.pre_ln ? A.n1 : A.x;
   wgrad(dqkv, 3 * H, 3 * H, a, H, p.wqkv, p.bqkv);
   if (f_.pre_ln) {
@@ -368,7 +411,10 @@ void Step::head(float* loss_dev) {
     a.bias = f_.head ? w(c_->i_bdec) : nullptr;
     gemm(a);
   }
-  if (!dry_) mk::softmax_xent(dt_, logits, ldv, labels_, row_loss, loss_dev, T_, V, n_valid_, st_);
+  {
+    Timed t(this, MIMOSE_K_XENT, 2.0 * T_ * ldv * es_d());
+    if (!dry_) mk::softmax_xent(dt_, logits, ldv, labels_, row_loss, loss_dev, T_, V, n_valid_, st_);
+  }
   // tied decoder: its weight gradient overwrites the embedding gradient, the embedding
   // backward adds onto it later
   {
@@ -450,6 +496,15 @@ void Step::run(const int32_t* tokens, const int32_t* labels, float* loss_out) {
     HIPCHK(c_, hipStreamSynchronize(st_));
     HIPCHK(c_, hipGetLastError());
     *loss_out = *c_->loss_host;
+    for (auto& p : c_->prof_pending) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess) {
+        auto& k = c_->prof[p.cls];
+        k.launches++; k.ms += ms; k.work += p.work;
+      }
+    }
+    c_->prof_pending.clear();
+    c_->ev_used = 0;
   }
 }
 
@@ -509,6 +564,7 @@ int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, int32_t
   try {
     s.run(tokens, labels, &lv);
   } catch (const OomError& e) {
+    c->prof_pending.clear(); c->ev_used = 0;
     c->arena.pop_to(c->fixed_top);
     if (!dry && c->has_device) (void)hipStreamSynchronize(c->stream);
     char buf[160];
@@ -516,6 +572,7 @@ int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, int32_t
              (unsigned long long)e.want, (unsigned long long)e.top, (unsigned long long)e.cap);
     return fail(c, MIMOSE_ERR_OOM_BUDGET, buf);
   } catch (const StepError& e) {
+    c->prof_pending.clear(); c->ev_used = 0;
     c->arena.pop_to(c->fixed_top);
     if (!dry && c->has_device) (void)hipStreamSynchronize(c->stream);
     return fail(c, e.code, e.msg);
@@ -698,6 +755,21 @@ int mimose_planner_query(mimose_ctx* c, int32_t B, int32_t L, uint64_t* plan, ui
   return MIMOSE_OK;
 }
 
+int mimose_profile_enable(mimose_ctx* c, int32_t on) {
+  if (!c) return MIMOSE_ERR_INVALID_ARG;
+  c->prof_on = on != 0;
+  for (auto& k : c->prof) k = mimose_ctx::ProfClass();
+  return MIMOSE_OK;
+}
+
+int mimose_profile_read(mimose_ctx* c, int32_t kernel_class, uint64_t* launches, double* total_ms, double* total_work) {
+  if (!c || kernel_class < 0 || kernel_class >= MIMOSE_K_COUNT) return fail(c, MIMOSE_ERR_INVALID_ARG, "kernel class out of range");
+  if (launches) *launches = c->prof[kernel_class].launches;
+  if (total_ms) *total_ms = c->prof[kernel_class].ms;
+  if (total_work) *total_work = c->prof[kernel_class].work;
+  return MIMOSE_OK;
+}
+
 int mimose_get_step_memory(mimose_ctx* c, uint64_t* fixed, uint64_t* embed, uint64_t* head, uint64_t* kept,
                            uint64_t* boundary, uint64_t* bwd) {
   if (!c) return MIMOSE_ERR_INVALID_ARG;
@@ -728,6 +800,7 @@ void mimose_destroy(mimose_ctx* c) {
   if (!c) return;
   if (c->has_device) {
     (void)hipStreamSynchronize(c->stream);
+    for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
     if (c->stage) (void)hipHostFree(c->stage);
     if (c->loss_host) (void)hipHostFree(c->loss_host);
   }
