@@ -1,6 +1,7 @@
 // Fused attention, forward and backward, without materialising the L x L matrices.
 //
-// Wave-per-row kernels in fp32 arithmetic for head sizes 32 and 64.  One wave owns one
+// Wave-per-row kernels in fp32 arithmetic for head sizes 32 and 64 (the fp32 configuration and
+// bf16 with head size 32; bf16 with head size 64 runs on the MFMA kernels of attention_mfma.hip).  One wave owns one
 // query row (forward, dQ) or one key row (dK/dV): its 64 lanes first each take one
 // opposite-side row to form a score, then each take one head-dimension column to
 // accumulate the output, with the scores broadcast lane by lane.  Every output element is
@@ -44,6 +45,11 @@ __device__ __forceinline__ float dot_row(const T* p, const float (&q)[D]) {
 }
 
 constexpr int kRowsPerBlock = 16;   // 4 waves x 4 rows
+
+// bf16, head size 64: MFMA kernels
+void attention_fwd_mfma(const void* qkv, void* ctx, float* lse, int B, int L, int nh, int causal, hipStream_t st);
+void attention_bwd_mfma(const void* qkv, const void* dctx, const float* lse, const float* delta, void* dqkv, int B,
+                        int L, int nh, int causal, hipStream_t st);
 
 // qkv row stride is 3*H; head hh of token t: q at t*3H + hh*D, k at +H, v at +2H.
 template <typename T, int D>
@@ -210,6 +216,7 @@ static void bwd_t(const void* qkv, const void* ctx, const void* dctx, const floa
 void attention_fwd(int dtype, const void* qkv, void* ctx, float* lse, int B, int L, int nh, int d, int causal,
                    hipStream_t st) {
   if (B * L <= 0) return;
+  if (dtype == BF16 && d == 64) { attention_fwd_mfma(qkv, ctx, lse, B, L, nh, causal, st); return; }
 #define F32_(DD) fwd_t<float, DD>(qkv, ctx, lse, B, L, nh, causal, st)
 #define BF_(DD) fwd_t<bf16_t, DD>(qkv, ctx, lse, B, L, nh, causal, st)
   DISPATCH_TD(F32_, BF_)
@@ -220,6 +227,13 @@ void attention_fwd(int dtype, const void* qkv, void* ctx, float* lse, int B, int
 void attention_bwd(int dtype, const void* qkv, const void* ctx, const void* dctx, const float* lse, float* delta,
                    void* dqkv, int B, int L, int nh, int d, int causal, hipStream_t st) {
   if (B * L <= 0) return;
+  if (dtype == BF16 && d == 64) {
+    int64_t n = (int64_t)B * L * nh;
+    hipLaunchKernelGGL((attn_delta_kernel<bf16_t, 64>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                       (const bf16_t*)ctx, (const bf16_t*)dctx, delta, B, L, nh);
+    attention_bwd_mfma(qkv, dctx, lse, delta, dqkv, B, L, nh, causal, st);
+    return;
+  }
 #define F32_(DD) bwd_t<float, DD>(qkv, ctx, dctx, lse, delta, dqkv, B, L, nh, causal, st)
 #define BF_(DD) bwd_t<bf16_t, DD>(qkv, ctx, dctx, lse, delta, dqkv, B, L, nh, causal, st)
   DISPATCH_TD(F32_, BF_)

@@ -1,0 +1,348 @@
+// Fused attention for bf16, head size 64, on the MFMA units (v_mfma_f32_32x32x16_bf16).
+//
+// All three kernels compute score tiles transposed, S^T = K Q^T, so that a lane's 32x32
+// accumulator registers belong to ONE query (forward, dQ) or ONE key (dK/dV): the softmax
+// statistics of a row are then reductions over a lane's own registers plus one exchange with
+// lane^32, and a lane's probabilities, converted to bf16, are directly the B operand of the
+// next product (P V, dS K, P^T dO, dS^T Q) without passing through LDS.  The operand that
+// multiplies them must be contiguous along the reduction index, so K / V / Q / dO tiles are
+// also stored transposed in LDS (register transpose of 4x8 blocks on the way in).
+//
+// MFMA 32x32x16 register layout used below (A: 32 x 16, B: 16 x 32, D: 32 x 32):
+//   A, B: lane holds row/column lane%32 and reduction indices 8*(lane/32) .. +7
+//   D:    lane holds column lane%32; register r holds row 8*(r/4) + 4*(lane/32) + r%4
+// Feeding D registers 8c..8c+7 as a B operand therefore assigns reduction slot (lane/32, e) the
+// row 16c + 8*(e/4) + 4*(lane/32) + e%4, and the A operand is gathered with the same map: two
+// runs of 4 consecutive indices.
+//
+// No atomics: dQ comes from a kernel that owns query rows, dK/dV from one that owns key rows.
+#include "device_common.h"
+#include "kernels.h"
+
+namespace mk {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+namespace {
+
+constexpr int D = 64;          // head size
+constexpr int TK = 64;         // rows of a streamed tile
+constexpr int LDT = 72;        // LDS row stride in elements (144 bytes)
+constexpr int ROWS_PER_BLOCK = 128;
+
+__device__ __forceinline__ bf16x8 ld_frag(const bf16_t* p) { return *(const bf16x8*)p; }
+
+__device__ __forceinline__ uint32_t pack2(float a, float b) {
+  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+}
+// registers 8c .. 8c+7 of an accumulator as a bf16 operand
+__device__ __forceinline__ bf16x8 regs_to_frag(const f32x16& v, int c) {
+  uint4 u;
+  u.x = pack2(v[8 * c + 0], v[8 * c + 1]);
+  u.y = pack2(v[8 * c + 2], v[8 * c + 3]);
+  u.z = pack2(v[8 * c + 4], v[8 * c + 5]);
+  u.w = pack2(v[8 * c + 6], v[8 * c + 7]);
+  return __builtin_bit_cast(bf16x8, u);
+}
+// A operand from a transposed tile: row `row`, reduction indices base+4h+{0..3}, base+8+4h+{0..3}
+__device__ __forceinline__ bf16x8 ld_frag_t(const bf16_t (*tile)[LDT], int row, int base, int h) {
+  uint2 lo = *(const uint2*)&tile[row][base + 4 * h];
+  uint2 hi = *(const uint2*)&tile[row][base + 8 + 4 * h];
+  uint4 u = make_uint4(lo.x, lo.y, hi.x, hi.y);
+  return __builtin_bit_cast(bf16x8, u);
+}
+
+// 128 threads bring one 64 x 64 tile (rows r0.., row stride ld, rows clamped to last) into LDS,
+// as is ([row][d]) and / or transposed ([d][row]).  t in [0,128): 4 rows x 8 columns each.
+template <bool NORMAL, bool TRANSPOSED>
+__device__ __forceinline__ void stage_tile(const bf16_t* src, int64_t ld, int r0, int last, int t,
+                                           bf16_t (*normal)[LDT], bf16_t (*transposed)[LDT]) {
+  const int rq = t >> 3, cb = t & 7;
+  uint4 v[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    int r = min(r0 + 4 * rq + j, last);
+    v[j] = *(const uint4*)(src + (int64_t)r * ld + 8 * cb);
+  }
+  if (NORMAL) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) *(uint4*)&normal[4 * rq + j][8 * cb] = v[j];
+  }
+  if (TRANSPOSED) {
+    const uint32_t* w0 = (const uint32_t*)&v[0];
+    const uint32_t* w1 = (const uint32_t*)&v[1];
+    const uint32_t* w2 = (const uint32_t*)&v[2];
+    const uint32_t* w3 = (const uint32_t*)&v[3];
+#pragma unroll
+    for (int mm = 0; mm < 8; ++mm) {
+      const int d = mm >> 1;
+      uint2 o;
+      if (mm & 1) {
+        o.x = (w0[d] >> 16) | (w1[d] & 0xFFFF0000u);
+        o.y = (w2[d] >> 16) | (w3[d] & 0xFFFF0000u);
+      } else {
+        o.x = (w0[d] & 0xFFFFu) | (w1[d] << 16);
+        o.y = (w2[d] & 0xFFFFu) | (w3[d] << 16);
+      }
+      *(uint2*)&transposed[8 * cb + mm][4 * rq] = o;
+    }
+  }
+}
+
+__device__ __forceinline__ void zero(f32x16& v) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) v[r] = 0.f;
+}
+
+// store a transposed accumulator pair (rows = head columns, lane column = token) as bf16
+__device__ __forceinline__ void store_rows(bf16_t* dst, const f32x16 (&acc)[2], int h, float mul) {
+#pragma unroll
+  for (int db = 0; db < 2; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      uint2 o;
+      o.x = pack2(acc[db][4 * g] * mul, acc[db][4 * g + 1] * mul);
+      o.y = pack2(acc[db][4 * g + 2] * mul, acc[db][4 * g + 3] * mul);
+      *(uint2*)(dst + 32 * db + 8 * g + 4 * h) = o;
+    }
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ forward
+template <bool CAUSAL>
+__global__ __launch_bounds__(256) void fa_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
+                                                     float* __restrict__ lse, int L, int nh) {
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[TK][LDT];   // [key][d]
+  __shared__ __attribute__((aligned(16))) bf16_t Vt[D][LDT];    // [d][key]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, ql = lane & 31, h = lane >> 5;
+  const int bh = blockIdx.y, b = bh / nh, hh = bh - b * nh;
+  const int H = nh * D;
+  const int64_t ld3 = 3 * (int64_t)H;
+  const bf16_t* base = qkv + (int64_t)b * L * ld3 + hh * D;
+  const int qi = blockIdx.x * ROWS_PER_BLOCK + wave * 32 + ql;
+  const int qc = min(qi, L - 1);
+  const float scale = 0.125f;
+
+  bf16x8 qf[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) qf[kk] = ld_frag(base + (int64_t)qc * ld3 + 16 * kk + 8 * h);
+  f32x16 o[2];
+  zero(o[0]); zero(o[1]);
+  float m = -INFINITY, l = 0.f;
+  const int kend = CAUSAL ? min(L, (int)(blockIdx.x + 1) * ROWS_PER_BLOCK) : L;
+
+  for (int k0 = 0; k0 < kend; k0 += TK) {
+    __syncthreads();
+    if (tid < 128) stage_tile<true, false>(base + H, ld3, k0, L - 1, tid, Ks, nullptr);
+    else stage_tile<false, true>(base + 2 * H, ld3, k0, L - 1, tid - 128, nullptr, Vt);
+    __syncthreads();
+    f32x16 s[2];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      zero(s[kb]);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(&Ks[32 * kb + ql][16 * kk + 8 * h]), qf[kk], s[kb], 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = k0 + 32 * kb + 8 * (r >> 2) + 4 * h + (r & 3);
+        float v = s[kb][r] * scale;
+        if (key >= L || (CAUSAL && key > qi)) v = -INFINITY;
+        s[kb][r] = v;
+        mx = fmaxf(mx, v);
+      }
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mnew = fmaxf(m, mx);
+    const float alpha = __expf(m - mnew);
+    float rs = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = __expf(s[kb][r] - mnew);
+        s[kb][r] = p;
+        rs += p;
+      }
+    rs += __shfl_xor(rs, 32, 64);
+    l = l * alpha + rs;
+    m = mnew;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const bf16x8 pf = regs_to_frag(s[kb], c);
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_t(Vt, 32 * db + ql, 32 * kb + 16 * c, h), pf, o[db], 0, 0, 0);
+      }
+  }
+  if (qi < L) {
+    store_rows(ctx + ((int64_t)b * L + qi) * H + hh * D, o, h, 1.f / l);
+    if (h == 0) lse[(int64_t)bh * L + qi] = m + __logf(l);
+  }
+}
+
+// ------------------------------------------------------------------ dQ
+template <bool CAUSAL>
+__global__ __launch_bounds__(256) void fa_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
+                                                        const float* __restrict__ lse, const float* __restrict__ delta,
+                                                        bf16_t* __restrict__ dqkv, int L, int nh) {
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[TK][LDT];   // [key][d]
+  __shared__ __attribute__((aligned(16))) bf16_t Kt[D][LDT];    // [d][key]
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[TK][LDT];   // [key][d]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, ql = lane & 31, h = lane >> 5;
+  const int bh = blockIdx.y, b = bh / nh, hh = bh - b * nh;
+  const int H = nh * D;
+  const int64_t ld3 = 3 * (int64_t)H;
+  const bf16_t* base = qkv + (int64_t)b * L * ld3 + hh * D;
+  const int qi = blockIdx.x * ROWS_PER_BLOCK + wave * 32 + ql;
+  const int qc = min(qi, L - 1);
+  const float scale = 0.125f;
+
+  bf16x8 qf[4], gf[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    qf[kk] = ld_frag(base + (int64_t)qc * ld3 + 16 * kk + 8 * h);
+    gf[kk] = ld_frag(dctx + ((int64_t)b * L + qc) * H + hh * D + 16 * kk + 8 * h);
+  }
+  const float lse_q = lse[(int64_t)bh * L + qc], delta_q = delta[(int64_t)bh * L + qc];
+  f32x16 dq[2];
+  zero(dq[0]); zero(dq[1]);
+  const int kend = CAUSAL ? min(L, (int)(blockIdx.x + 1) * ROWS_PER_BLOCK) : L;
+
+  for (int k0 = 0; k0 < kend; k0 += TK) {
+    __syncthreads();
+    if (tid < 128) stage_tile<true, true>(base + H, ld3, k0, L - 1, tid, Ks, Kt);
+    else stage_tile<true, false>(base + 2 * H, ld3, k0, L - 1, tid - 128, Vs, nullptr);
+    __syncthreads();
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      f32x16 s, dp;
+      zero(s); zero(dp);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(&Ks[32 * kb + ql][16 * kk + 8 * h]), qf[kk], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(&Vs[32 * kb + ql][16 * kk + 8 * h]), gf[kk], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = k0 + 32 * kb + 8 * (r >> 2) + 4 * h + (r & 3);
+        const bool masked = key >= L || (CAUSAL && key > qi);
+        const float p = masked ? 0.f : __expf(s[r] * scale - lse_q);
+        s[r] = p * (dp[r] - delta_q);
+      }
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const bf16x8 dsf = regs_to_frag(s, c);
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+          dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_t(Kt, 32 * db + ql, 32 * kb + 16 * c, h), dsf, dq[db], 0, 0, 0);
+      }
+    }
+  }
+  if (qi < L) store_rows(dqkv + ((int64_t)b * L + qi) * ld3 + hh * D, dq, h, scale);
+}
+
+// ------------------------------------------------------------------ dK, dV
+template <bool CAUSAL>
+__global__ __launch_bounds__(256) void fa_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
+                                                         const float* __restrict__ lse, const float* __restrict__ delta,
+                                                         bf16_t* __restrict__ dqkv, int L, int nh) {
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[TK][LDT];   // [query][d]
+  __shared__ __attribute__((aligned(16))) bf16_t Qt[D][LDT];    // [d][query]
+  __shared__ __attribute__((aligned(16))) bf16_t Gs[TK][LDT];   // dO [query][d]
+  __shared__ __attribute__((aligned(16))) bf16_t Gt[D][LDT];    // dO [d][query]
+  __shared__ float lse_s[TK], delta_s[TK];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, kl = lane & 31, h = lane >> 5;
+  const int bh = blockIdx.y, b = bh / nh, hh = bh - b * nh;
+  const int H = nh * D;
+  const int64_t ld3 = 3 * (int64_t)H;
+  const bf16_t* base = qkv + (int64_t)b * L * ld3 + hh * D;
+  const bf16_t* gbase = dctx + (int64_t)b * L * H + hh * D;
+  const int ki = blockIdx.x * ROWS_PER_BLOCK + wave * 32 + kl;
+  const int kc = min(ki, L - 1);
+  const float scale = 0.125f;
+
+  bf16x8 kf[4], vf[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    kf[kk] = ld_frag(base + (int64_t)kc * ld3 + H + 16 * kk + 8 * h);
+    vf[kk] = ld_frag(base + (int64_t)kc * ld3 + 2 * H + 16 * kk + 8 * h);
+  }
+  f32x16 dk[2], dv[2];
+  zero(dk[0]); zero(dk[1]); zero(dv[0]); zero(dv[1]);
+  const int qstart = CAUSAL ? blockIdx.x * ROWS_PER_BLOCK : 0;     // earlier queries never see these keys
+
+  for (int q0 = qstart; q0 < L; q0 += TK) {
+    __syncthreads();
+    if (tid < 128) stage_tile<true, true>(base, ld3, q0, L - 1, tid, Qs, Qt);
+    else stage_tile<true, true>(gbase, H, q0, L - 1, tid - 128, Gs, Gt);
+    if (tid < TK) {
+      const int q = min(q0 + tid, L - 1);
+      lse_s[tid] = lse[(int64_t)bh * L + q];
+      delta_s[tid] = delta[(int64_t)bh * L + q];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      f32x16 s, dp;
+      zero(s); zero(dp);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(&Qs[32 * qb + kl][16 * kk + 8 * h]), kf[kk], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(&Gs[32 * qb + kl][16 * kk + 8 * h]), vf[kk], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int qq = 32 * qb + 8 * (r >> 2) + 4 * h + (r & 3);
+        const int q = q0 + qq;
+        const bool masked = q >= L || (CAUSAL && ki > q);
+        const float p = masked ? 0.f : __expf(s[r] * scale - lse_s[qq]);
+        s[r] = p;
+        dp[r] = p * (dp[r] - delta_s[qq]);
+      }
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const bf16x8 pf = regs_to_frag(s, c), dsf = regs_to_frag(dp, c);
+#pragma unroll
+        for (int db = 0; db < 2; ++db) {
+          dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_t(Gt, 32 * db + kl, 32 * qb + 16 * c, h), pf, dv[db], 0, 0, 0);
+          dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag_t(Qt, 32 * db + kl, 32 * qb + 16 * c, h), dsf, dk[db], 0, 0, 0);
+        }
+      }
+    }
+  }
+  if (ki < L) {
+    bf16_t* out = dqkv + ((int64_t)b * L + ki) * ld3 + hh * D;
+    store_rows(out + H, dk, h, scale);
+    store_rows(out + 2 * H, dv, h, 1.f);
+  }
+}
+
+void attention_fwd_mfma(const void* qkv, void* ctx, float* lse, int B, int L, int nh, int causal, hipStream_t st) {
+  dim3 grid((L + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, B * nh);
+  if (causal) hipLaunchKernelGGL(fa_fwd_kernel<true>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (bf16_t*)ctx, lse, L, nh);
+  else hipLaunchKernelGGL(fa_fwd_kernel<false>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (bf16_t*)ctx, lse, L, nh);
+}
+
+void attention_bwd_mfma(const void* qkv, const void* dctx, const float* lse, const float* delta, void* dqkv, int B,
+                        int L, int nh, int causal, hipStream_t st) {
+  dim3 grid((L + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, B * nh);
+  if (causal) {
+    hipLaunchKernelGGL(fa_bwd_dq_kernel<true>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, L, nh);
+    hipLaunchKernelGGL(fa_bwd_dkv_kernel<true>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, L, nh);
+  } else {
+    hipLaunchKernelGGL(fa_bwd_dq_kernel<false>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, L, nh);
+    hipLaunchKernelGGL(fa_bwd_dkv_kernel<false>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, L, nh);
+  }
+}
+
+}  // namespace mk

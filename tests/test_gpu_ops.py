@@ -167,7 +167,13 @@ def attention_case(dtype, B, L, nh, d, causal, seed):
     lse = torch.zeros(B * nh * L, dtype=torch.float32, device=DEV)
     mi.mimose_op_attention_fwd(dtype, dqkv_dev, ctx, lse, B, L, nh, d, causal)
     sync()
-    close(host(ctx), ctx_ref, dtype, k=3.0)
+    if dtype == 0:
+        close(host(ctx), ctx_ref, dtype, k=3.0)
+    else:
+        # bf16 path: probabilities are rounded to bf16 before the P V product, so the output error
+        # is a sum of many independent roundings: bound it in norm and in the largest element
+        assert rel_l2(host(ctx), ctx_ref) < 6e-3
+        assert np.abs(host(ctx) - ctx_ref).max() < 4 * EPS[1] * np.abs(ctx_ref).max()
     assert np.abs(host(lse).reshape(B, nh, L) - lse_ref).max() < (1e-4 if dtype == 0 else 2e-2)
     # backward consumes the stored (rounded) forward output, like the training step does
     ctx_q = host(ctx)
@@ -180,15 +186,17 @@ def attention_case(dtype, B, L, nh, d, causal, seed):
     mi.mimose_op_attention_bwd(dtype, dqkv_dev, ctx, ddctx, lse, delta, out, B, L, nh, d, causal)
     sync()
     got = host(out)
+    floor = 1e-2 * np.linalg.norm(ref)                      # dQ and dK vanish identically when L = 1
     for i, name in enumerate("qkv"):
-        e = rel_l2(got[:, i * H:(i + 1) * H], ref[:, i * H:(i + 1) * H])
+        part = ref[:, i * H:(i + 1) * H]
+        e = np.linalg.norm(got[:, i * H:(i + 1) * H] - part) / max(np.linalg.norm(part), floor)
         assert e < (2e-5 if dtype == 0 else 1.5e-2), (name, e)
     assert ctx_q.shape == ctx_ref.shape
 
 
 @pytest.mark.parametrize("dtype", [0, 1])
 @pytest.mark.parametrize("causal", [0, 1])
-@pytest.mark.parametrize("B,L,nh,d", [(2, 70, 2, 32), (1, 200, 3, 64), (3, 1, 2, 64), (2, 17, 1, 32), (1, 129, 2, 64)])
+@pytest.mark.parametrize("B,L,nh,d", [(2, 70, 2, 32), (1, 200, 3, 64), (3, 1, 2, 64), (2, 17, 1, 32), (1, 129, 2, 64), (2, 333, 2, 64)])
 def test_attention(dtype, causal, B, L, nh, d):
     attention_case(dtype, B, L, nh, d, causal, seed=B * 100 + L)
 
