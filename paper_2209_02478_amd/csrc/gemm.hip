@@ -6,11 +6,13 @@
 //   wgrad     dW[out,in]= dY[T,out]^T X[T,in]       A m-major, B m-major
 // "k-major": the reduction index is the contiguous one in memory.
 //
-// bf16: 128x128x32 tiles, 4 waves (2x2), each wave 64x64 as 2x2 MFMA 32x32x16
-// tiles with fp32 accumulators.  Both operands are staged in LDS k-contiguous;
-// m-major operands are transposed in registers on the way in, so the MFMA inner
-// loop is the same for all three products.  The reduction order over k is fixed
-// by the shape alone, so results are reproducible bit for bit.
+// bf16: 128x128x64 tiles, 4 waves (2x2), each wave 64x64 as 2x2 MFMA 32x32x16
+// tiles with fp32 accumulators, LDS double-buffered through registers.  k-major
+// operands are staged [row][k] and read 16 bytes per lane; m-major operands are
+// staged as they come, [k][row], and read with the transposing LDS loads of
+// gfx950, so no operand is ever transposed in memory or in registers.  The
+// reduction order over k is fixed by the shape alone: results are reproducible
+// bit for bit.
 // fp32: a plain 64x64x16 LDS-tiled kernel (small-model configuration only).
 #include "device_common.h"
 #include "kernels.h"
@@ -93,95 +95,142 @@ __global__ __launch_bounds__(256) void sgemm_kernel(GemmDev p) {
 // ------------------------------------------------------------------ bf16 MFMA
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 
-constexpr int BM = 128, BN = 128, BK = 32, LDSK = BK + 8;
+constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int LDK = BK + 8;        // row stride of a k-major tile [128 rows][64 k] (144 B: conflict-free 16 B reads)
+constexpr int LDM = 128 + 32;      // row stride of an m-major tile [64 k][128 rows] (320 B: conflict-free transposing reads)
+constexpr int TILE_K_ELEMS = 128 * LDK, TILE_M_ELEMS = BK * LDM;
 
-// Stage registers for one operand tile (128 rows x 32 k).
-struct Stage { uint4 v[4]; };
+// One operand tile: global -> registers -> LDS -> MFMA fragments.
+//   k-major source (elem(r,k) = X[r*ld+k]) is stored [row][k]; a fragment is one 16-byte read.
+//   m-major source (elem(r,k) = X[k*ld+r]) is stored as it comes, [k][row]; a fragment is two
+//   transposing 8-byte reads (ds_read_b64_tr_b16: within 16 lanes, lane i receives element i%4
+//   of the four lanes 4k + i/4, i.e. a 4(k) x 16(row) block is handed out one row index per lane).
+template <bool KM>
+struct Tile {
+  static constexpr int ELEMS = KM ? TILE_K_ELEMS : TILE_M_ELEMS;
 
-// k-major source: elem(r,k) = X[r*ld + k]; two 16-byte chunks per thread.
-__device__ __forceinline__ void load_kmajor(Stage& s, const bf16_t* X, int64_t ldx, int R, int K,
-                                            int r0, int k0, int tid) {
+  static __device__ __forceinline__ void load(uint4 (&v)[4], const bf16_t* __restrict__ X, int64_t ldx, int R, int K,
+                                              int r0, int k0, int tid, bool interior) {
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    int c = tid + i * 256;
-    int gr = r0 + (c >> 2), gk = k0 + (c & 3) * 8;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (gr < R) {
-      const bf16_t* src = X + (int64_t)gr * ldx + gk;
-      if (gk + 8 <= K) {
-        v = *(const uint4*)src;
-      } else if (gk < K) {
-        bf16_t t[8];
+    for (int i = 0; i < 4; ++i) {
+      const int c = tid + i * 256;
+      const int a = KM ? (c >> 3) : (c >> 4);          // slow index within the tile
+      const int f = KM ? (c & 7) * 8 : (c & 15) * 8;   // fast (contiguous) index
+      const int gr = KM ? r0 + a : r0 + f;             // row (m or n) of the first element
+      const int gk = KM ? k0 + f : k0 + a;             // reduction index of the first element
+      const bf16_t* src = KM ? X + (int64_t)gr * ldx + gk : X + (int64_t)gk * ldx + gr;
+      if (interior) {
+        v[i] = *(const uint4*)src;
+      } else {
+        uint4 t = make_uint4(0, 0, 0, 0);
+        const int slow_ok = KM ? gr < R : gk < K;
+        const int fast_pos = KM ? gk : gr, fast_end = KM ? K : R;
+        if (slow_ok) {
+          if (fast_pos + 8 <= fast_end) {
+            t = *(const uint4*)src;
+          } else if (fast_pos < fast_end) {
+            bf16_t e[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) t[e] = (gk + e < K) ? src[e] : (bf16_t)0;
-        v = *(uint4*)t;
+            for (int q = 0; q < 8; ++q) e[q] = fast_pos + q < fast_end ? src[q] : (bf16_t)0;
+            t = *(uint4*)e;
+          }
+        }
+        v[i] = t;
       }
     }
-    s.v[i] = v;
   }
-}
-__device__ __forceinline__ void store_kmajor(const Stage& s, bf16_t (*tile)[LDSK], int tid) {
+  static __device__ __forceinline__ void store(const uint4 (&v)[4], bf16_t* tile, int tid) {
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    int c = tid + i * 256;
-    *(uint4*)&tile[c >> 2][(c & 3) * 8] = s.v[i];
+    for (int i = 0; i < 4; ++i) {
+      const int c = tid + i * 256;
+      if (KM) *(uint4*)&tile[(c >> 3) * LDK + (c & 7) * 8] = v[i];
+      else *(uint4*)&tile[(c >> 4) * LDM + (c & 15) * 8] = v[i];
+    }
+  }
+  // fragment for rows rbase + lane%32, reduction indices 16*ks + 8*(lane/32) .. +7
+  static __device__ __forceinline__ bf16x8 frag(const bf16_t* tile, int rbase, int ks, int lane) {
+    if (KM) return *(const bf16x8*)&tile[(rbase + (lane & 31)) * LDK + ks * 16 + (lane >> 5) * 8];
+    const int krow = ks * 16 + 8 * (lane >> 5) + ((lane & 15) >> 2);
+    const int col = rbase + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    struct { s16x4 lo, hi; } r;
+    r.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)&tile[krow * LDM + col]);
+    r.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)&tile[(krow + 4) * LDM + col]);
+    return __builtin_bit_cast(bf16x8, r);
+  }
+  // sum over the tile's 64 reduction indices of row `row` (partial, see caller)
+  static __device__ __forceinline__ float rowsum_part(const bf16_t* tile, int tid) {
+    float s = 0.f;
+    if (KM) {                       // two threads per row, 32 indices each
+      const bf16_t* src = &tile[(tid >> 1) * LDK + (tid & 1) * 32];
+#pragma unroll
+      for (int e = 0; e < 32; ++e) s += bf16_to_f32(src[e]);
+    } else {                        // two threads per row: even / odd halves of the 64 k rows
+      const bf16_t* src = &tile[(tid & 1) * 32 * LDM + (tid >> 1)];
+#pragma unroll
+      for (int e = 0; e < 32; ++e) s += bf16_to_f32(src[e * LDM]);
+    }
+    return s;
+  }
+};
+
+// epilogue for 4 consecutive columns n..n+3 of row m
+template <bool VEC>
+__device__ __forceinline__ void epilogue4(const GemmDev& p, int m, int n, float v0, float v1, float v2, float v3) {
+  if (m >= p.M || n >= p.N) return;
+  if (!VEC || n + 4 > p.N) {
+    epilogue<bf16_t>(p, m, n, v0); epilogue<bf16_t>(p, m, n + 1, v1);
+    epilogue<bf16_t>(p, m, n + 2, v2); epilogue<bf16_t>(p, m, n + 3, v3);
+    return;
+  }
+  float v[4] = {v0, v1, v2, v3};
+  if (p.bias) {
+    const uint2 b = *(const uint2*)((const bf16_t*)p.bias + n);
+    v[0] += __uint_as_float(b.x << 16); v[1] += __uint_as_float(b.x & 0xFFFF0000u);
+    v[2] += __uint_as_float(b.y << 16); v[3] += __uint_as_float(b.y & 0xFFFF0000u);
+  }
+  if (p.resid) {
+    const uint2 b = *(const uint2*)((const bf16_t*)p.resid + (int64_t)m * p.ldr + n);
+    v[0] += __uint_as_float(b.x << 16); v[1] += __uint_as_float(b.x & 0xFFFF0000u);
+    v[2] += __uint_as_float(b.y << 16); v[3] += __uint_as_float(b.y & 0xFFFF0000u);
+  }
+  const int64_t o = (int64_t)m * p.ldc + n;
+  if (p.c_f32) {
+    *(float4*)((float*)p.C + o) = make_float4(v[0], v[1], v[2], v[3]);
+    return;
+  }
+  uint2 w;
+  w.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+  w.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+  *(uint2*)((bf16_t*)p.C + o) = w;
+  if (p.gelu) {
+    float g[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) g[e] = p.gelu == GELU_TANH ? gelu_tanh(v[e]) : gelu_erf(v[e]);
+    w.x = (uint32_t)f32_to_bf16(g[0]) | ((uint32_t)f32_to_bf16(g[1]) << 16);
+    w.y = (uint32_t)f32_to_bf16(g[2]) | ((uint32_t)f32_to_bf16(g[3]) << 16);
+    *(uint2*)((bf16_t*)p.gelu_out + o) = w;
   }
 }
 
-// m-major source: elem(r,k) = X[k*ld + r]; threads 0..127 each take a 4(k) x 8(r) block.
-__device__ __forceinline__ void load_mmajor(Stage& s, const bf16_t* X, int64_t ldx, int R, int K,
-                                            int r0, int k0, int tid) {
-  if (tid >= 128) return;
-  int kq = tid >> 4, rb = tid & 15;
-  int gr = r0 + rb * 8;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    int gk = k0 + kq * 4 + j;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (gk < K) {
-      const bf16_t* src = X + (int64_t)gk * ldx + gr;
-      if (gr + 8 <= R) {
-        v = *(const uint4*)src;
-      } else if (gr < R) {
-        bf16_t t[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) t[e] = (gr + e < R) ? src[e] : (bf16_t)0;
-        v = *(uint4*)t;
-      }
-    }
-    s.v[j] = v;
-  }
-}
-__device__ __forceinline__ uint32_t pick(const uint4& v, int d) {
-  return d == 0 ? v.x : d == 1 ? v.y : d == 2 ? v.z : v.w;
-}
-__device__ __forceinline__ void store_mmajor(const Stage& s, bf16_t (*tile)[LDSK], int tid) {
-  if (tid >= 128) return;
-  int kq = tid >> 4, rb = tid & 15;
-#pragma unroll
-  for (int mm = 0; mm < 8; ++mm) {
-    const int d = mm >> 1;
-    uint32_t a0 = pick(s.v[0], d), a1 = pick(s.v[1], d), a2 = pick(s.v[2], d), a3 = pick(s.v[3], d);
-    uint2 o;
-    if (mm & 1) {
-      o.x = (a0 >> 16) | (a1 & 0xFFFF0000u);
-      o.y = (a2 >> 16) | (a3 & 0xFFFF0000u);
-    } else {
-      o.x = (a0 & 0xFFFFu) | (a1 << 16);
-      o.y = (a2 & 0xFFFFu) | (a3 << 16);
-    }
-    *(uint2*)&tile[rb * 8 + mm][kq * 4] = o;
-  }
-}
-
-template <bool AK, bool BKM>
-__global__ __launch_bounds__(256) void bgemm_kernel(GemmDev p) {
-  __shared__ __attribute__((aligned(16))) bf16_t As[2][BM][LDSK];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN][LDSK];
+// Grid: one-dimensional, 8 * ceil(tiles/8) blocks.  Hardware hands consecutive block ids to
+// the 8 XCDs in turn, so block id -> (xcd, slot) -> tile xcd*per + slot gives every XCD (and
+// its L2) a contiguous run of tiles that share A row panels.
+template <bool AK, bool BKM, bool VEC>
+__global__ __launch_bounds__(256, 2) void bgemm_kernel(GemmDev p, int tiles_n, int total, int per_xcd) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  typedef Tile<AK> TA;
+  typedef Tile<BKM> TB;
+  bf16_t* As = (bf16_t*)smem_raw;                    // two buffers of TA::ELEMS
+  bf16_t* Bs = As + 2 * TA::ELEMS;                   // two buffers of TB::ELEMS
+  const int t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (t >= total) return;
+  const int tile_m = t / tiles_n, tile_n = t - tile_m * tiles_n;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
   const bf16_t* A = (const bf16_t*)p.A;
   const bf16_t* B = (const bf16_t*)p.B;
   f32x16 acc[2][2];
@@ -192,69 +241,83 @@ __global__ __launch_bounds__(256) void bgemm_kernel(GemmDev p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  Stage sa, sb;
   const int nk = (p.K + BK - 1) / BK;
-  // bias gradient: blocks of the first column tile also sum their A rows (2 threads per row)
-  const bool do_rowsum = p.a_rowsum && blockIdx.x == 0;
+  const bool rows_in = m0 + BM <= p.M && n0 + BN <= p.N;
+  const bool do_rowsum = p.a_rowsum && tile_n == 0;
   float rs = 0.f;
-  if (AK) load_kmajor(sa, A, p.lda, p.M, p.K, m0, 0, tid); else load_mmajor(sa, A, p.lda, p.M, p.K, m0, 0, tid);
-  if (BKM) load_kmajor(sb, B, p.ldb, p.N, p.K, n0, 0, tid); else load_mmajor(sb, B, p.ldb, p.N, p.K, n0, 0, tid);
-  if (AK) store_kmajor(sa, As[0], tid); else store_mmajor(sa, As[0], tid);
-  if (BKM) store_kmajor(sb, Bs[0], tid); else store_mmajor(sb, Bs[0], tid);
+  uint4 sa[4], sb[4];
+  {
+    const bool interior = rows_in && BK <= p.K;
+    TA::load(sa, A, p.lda, p.M, p.K, m0, 0, tid, interior);
+    TB::load(sb, B, p.ldb, p.N, p.K, n0, 0, tid, interior);
+    TA::store(sa, As, tid);
+    TB::store(sb, Bs, tid);
+  }
   __syncthreads();
 
   for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
+    const bf16_t* at = As + (kt & 1) * TA::ELEMS;
+    const bf16_t* bt = Bs + (kt & 1) * TB::ELEMS;
     const bool more = kt + 1 < nk;
     if (more) {
       const int k0 = (kt + 1) * BK;
-      if (AK) load_kmajor(sa, A, p.lda, p.M, p.K, m0, k0, tid); else load_mmajor(sa, A, p.lda, p.M, p.K, m0, k0, tid);
-      if (BKM) load_kmajor(sb, B, p.ldb, p.N, p.K, n0, k0, tid); else load_mmajor(sb, B, p.ldb, p.N, p.K, n0, k0, tid);
+      const bool interior = rows_in && k0 + BK <= p.K;
+      TA::load(sa, A, p.lda, p.M, p.K, m0, k0, tid, interior);
+      TB::load(sb, B, p.ldb, p.N, p.K, n0, k0, tid, interior);
     }
-    if (do_rowsum) {
-      const bf16_t* src = &As[cur][tid >> 1][(tid & 1) * 16];
-#pragma unroll
-      for (int e = 0; e < 16; ++e) rs += bf16_to_f32(src[e]);
-    }
+    if (do_rowsum) rs += TA::rowsum_part(at, tid);
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       bf16x8 af[2], bfr[2];
-      const int kk = ks * 16 + (lane >> 5) * 8;
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        af[i] = *(const bf16x8*)&As[cur][wm * 64 + i * 32 + (lane & 31)][kk];
-        bfr[i] = *(const bf16x8*)&Bs[cur][wn * 64 + i * 32 + (lane & 31)][kk];
+        af[i] = TA::frag(at, wm * 64 + i * 32, ks, lane);
+        bfr[i] = TB::frag(bt, wn * 64 + i * 32, ks, lane);
       }
+      // roles swapped (B tile rows feed the MFMA's A side): a lane then owns one output row m
+      // and, per register group, four consecutive columns n
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
     }
     if (more) {
-      if (AK) store_kmajor(sa, As[cur ^ 1], tid); else store_mmajor(sa, As[cur ^ 1], tid);
-      if (BKM) store_kmajor(sb, Bs[cur ^ 1], tid); else store_mmajor(sb, Bs[cur ^ 1], tid);
+      TA::store(sa, As + ((kt + 1) & 1) * TA::ELEMS, tid);
+      TB::store(sb, Bs + ((kt + 1) & 1) * TB::ELEMS, tid);
     }
     __syncthreads();
   }
 
   if (do_rowsum) {
-    float tot = rs + __shfl_xor(rs, 1, 64);
-    int m = m0 + (tid >> 1);
+    const float tot = rs + __shfl_xor(rs, 1, 64);
+    const int m = m0 + (tid >> 1);
     if ((tid & 1) == 0 && m < p.M) p.a_rowsum[m] = tot;
   }
-  // accumulator layout of the 32x32 MFMA: lane%32 is the column, register r holds
-  // row 8*(r/4) + 4*(lane/32) + r%4
+  // accumulator (i, j), register r: row m = .. + lane%32, column n = .. + 8*(r/4) + 4*(lane/32) + r%4
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        int n = n0 + wn * 64 + j * 32 + (lane & 31);
-        epilogue<bf16_t>(p, m, n, acc[i][j][r]);
+      for (int g = 0; g < 4; ++g) {
+        const int m = m0 + wm * 64 + i * 32 + (lane & 31);
+        const int n = n0 + wn * 64 + j * 32 + 8 * g + 4 * (lane >> 5);
+        epilogue4<VEC>(p, m, n, acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
       }
+}
+
+template <bool AK, bool BKM, bool VEC>
+static void launch_bgemm(const GemmDev& p, hipStream_t st) {
+  constexpr int smem = 2 * (Tile<AK>::ELEMS + Tile<BKM>::ELEMS) * 2;
+  static bool configured = false;
+  if (!configured) {
+    (void)hipFuncSetAttribute((const void*)bgemm_kernel<AK, BKM, VEC>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    configured = true;
+  }
+  const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+  const int total = tiles_m * tiles_n, per = (total + 7) / 8;
+  hipLaunchKernelGGL((bgemm_kernel<AK, BKM, VEC>), dim3(per * 8), dim3(256), smem, st, p, tiles_n, total, per);
 }
 
 static bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
@@ -273,11 +336,18 @@ bool gemm(int dtype, const GemmArgs& g, hipStream_t st) {
     return true;
   }
   if ((g.lda & 7) || (g.ldb & 7) || !aligned16(g.A) || !aligned16(g.B)) return false;
-  dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM);
-  if (g.a_kmajor && g.b_kmajor) hipLaunchKernelGGL((bgemm_kernel<true, true>), grid, dim3(256), 0, st, p);
-  else if (g.a_kmajor && !g.b_kmajor) hipLaunchKernelGGL((bgemm_kernel<true, false>), grid, dim3(256), 0, st, p);
-  else if (!g.a_kmajor && g.b_kmajor) hipLaunchKernelGGL((bgemm_kernel<false, true>), grid, dim3(256), 0, st, p);
-  else hipLaunchKernelGGL((bgemm_kernel<false, false>), grid, dim3(256), 0, st, p);
+  // vector epilogue: four consecutive columns per access
+  const int cshift = g.c_f32 ? 15 : 7;
+  const bool vec = (g.ldc & 3) == 0 && (((uintptr_t)g.C) & cshift) == 0 &&
+                   (!g.resid || ((g.ldr & 3) == 0 && (((uintptr_t)g.resid) & 7) == 0)) &&
+                   (!g.bias || (((uintptr_t)g.bias) & 7) == 0) &&
+                   (!g.gelu_out || (((uintptr_t)g.gelu_out) & 7) == 0);
+#define LAUNCH_(AKV, BKV) do { if (vec) launch_bgemm<AKV, BKV, true>(p, st); else launch_bgemm<AKV, BKV, false>(p, st); } while (0)
+  if (g.a_kmajor && g.b_kmajor) LAUNCH_(true, true);
+  else if (g.a_kmajor && !g.b_kmajor) LAUNCH_(true, false);
+  else if (!g.a_kmajor && g.b_kmajor) LAUNCH_(false, true);
+  else LAUNCH_(false, false);
+#undef LAUNCH_
   return true;
 }
 
