@@ -175,11 +175,17 @@ void mimose_destroy(mimose_ctx* ctx);
  * likewise B with ldb.  c_f32: C is fp32 regardless of dtype (weight gradients).
  * a_rowsum (optional, fp32[M]) receives sum_k A(m,k) (the bias gradient of a weight-gradient
  * product).  gelu: 0 none, 1 erf, 2 tanh.  bf16: lda, ldb must be multiples of 8 and A, B
- * 16-byte aligned, otherwise INVALID_ARG. */
+ * 16-byte aligned, otherwise INVALID_ARG.  workspace: optional device scratch, see
+ * mimose_op_gemm_workspace_bytes. */
 int mimose_op_gemm(int32_t dtype, const void* A, int64_t lda, int32_t a_kmajor, const void* B,
                    int64_t ldb, int32_t b_kmajor, void* C, int64_t ldc, int32_t c_f32, int32_t M,
                    int32_t N, int32_t K, const void* bias, const void* resid, int64_t ldr,
-                   void* gelu_out, int32_t gelu, float* a_rowsum, void* stream);
+                   void* gelu_out, int32_t gelu, float* a_rowsum, void* workspace,
+                   uint64_t workspace_bytes, void* stream);
+/* Scratch that lets a bf16 product with fp32 output and few output tiles cut its reduction
+ * into parts that are summed in a fixed order (a function of M and N only; 0 = never needed).
+ * Passing NULL workspace to mimose_op_gemm is always allowed. */
+uint64_t mimose_op_gemm_workspace_bytes(int32_t M, int32_t N);
 /* y = LayerNorm(x) * gamma + beta over rows of length H <= 1024. */
 int mimose_op_layernorm_fwd(int32_t dtype, const void* x, const void* gamma, const void* beta,
                             void* y, int32_t T, int32_t H, float eps, void* stream);

@@ -72,7 +72,8 @@ SIGNATURES = {
     "mimose_last_error": (C.c_char_p, [_vp]),
     "mimose_destroy": (None, [_vp]),
     "mimose_op_gemm": (C.c_int, [_i32, _vp, _i64, _i32, _vp, _i64, _i32, _vp, _i64, _i32, _i32, _i32, _i32,
-                                 _vp, _vp, _i64, _vp, _i32, _vp, _vp]),
+                                 _vp, _vp, _i64, _vp, _i32, _vp, _vp, _u64, _vp]),
+    "mimose_op_gemm_workspace_bytes": (_u64, [_i32, _i32]),
     "mimose_op_layernorm_fwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _i32, _i32, _f32, _vp]),
     "mimose_op_layernorm_bwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _f32, _vp]),
     "mimose_op_partial_rows": (_i32, [_i32]),
@@ -240,10 +241,14 @@ def mimose_destroy(ctx):
 
 # kernel-level entry points: device tensors in, same argument order as the header
 def mimose_op_gemm(dtype, A, lda, a_kmajor, B, ldb, b_kmajor, Cm, ldc, c_f32, M, N, K, bias=None, resid=None, ldr=0,
-                   gelu_out=None, gelu=0, a_rowsum=None, stream=None):
+                   gelu_out=None, gelu=0, a_rowsum=None, workspace=None, workspace_bytes=0, stream=None):
     _check(load_library().mimose_op_gemm(dtype, _ptr(A), lda, a_kmajor, _ptr(B), ldb, b_kmajor, _ptr(Cm), ldc, c_f32,
                                          M, N, K, _ptr(bias), _ptr(resid), ldr, _ptr(gelu_out), gelu, _ptr(a_rowsum),
-                                         _ptr(stream)))
+                                         _ptr(workspace), workspace_bytes, _ptr(stream)))
+
+
+def mimose_op_gemm_workspace_bytes(M: int, N: int) -> int:
+    return load_library().mimose_op_gemm_workspace_bytes(M, N)
 
 
 def mimose_op_layernorm_fwd(dtype, x, gamma, beta, y, T, H, eps, stream=None):

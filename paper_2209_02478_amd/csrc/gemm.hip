@@ -25,6 +25,8 @@ struct GemmDev {
   int64_t lda, ldb, ldc, ldr;
   int M, N, K;
   int a_k, b_k, c_f32, gelu;
+  int splits;            // > 1: k range cut in `splits` parts, raw fp32 tiles go to `partial`
+  float* partial;        // [splits][M][N] followed by [splits][M] row sums
 };
 
 template <typename T>
@@ -96,6 +98,7 @@ __global__ __launch_bounds__(256) void sgemm_kernel(GemmDev p) {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers
 
 constexpr int BM = 128, BN = 128, BK = 64;
 constexpr int LDK = BK + 8;        // row stride of a k-major tile [128 rows][64 k] (144 B: conflict-free 16 B reads)
@@ -111,42 +114,56 @@ template <bool KM>
 struct Tile {
   static constexpr int ELEMS = KM ? TILE_K_ELEMS : TILE_M_ELEMS;
 
-  static __device__ __forceinline__ void load(uint4 (&v)[4], const bf16_t* __restrict__ X, int64_t ldx, int R, int K,
-                                              int r0, int k0, int tid, bool interior) {
+  static __device__ __forceinline__ void addr(int c, int r0, int k0, int& gr, int& gk) {
+    const int a = KM ? (c >> 3) : (c >> 4);          // slow index within the tile
+    const int f = KM ? (c & 7) * 8 : (c & 15) * 8;   // fast (contiguous) index
+    gr = KM ? r0 + a : r0 + f;                       // row (m or n) of the first element
+    gk = KM ? k0 + f : k0 + a;                       // reduction index of the first element
+  }
+  // tile fully inside the matrix: plain 16-byte loads
+  static __device__ __forceinline__ void load(u32x4 (&v)[4], const bf16_t* __restrict__ X, int64_t ldx, int r0, int k0,
+                                              int tid) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int c = tid + i * 256;
-      const int a = KM ? (c >> 3) : (c >> 4);          // slow index within the tile
-      const int f = KM ? (c & 7) * 8 : (c & 15) * 8;   // fast (contiguous) index
-      const int gr = KM ? r0 + a : r0 + f;             // row (m or n) of the first element
-      const int gk = KM ? k0 + f : k0 + a;             // reduction index of the first element
-      const bf16_t* src = KM ? X + (int64_t)gr * ldx + gk : X + (int64_t)gk * ldx + gr;
-      if (interior) {
-        v[i] = *(const uint4*)src;
-      } else {
-        uint4 t = make_uint4(0, 0, 0, 0);
-        const int slow_ok = KM ? gr < R : gk < K;
-        const int fast_pos = KM ? gk : gr, fast_end = KM ? K : R;
-        if (slow_ok) {
-          if (fast_pos + 8 <= fast_end) {
-            t = *(const uint4*)src;
-          } else if (fast_pos < fast_end) {
-            bf16_t e[8];
-#pragma unroll
-            for (int q = 0; q < 8; ++q) e[q] = fast_pos + q < fast_end ? src[q] : (bf16_t)0;
-            t = *(uint4*)e;
-          }
-        }
-        v[i] = t;
-      }
+      int gr, gk;
+      addr(tid + i * 256, r0, k0, gr, gk);
+      v[i] = *(const u32x4*)(KM ? X + (int64_t)gr * ldx + gk : X + (int64_t)gk * ldx + gr);
     }
   }
-  static __device__ __forceinline__ void store(const uint4 (&v)[4], bf16_t* tile, int tid) {
+  // tile crossing an edge: out-of-range elements read as zero
+  struct Regs { u32x4 v[4]; };
+  static __device__ __forceinline__ Regs load_edge(const bf16_t* __restrict__ X, int64_t ldx, int R, int K, int r0,
+                                                int k0, int tid) {
+    Regs out;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int gr, gk;
+      addr(tid + i * 256, r0, k0, gr, gk);
+      const bf16_t* src = KM ? X + (int64_t)gr * ldx + gk : X + (int64_t)gk * ldx + gr;
+      u32x4 t = {0u, 0u, 0u, 0u};
+      const bool slow_ok = KM ? gr < R : gk < K;
+      const int fast_pos = KM ? gk : gr, fast_end = KM ? K : R;
+      if (slow_ok) {
+        if (fast_pos + 8 <= fast_end) {
+          t = *(const u32x4*)src;
+        } else if (fast_pos < fast_end) {
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            const uint32_t e = fast_pos + q < fast_end ? (uint32_t)src[q] : 0u;
+            t[q >> 1] |= e << (16 * (q & 1));
+          }
+        }
+      }
+      out.v[i] = t;
+    }
+    return out;
+  }
+  static __device__ __forceinline__ void store(const u32x4 (&v)[4], bf16_t* tile, int tid) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int c = tid + i * 256;
-      if (KM) *(uint4*)&tile[(c >> 3) * LDK + (c & 7) * 8] = v[i];
-      else *(uint4*)&tile[(c >> 4) * LDM + (c & 15) * 8] = v[i];
+      if (KM) *(u32x4*)&tile[(c >> 3) * LDK + (c & 7) * 8] = v[i];
+      else *(u32x4*)&tile[(c >> 4) * LDM + (c & 15) * 8] = v[i];
     }
   }
   // fragment for rows rbase + lane%32, reduction indices 16*ks + 8*(lane/32) .. +7
@@ -176,15 +193,16 @@ struct Tile {
   }
 };
 
+__device__ __forceinline__ void epilogue4_edge(const GemmDev& p, int m, int n, float v0, float v1, float v2, float v3) {
+  epilogue<bf16_t>(p, m, n, v0); epilogue<bf16_t>(p, m, n + 1, v1);
+  epilogue<bf16_t>(p, m, n + 2, v2); epilogue<bf16_t>(p, m, n + 3, v3);
+}
+
 // epilogue for 4 consecutive columns n..n+3 of row m
 template <bool VEC>
 __device__ __forceinline__ void epilogue4(const GemmDev& p, int m, int n, float v0, float v1, float v2, float v3) {
   if (m >= p.M || n >= p.N) return;
-  if (!VEC || n + 4 > p.N) {
-    epilogue<bf16_t>(p, m, n, v0); epilogue<bf16_t>(p, m, n + 1, v1);
-    epilogue<bf16_t>(p, m, n + 2, v2); epilogue<bf16_t>(p, m, n + 3, v3);
-    return;
-  }
+  if (!VEC || n + 4 > p.N) { epilogue4_edge(p, m, n, v0, v1, v2, v3); return; }
   float v[4] = {v0, v1, v2, v3};
   if (p.bias) {
     const uint2 b = *(const uint2*)((const bf16_t*)p.bias + n);
@@ -215,57 +233,39 @@ __device__ __forceinline__ void epilogue4(const GemmDev& p, int m, int n, float 
   }
 }
 
-// Grid: one-dimensional, 8 * ceil(tiles/8) blocks.  Hardware hands consecutive block ids to
-// the 8 XCDs in turn, so block id -> (xcd, slot) -> tile xcd*per + slot gives every XCD (and
-// its L2) a contiguous run of tiles that share A row panels.
-template <bool AK, bool BKM, bool VEC>
-__global__ __launch_bounds__(256, 2) void bgemm_kernel(GemmDev p, int tiles_n, int total, int per_xcd) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+// k loop of one block.  Global loads run two k tiles ahead of the MFMAs (two register sets), LDS
+// holds two tiles, one barrier per k tile.  EDGE: tile crosses a matrix edge or K has a tail.
+template <bool AK, bool BKM, bool EDGE>
+__device__ __forceinline__ void mainloop(const GemmDev& p, bf16_t* As, bf16_t* Bs, int m0, int n0, int kt_begin, int nk,
+                                         int tid, int lane, int wm, int wn, bool do_rowsum, f32x16 (&acc)[2][2],
+                                         float& rs) {
   typedef Tile<AK> TA;
   typedef Tile<BKM> TB;
-  bf16_t* As = (bf16_t*)smem_raw;                    // two buffers of TA::ELEMS
-  bf16_t* Bs = As + 2 * TA::ELEMS;                   // two buffers of TB::ELEMS
-  const int t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (t >= total) return;
-  const int tile_m = t / tiles_n, tile_n = t - tile_m * tiles_n;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
   const bf16_t* A = (const bf16_t*)p.A;
   const bf16_t* B = (const bf16_t*)p.B;
-  f32x16 acc[2][2];
+  // two register sets (named, never indexed at run time, so they stay in registers)
+  u32x4 ra0[4], rb0[4], ra1[4], rb1[4];
+  auto fetch = [&](u32x4 (&xa)[4], u32x4 (&xb)[4], int kt) {      // k tile kt (relative) -> register set
+    const int k0 = (kt_begin + kt) * BK;
+    if (!EDGE) {
+      TA::load(xa, A, p.lda, m0, k0, tid);
+      TB::load(xb, B, p.ldb, n0, k0, tid);
+    } else {
+      const typename TA::Regs ea = TA::load_edge(A, p.lda, p.M, p.K, m0, k0, tid);
+      const typename TB::Regs eb = TB::load_edge(B, p.ldb, p.N, p.K, n0, k0, tid);
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  const int nk = (p.K + BK - 1) / BK;
-  const bool rows_in = m0 + BM <= p.M && n0 + BN <= p.N;
-  const bool do_rowsum = p.a_rowsum && tile_n == 0;
-  float rs = 0.f;
-  uint4 sa[4], sb[4];
-  {
-    const bool interior = rows_in && BK <= p.K;
-    TA::load(sa, A, p.lda, p.M, p.K, m0, 0, tid, interior);
-    TB::load(sb, B, p.ldb, p.N, p.K, n0, 0, tid, interior);
-    TA::store(sa, As, tid);
-    TB::store(sb, Bs, tid);
-  }
-  __syncthreads();
-
-  for (int kt = 0; kt < nk; ++kt) {
-    const bf16_t* at = As + (kt & 1) * TA::ELEMS;
-    const bf16_t* bt = Bs + (kt & 1) * TB::ELEMS;
-    const bool more = kt + 1 < nk;
-    if (more) {
-      const int k0 = (kt + 1) * BK;
-      const bool interior = rows_in && k0 + BK <= p.K;
-      TA::load(sa, A, p.lda, p.M, p.K, m0, k0, tid, interior);
-      TB::load(sb, B, p.ldb, p.N, p.K, n0, k0, tid, interior);
+      for (int i = 0; i < 4; ++i) { xa[i] = ea.v[i]; xb[i] = eb.v[i]; }
     }
+  };
+  auto stash = [&](const u32x4 (&xa)[4], const u32x4 (&xb)[4], int buf) {
+    TA::store(xa, As + buf * TA::ELEMS, tid);
+    TB::store(xb, Bs + buf * TB::ELEMS, tid);
+  };
+  auto compute = [&](int buf) {
+    const bf16_t* at = As + buf * TA::ELEMS;
+    const bf16_t* bt = Bs + buf * TB::ELEMS;
     if (do_rowsum) rs += TA::rowsum_part(at, tid);
+    __builtin_amdgcn_iglp_opt(0);
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       bf16x8 af[2], bfr[2];
@@ -282,11 +282,111 @@ __global__ __launch_bounds__(256, 2) void bgemm_kernel(GemmDev p, int tiles_n, i
         for (int j = 0; j < 2; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
     }
-    if (more) {
-      TA::store(sa, As + ((kt + 1) & 1) * TA::ELEMS, tid);
-      TB::store(sb, Bs + ((kt + 1) & 1) * TB::ELEMS, tid);
-    }
+  };
+  if (nk <= 0) return;
+  fetch(ra0, rb0, 0);
+  stash(ra0, rb0, 0);
+  if (nk > 1) fetch(ra1, rb1, 1);
+  __syncthreads();
+  int kt = 0;
+  // steady state: every fetch is unconditional, so the wait before a stash only covers the
+  // older register set and the newer loads stay in flight across the MFMAs
+  for (; kt + 3 < nk; kt += 2) {
+    fetch(ra0, rb0, kt + 2);
+    compute(0);
+    stash(ra1, rb1, 1);
     __syncthreads();
+    fetch(ra1, rb1, kt + 3);
+    compute(1);
+    stash(ra0, rb0, 0);
+    __syncthreads();
+  }
+  // one to three tiles left: buffer 0 holds tile kt, set 1 holds tile kt+1 (if any)
+  if (kt + 2 < nk) fetch(ra0, rb0, kt + 2);
+  compute(0);
+  if (kt + 1 < nk) {
+    stash(ra1, rb1, 1);
+    __syncthreads();
+    compute(1);
+    if (kt + 2 < nk) {
+      stash(ra0, rb0, 0);
+      __syncthreads();
+      compute(0);
+    }
+  }
+}
+
+// Grid: one-dimensional, 8 * ceil(units/8) blocks, a unit being (tile, k split).  Hardware hands
+// consecutive block ids to the 8 XCDs in turn, so block id -> (xcd, slot) -> unit xcd*per + slot
+// gives every XCD (and its L2) a contiguous run of tiles that share A row panels.
+//
+// Pipeline: global loads run two k tiles ahead of the MFMAs (two register sets), LDS holds two
+// tiles; one barrier per k tile.
+template <bool AK, bool BKM, bool VEC>
+__global__ __launch_bounds__(256, 2) void bgemm_kernel(GemmDev p, int tiles_n, int total, int per_xcd) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  typedef Tile<AK> TA;
+  typedef Tile<BKM> TB;
+  bf16_t* As = (bf16_t*)smem_raw;                    // two buffers of TA::ELEMS
+  bf16_t* Bs = As + 2 * TA::ELEMS;                   // two buffers of TB::ELEMS
+  const int unit = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (unit >= total) return;
+  const int t = unit / p.splits, split = unit - t * p.splits;
+  const int tile_m = t / tiles_n, tile_n = t - tile_m * tiles_n;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const bf16_t* A = (const bf16_t*)p.A;
+  const bf16_t* B = (const bf16_t*)p.B;
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // this block's k tiles: [kt_begin, kt_begin + nk)
+  const int nk_all = (p.K + BK - 1) / BK;
+  const int per_split = (nk_all + p.splits - 1) / p.splits;
+  const int kt_begin = split * per_split;
+  const int nk = max(0, min(nk_all, kt_begin + per_split) - kt_begin);
+  const bool do_rowsum = p.a_rowsum && tile_n == 0;
+  float rs = 0.f;
+  // tiles fully inside the matrices take the loop without any bounds logic
+  if (m0 + BM <= p.M && n0 + BN <= p.N && p.K % BK == 0)
+    mainloop<AK, BKM, false>(p, As, Bs, m0, n0, kt_begin, nk, tid, lane, wm, wn, do_rowsum, acc, rs);
+  else
+    mainloop<AK, BKM, true>(p, As, Bs, m0, n0, kt_begin, nk, tid, lane, wm, wn, do_rowsum, acc, rs);
+
+  if (p.splits > 1) {
+    // raw fp32 tile and row sums of this k range; a second kernel adds the parts in order
+    float* part = p.partial + (int64_t)split * p.M * p.N;
+    float* rpart = p.partial + (int64_t)p.splits * p.M * p.N + (int64_t)split * p.M;
+    if (do_rowsum) {
+      const float tot = rs + __shfl_xor(rs, 1, 64);
+      const int m = m0 + (tid >> 1);
+      if ((tid & 1) == 0 && m < p.M) rpart[m] = tot;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int m = m0 + wm * 64 + i * 32 + (lane & 31);
+          const int n = n0 + wn * 64 + j * 32 + 8 * g + 4 * (lane >> 5);
+          if (m < p.M) {
+            float* dst = part + (int64_t)m * p.N + n;
+            if (n + 4 <= p.N && (p.N & 3) == 0) {
+              *(float4*)dst = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+            } else {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) if (n + e < p.N) dst[e] = acc[i][j][4 * g + e];
+            }
+          }
+        }
+    return;
   }
 
   if (do_rowsum) {
@@ -307,6 +407,53 @@ __global__ __launch_bounds__(256, 2) void bgemm_kernel(GemmDev p, int tiles_n, i
       }
 }
 
+// C[m][n] = sum over splits (in order) of partial tiles; row sums likewise.  fp32 output only.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, float* __restrict__ C,
+                                                            int64_t ldc, float* __restrict__ rowsum, int M, int N,
+                                                            int splits) {
+  const int64_t MN = (int64_t)M * N;
+  const int64_t idx = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (idx < MN) {
+    const int m = (int)(idx / N), n = (int)(idx - (int64_t)m * N);
+    if ((N & 3) == 0) {
+      float4 s = *(const float4*)(partial + idx);
+      for (int k = 1; k < splits; ++k) {
+        const float4 v = *(const float4*)(partial + k * MN + idx);
+        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+      }
+      float* dst = C + (int64_t)m * ldc + n;
+      dst[0] = s.x; dst[1] = s.y; dst[2] = s.z; dst[3] = s.w;
+    } else {
+      for (int e = 0; e < 4 && idx + e < MN; ++e) {
+        const int64_t q = idx + e;
+        float s2 = partial[q];
+        for (int k = 1; k < splits; ++k) s2 += partial[k * MN + q];
+        const int mm = (int)(q / N), nn = (int)(q - (int64_t)mm * N);
+        C[(int64_t)mm * ldc + nn] = s2;
+      }
+    }
+  }
+  if (rowsum && idx < M) {       // the first M/4 threads also finish the row sums
+    const float* rp = partial + (int64_t)splits * MN;
+    for (int e = 0; e < 4 && idx + e < M; ++e) {
+      float s2 = rp[idx + e];
+      for (int k = 1; k < splits; ++k) s2 += rp[(int64_t)k * M + idx + e];
+      rowsum[idx + e] = s2;
+    }
+  }
+}
+
+int gemm_splits(int M, int N) {
+  const int tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+  int s = (256 + tiles - 1) / tiles;
+  return s < 1 ? 1 : (s > 8 ? 8 : s);
+}
+
+size_t gemm_workspace_bytes(int M, int N) {
+  const int s = gemm_splits(M, N);
+  return s > 1 ? ((size_t)s * M * N + (size_t)s * M) * 4 : 0;
+}
+
 template <bool AK, bool BKM, bool VEC>
 static void launch_bgemm(const GemmDev& p, hipStream_t st) {
   constexpr int smem = 2 * (Tile<AK>::ELEMS + Tile<BKM>::ELEMS) * 2;
@@ -316,8 +463,13 @@ static void launch_bgemm(const GemmDev& p, hipStream_t st) {
     configured = true;
   }
   const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-  const int total = tiles_m * tiles_n, per = (total + 7) / 8;
+  const int total = tiles_m * tiles_n * p.splits, per = (total + 7) / 8;
   hipLaunchKernelGGL((bgemm_kernel<AK, BKM, VEC>), dim3(per * 8), dim3(256), smem, st, p, tiles_n, total, per);
+  if (p.splits > 1) {
+    const int64_t MN = (int64_t)p.M * p.N;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((MN / 4 + 256) / 256)), dim3(256), 0, st, p.partial,
+                       (float*)p.C, p.ldc, p.a_rowsum, p.M, p.N, p.splits);
+  }
 }
 
 static bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
@@ -329,6 +481,7 @@ bool gemm(int dtype, const GemmArgs& g, hipStream_t st) {
   p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc; p.ldr = g.ldr;
   p.M = g.M; p.N = g.N; p.K = g.K;
   p.a_k = g.a_kmajor; p.b_k = g.b_kmajor; p.c_f32 = g.c_f32; p.gelu = g.gelu;
+  p.splits = 1; p.partial = nullptr;
   if (p.gelu && (p.c_f32 || !p.gelu_out)) return false;
   if (dtype == F32) {
     dim3 grid((g.N + 63) / 64, (g.M + 63) / 64);
@@ -336,6 +489,15 @@ bool gemm(int dtype, const GemmArgs& g, hipStream_t st) {
     return true;
   }
   if ((g.lda & 7) || (g.ldb & 7) || !aligned16(g.A) || !aligned16(g.B)) return false;
+  // few output tiles and a long reduction (weight gradients): cut k so the whole chip works
+  if (g.workspace && g.c_f32 && !g.bias && !g.resid && !g.gelu && aligned16(g.workspace)) {
+    const int want = gemm_splits(g.M, g.N), by_k = (g.K + 4 * BK - 1) / (4 * BK);   // >= 4 k tiles per part
+    const int sp = want < by_k ? want : by_k;
+    if (sp > 1 && g.workspace_bytes >= ((size_t)sp * g.M * g.N + (size_t)sp * g.M) * 4) {
+      p.splits = sp;
+      p.partial = (float*)g.workspace;
+    }
+  }
   // vector epilogue: four consecutive columns per access
   const int cshift = g.c_f32 ? 15 : 7;
   const bool vec = (g.ldc & 3) == 0 && (((uintptr_t)g.C) & cshift) == 0 &&

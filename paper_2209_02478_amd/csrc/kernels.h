@@ -24,7 +24,13 @@ struct GemmArgs {
   void* gelu_out = nullptr;        // [M, ldc], storage dtype
   int gelu = GELU_NONE;
   float* a_rowsum = nullptr;       // [M] fp32: sum_k A(m,k) (bias gradient of a weight-gradient product)
+  void* workspace = nullptr;       // optional scratch of gemm_workspace_bytes(M, N) for split reductions
+  size_t workspace_bytes = 0;
 };
+
+// scratch that lets a bf16 product with fp32 output cut its reduction in parts (0: never splits);
+// a function of the output shape alone
+size_t gemm_workspace_bytes(int M, int N);
 
 // returns false when the arguments violate the kernel's alignment assumptions
 bool gemm(int dtype, const GemmArgs& g, hipStream_t st);

@@ -14,6 +14,7 @@
 #include <cstring>
 #include <memory>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "../../include/mimose.h"
@@ -237,6 +238,22 @@ class Step {
   void wgrad(const void* dY, int64_t ldy, int out, const void* X, int in, int wi, int bi) {
     mk::GemmArgs a{dY, ldy, false, X, in, false, g(wi), in, true, out, in, T_};
     a.a_rowsum = bi >= 0 ? g(bi) : nullptr;
+    with_workspace(a);
+  }
+  // Weight-gradient products may cut their reduction in parts; the scratch for that is taken
+  // once per layer backward / head (a size fixed by the weight shapes), so that every
+  // component of the step's memory stays a polynomial of the input size.
+  void* ws_ = nullptr;
+  size_t ws_bytes_ = 0;
+  void reserve_workspace(std::initializer_list<std::pair<int, int>> shapes) {
+    size_t need = 0;
+    if (dt_ == mk::BF16)
+      for (auto& s : shapes) need = std::max(need, mk::gemm_workspace_bytes(s.first, s.second));
+    ws_ = need ? c_->arena.alloc(need) : nullptr;
+    ws_bytes_ = need;
+  }
+  void with_workspace(mk::GemmArgs& a) {
+    a.workspace = ws_; a.workspace_bytes = ws_bytes_;
     gemm(a);
   }
   void ln_fwd(const void* x, int gi, int bi, void* y) {
@@ -347,6 +364,7 @@ void Step::layer_backward(int l, LayerActs& A) {
   const int H = f_.hidden, F = f_.ffn, nh = f_.n_heads, d = H / nh;
   const int64_t TH = (int64_t)T_ * H, TF = (int64_t)T_ * F;
   Arena& ar = c_->arena;
+  reserve_workspace({{H, F}, {F, H}, {H, H}, {3 * H, H}});
   const uint64_t m0 = ar.top();
   if (!f_.pre_ln) ln_bwd(dA_, A.s2, p.ln2g, p.ln2b, dA_, nullptr);           // dA = d s2
   wgrad(dA_, H, H, A.act, F, p.w2, p.b2);
@@ -393,6 +411,7 @@ void Step::head(float* loss_dev) {
   const int64_t TH = (int64_t)T_ * H, ldv = c_->ldv();
   const int gelu = f_.gelu_tanh ? mk::GELU_TANH : mk::GELU_ERF;
   const void* hlast = f_.n_layers ? c_->acts[f_.n_layers - 1].out : h0_;
+  reserve_workspace({{V, H}, {H, H}});
   const void* hs = hlast;
   void* hs_buf = nullptr;
   if (f_.pre_ln) { hs_buf = talloc(TH); ln_fwd(hlast, c_->i_fg, c_->i_fb, hs_buf); hs = hs_buf; }
@@ -420,7 +439,7 @@ void Step::head(float* loss_dev) {
   {
     mk::GemmArgs a{logits, ldv, false, dec_in, H, false, g(c_->i_tok), H, true, V, H, T_};
     a.a_rowsum = f_.head ? g(c_->i_bdec) : nullptr;
-    gemm(a);
+    with_workspace(a);
   }
   void* dhs = f_.pre_ln ? talloc(TH) : dA_;
   if (f_.head) {

@@ -15,13 +15,18 @@ extern "C" {
 int mimose_op_gemm(int32_t dtype, const void* A, int64_t lda, int32_t a_kmajor, const void* B, int64_t ldb,
                    int32_t b_kmajor, void* C, int64_t ldc, int32_t c_f32, int32_t M, int32_t N, int32_t K,
                    const void* bias, const void* resid, int64_t ldr, void* gelu_out, int32_t gelu,
-                   float* a_rowsum, void* stream) {
+                   float* a_rowsum, void* workspace, uint64_t workspace_bytes, void* stream) {
   if (bad_dtype(dtype) || !A || !B || !C || M < 0 || N < 0 || K < 0 || gelu < 0 || gelu > 2) return MIMOSE_ERR_INVALID_ARG;
   if (lda < (a_kmajor ? K : M) || ldb < (b_kmajor ? K : N) || ldc < N || (resid && ldr < N)) return MIMOSE_ERR_INVALID_ARG;
   mk::GemmArgs g{A, lda, a_kmajor != 0, B, ldb, b_kmajor != 0, C, ldc, c_f32 != 0, M, N, K};
   g.bias = bias; g.resid = resid; g.ldr = ldr; g.gelu_out = gelu_out; g.gelu = gelu; g.a_rowsum = a_rowsum;
+  g.workspace = workspace; g.workspace_bytes = workspace_bytes;
   if (!mk::gemm(dtype, g, (hipStream_t)stream)) return MIMOSE_ERR_INVALID_ARG;
   return done();
+}
+
+uint64_t mimose_op_gemm_workspace_bytes(int32_t M, int32_t N) {
+  return M > 0 && N > 0 ? mk::gemm_workspace_bytes(M, N) : 0;
 }
 
 int mimose_op_layernorm_fwd(int32_t dtype, const void* x, const void* gamma, const void* beta, void* y, int32_t T,

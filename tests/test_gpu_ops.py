@@ -92,6 +92,19 @@ def test_gemm_epilogues(dtype):
     sync()
     close(host(W), quant(dY, dtype).T @ quant(X, dtype), 0, k=20.0)
     close(host(rs), quant(dY, dtype).sum(0), 0, k=20.0)
+    # the same product with the reduction cut in parts (long reduction, few output tiles)
+    T = 2000
+    dY = rng.standard_normal((T, M)).astype(np.float32)
+    X = rng.standard_normal((T, N)).astype(np.float32)
+    ddY, dX = dev(dY, dtype), dev(X, dtype)
+    nws = mi.mimose_op_gemm_workspace_bytes(M, N)
+    assert nws > 0                                             # ignored by the fp32 kernel
+    ws = torch.zeros(max(nws, 16), dtype=torch.uint8, device=DEV)
+    W.fill_(9.0); rs.fill_(9.0)
+    mi.mimose_op_gemm(dtype, ddY, M, 0, dX, N, 0, W, N, 1, M, N, T, a_rowsum=rs, workspace=ws, workspace_bytes=nws)
+    sync()
+    close(host(W), quant(dY, dtype).T @ quant(X, dtype), 0, k=40.0)
+    close(host(rs), quant(dY, dtype).sum(0), 0, k=40.0)
 
 
 def test_gemm_rejects_misaligned_bf16():
