@@ -44,6 +44,21 @@ __device__ __forceinline__ float wave_max(float v) {
 __device__ __forceinline__ float gelu_erf(float x) {
   return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
 }
+// erf by the rational approximation of Abramowitz & Stegun 7.1.26 (absolute error < 1.5e-7),
+// one exponential and one reciprocal: used where the result is rounded to bf16 anyway
+__device__ __forceinline__ float erf_as(float x) {
+  const float ax = fabsf(x);
+  const float t = __frcp_rn(fmaf(0.3275911f, ax, 1.0f));
+  float p = fmaf(t, 1.061405429f, -1.453152027f);
+  p = fmaf(t, p, 1.421413741f);
+  p = fmaf(t, p, -0.284496736f);
+  p = fmaf(t, p, 0.254829592f);
+  const float r = 1.0f - p * t * __expf(-ax * ax);
+  return copysignf(r, x);
+}
+__device__ __forceinline__ float gelu_erf_bf16(float x) {
+  return 0.5f * x * (1.0f + erf_as(x * 0.70710678118654752440f));
+}
 __device__ __forceinline__ float gelu_tanh(float x) {
   const float c = 0.79788456080286535588f;
   return 0.5f * x * (1.0f + tanhf(c * (x + 0.044715f * x * x * x)));

@@ -226,7 +226,7 @@ __device__ __forceinline__ void epilogue4(const GemmDev& p, int m, int n, float 
   if (p.gelu) {
     float g[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) g[e] = p.gelu == GELU_TANH ? gelu_tanh(v[e]) : gelu_erf(v[e]);
+    for (int e = 0; e < 4; ++e) g[e] = p.gelu == GELU_TANH ? gelu_tanh(v[e]) : gelu_erf_bf16(v[e]);
     w.x = (uint32_t)f32_to_bf16(g[0]) | ((uint32_t)f32_to_bf16(g[1]) << 16);
     w.y = (uint32_t)f32_to_bf16(g[2]) | ((uint32_t)f32_to_bf16(g[3]) << 16);
     *(uint2*)((bf16_t*)p.gelu_out + o) = w;

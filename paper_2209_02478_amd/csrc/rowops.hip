@@ -6,6 +6,8 @@
 // Column reductions over rows (LayerNorm's dgamma/dbeta) are two-stage with a row ->
 // chunk mapping fixed by the shape, so they are reproducible bit for bit (no atomics).
 #include "device_common.h"
+#include <initializer_list>
+
 #include "kernels.h"
 
 namespace mk {
@@ -137,6 +139,187 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
   }
 }
 
+// ---------------------------------------------------------------- vectorised row access
+// 16-byte chunks: 8 bf16 or 4 fp32 per lane and access; lane l owns chunks l, l+64, ...
+template <typename T> struct Chunk;
+template <> struct Chunk<bf16_t> {
+  static constexpr int N = 8;
+  static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[8]) {
+    const uint4 u = *(const uint4*)p;
+    v[0] = __uint_as_float(u.x << 16); v[1] = __uint_as_float(u.x & 0xFFFF0000u);
+    v[2] = __uint_as_float(u.y << 16); v[3] = __uint_as_float(u.y & 0xFFFF0000u);
+    v[4] = __uint_as_float(u.z << 16); v[5] = __uint_as_float(u.z & 0xFFFF0000u);
+    v[6] = __uint_as_float(u.w << 16); v[7] = __uint_as_float(u.w & 0xFFFF0000u);
+  }
+  static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[8]) {
+    uint4 u;
+    u.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+    u.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+    u.z = (uint32_t)f32_to_bf16(v[4]) | ((uint32_t)f32_to_bf16(v[5]) << 16);
+    u.w = (uint32_t)f32_to_bf16(v[6]) | ((uint32_t)f32_to_bf16(v[7]) << 16);
+    *(uint4*)p = u;
+  }
+};
+template <> struct Chunk<float> {
+  static constexpr int N = 4;
+  static __device__ __forceinline__ void load(const float* p, float (&v)[4]) {
+    const float4 u = *(const float4*)p;
+    v[0] = u.x; v[1] = u.y; v[2] = u.z; v[3] = u.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float (&v)[4]) {
+    *(float4*)p = make_float4(v[0], v[1], v[2], v[3]);
+  }
+};
+
+// mean and 1/std of a row held as NC chunks per lane (chunks >= nchunks hold zeros)
+template <int NC, int E>
+__device__ __forceinline__ void chunk_stats(const float (&v)[NC][E], int nchunks, int lane, int H, float eps,
+                                            float& mean, float& rstd) {
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NC; ++i)
+#pragma unroll
+    for (int e = 0; e < E; ++e) s += v[i][e];
+  mean = wave_sum(s) / (float)H;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < NC; ++i)
+    if (lane + 64 * i < nchunks)
+#pragma unroll
+      for (int e = 0; e < E; ++e) { const float d = v[i][e] - mean; q += d * d; }
+  rstd = rsqrtf(wave_sum(q) / (float)H + eps);
+}
+
+template <typename T, int NC>
+__global__ __launch_bounds__(256) void ln_fwd_vec_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
+                                                         const T* __restrict__ beta, T* __restrict__ y, int Trows,
+                                                         int H, float eps) {
+  constexpr int E = Chunk<T>::N;
+  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= Trows) return;
+  const int nchunks = H / E;
+  const T* xr = x + (int64_t)row * H;
+  float v[NC][E];
+#pragma unroll
+  for (int i = 0; i < NC; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nchunks) Chunk<T>::load(xr + c * E, v[i]);
+    else
+#pragma unroll
+      for (int e = 0; e < E; ++e) v[i][e] = 0.f;
+  }
+  float mean, rstd;
+  chunk_stats<NC, E>(v, nchunks, lane, H, eps, mean, rstd);
+  T* yr = y + (int64_t)row * H;
+#pragma unroll
+  for (int i = 0; i < NC; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nchunks) {
+      float g[E], b[E], o[E];
+      Chunk<T>::load(gamma + c * E, g);
+      Chunk<T>::load(beta + c * E, b);
+#pragma unroll
+      for (int e = 0; e < E; ++e) o[e] = (v[i][e] - mean) * rstd * g[e] + b[e];
+      Chunk<T>::store(yr + c * E, o);
+    }
+  }
+}
+
+// Backward: block = 4 waves = kRowsPerChunk rows, every wave takes 4 rows and issues all their
+// loads before any arithmetic.  Same outputs and the same summation order as ln_bwd_kernel.
+template <typename T, int NC>
+__global__ __launch_bounds__(256) void ln_bwd_vec_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                         const T* __restrict__ gamma, T* __restrict__ dx,
+                                                         const T* __restrict__ add, float* __restrict__ partial,
+                                                         int Trows, int H, float eps) {
+  constexpr int E = Chunk<T>::N;
+  constexpr int R = kRowsPerChunk / 4;
+  __shared__ float red[4][2][64 * NC * E];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nchunks = H / E;
+  float g[NC][E], sg[NC][E], sb[NC][E];
+#pragma unroll
+  for (int i = 0; i < NC; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nchunks) Chunk<T>::load(gamma + c * E, g[i]);
+#pragma unroll
+    for (int e = 0; e < E; ++e) { if (c >= nchunks) g[i][e] = 0.f; sg[i][e] = 0.f; sb[i][e] = 0.f; }
+  }
+  float v[R][NC][E], d[R][NC][E];
+#pragma unroll
+  for (int rr = 0; rr < R; ++rr) {
+    const int row = blockIdx.x * kRowsPerChunk + rr * 4 + wave;
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+      const int c = lane + 64 * i;
+      if (row < Trows && c < nchunks) {
+        Chunk<T>::load(x + (int64_t)row * H + c * E, v[rr][i]);
+        Chunk<T>::load(dy + (int64_t)row * H + c * E, d[rr][i]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < E; ++e) { v[rr][i][e] = 0.f; d[rr][i][e] = 0.f; }
+      }
+    }
+  }
+#pragma unroll
+  for (int rr = 0; rr < R; ++rr) {
+    const int row = blockIdx.x * kRowsPerChunk + rr * 4 + wave;
+    if (row >= Trows) break;
+    float mean, rstd;
+    chunk_stats<NC, E>(v[rr], nchunks, lane, H, eps, mean, rstd);
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NC; ++i)
+      if (lane + 64 * i < nchunks)
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          const float xh = (v[rr][i][e] - mean) * rstd;
+          v[rr][i][e] = xh;
+          sg[i][e] += d[rr][i][e] * xh;
+          sb[i][e] += d[rr][i][e];
+          const float dxh = d[rr][i][e] * g[i][e];
+          d[rr][i][e] = dxh;
+          s1 += dxh;
+          s2 += dxh * xh;
+        }
+    s1 = wave_sum(s1) / (float)H;
+    s2 = wave_sum(s2) / (float)H;
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nchunks) {
+        float o[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[e] = rstd * (d[rr][i][e] - s1 - v[rr][i][e] * s2);
+        if (add) {
+          float a[E];
+          Chunk<T>::load(add + (int64_t)row * H + c * E, a);
+#pragma unroll
+          for (int e = 0; e < E; ++e) o[e] += a[e];
+        }
+        Chunk<T>::store(dx + (int64_t)row * H + c * E, o);
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NC; ++i)
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      red[wave][0][(lane + 64 * i) * E + e] = sg[i][e];
+      red[wave][1][(lane + 64 * i) * E + e] = sb[i][e];
+    }
+  __syncthreads();
+  float* prow = partial + (int64_t)blockIdx.x * 2 * H;
+  for (int c = threadIdx.x; c < 2 * H; c += 256) {
+    const int which = c / H, col = c - which * H;
+    float s = red[0][which][col];
+    s += red[1][which][col];
+    s += red[2][which][col];
+    s += red[3][which][col];
+    prow[c] = s;
+  }
+}
+
 // ---------------------------------------------------------------- GELU backward (in place)
 template <typename T>
 __global__ __launch_bounds__(256) void gelu_bwd_scalar_kernel(T* __restrict__ d, const T* __restrict__ pre,
@@ -210,6 +393,71 @@ __global__ __launch_bounds__(256) void xent_kernel(T* __restrict__ logits, int64
     float g = 0.f;
     if (c < V) g = (__expf(ld<T>(lr + c) - lse) - (c == label ? 1.f : 0.f)) * scale;
     st<T>(lr + c, g);
+  }
+}
+
+// bf16 rows of up to 16 * THREADS 16-byte chunks: the row is read once, kept in registers as
+// fp32, and written once.
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void xent_bf16_kernel(bf16_t* __restrict__ logits, int64_t ldl,
+                                                            const int32_t* __restrict__ labels,
+                                                            float* __restrict__ row_loss, int V, float inv_n) {
+  constexpr int NCH = 16, NW = THREADS / 64;
+  __shared__ float sm[NW], ss[NW];
+  const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  bf16_t* lr = logits + (int64_t)row * ldl;
+  const int label = labels[row];
+  const float picked = (tid == 0 && label >= 0) ? bf16_to_f32(lr[label]) : 0.f;
+  const int nchunks = (int)(ldl / 8);
+  float v[NCH][8];
+  float m = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = tid + THREADS * i;
+    if (c < nchunks) {
+      Chunk<bf16_t>::load(lr + c * 8, v[i]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if (c * 8 + e >= V) v[i][e] = -INFINITY;
+        m = fmaxf(m, v[i][e]);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[i][e] = -INFINITY;
+    }
+  }
+  m = wave_max(m);
+  if (lane == 0) sm[wave] = m;
+  __syncthreads();
+  float bm = sm[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) bm = fmaxf(bm, sm[w]);
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s += __expf(v[i][e] - bm);
+  s = wave_sum(s);
+  if (lane == 0) ss[wave] = s;
+  __syncthreads();
+  float bs = 0.f;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) bs += ss[w];
+  const float lse = bm + __logf(bs);
+  if (tid == 0) row_loss[row] = label >= 0 ? lse - picked : 0.f;
+  const float scale = label >= 0 ? inv_n : 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = tid + THREADS * i;
+    if (c < nchunks) {
+      float g[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int col = c * 8 + e;
+        g[e] = col < V ? (__expf(v[i][e] - lse) - (col == label ? 1.f : 0.f)) * scale : 0.f;
+      }
+      Chunk<bf16_t>::store(lr + c * 8, g);
+    }
   }
 }
 
@@ -320,10 +568,27 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* __restrict__ p
     else { M(16); }                             \
   } while (0)
 
+// rows whose length is a whole number of 16-byte chunks and whose storage is 16-byte aligned
+template <typename T>
+static bool vec_ok(int H, std::initializer_list<const void*> ptrs) {
+  if (H % Chunk<T>::N) return false;
+  for (const void* p : ptrs) if (p && (((uintptr_t)p) & 15)) return false;
+  return true;
+}
+
 template <typename T>
 static void ln_fwd_t(const void* x, const void* g, const void* b, void* y, int T_, int H, float eps,
                      hipStream_t st) {
   dim3 grid((T_ + 3) / 4);
+  if (vec_ok<T>(H, {x, g, b, y})) {
+    const int nc = (H / Chunk<T>::N + 63) / 64;
+#define V_(NC) hipLaunchKernelGGL((ln_fwd_vec_kernel<T, NC>), grid, dim3(256), 0, st, (const T*)x, (const T*)g, \
+                                   (const T*)b, (T*)y, T_, H, eps)
+    if (nc <= 1) { V_(1); return; }
+    if (nc <= 2) { V_(2); return; }
+    if (nc <= 4) { V_(4); return; }
+#undef V_
+  }
 #define M_(NPL) hipLaunchKernelGGL((ln_fwd_kernel<T, NPL>), grid, dim3(256), 0, st, (const T*)x, (const T*)g, \
                                    (const T*)b, (T*)y, T_, H, eps)
   DISPATCH_NPL(H, M_);
@@ -340,6 +605,14 @@ template <typename T>
 static void ln_bwd_t(const void* dy, const void* x, const void* g, void* dx, const void* add, float* partial,
                      int T_, int H, float eps, hipStream_t st) {
   dim3 grid((T_ + kRowsPerChunk - 1) / kRowsPerChunk);
+  if (vec_ok<T>(H, {dy, x, g, dx, add})) {
+    const int nc = (H / Chunk<T>::N + 63) / 64;
+#define V_(NC) hipLaunchKernelGGL((ln_bwd_vec_kernel<T, NC>), grid, dim3(256), 0, st, (const T*)dy, (const T*)x, \
+                                   (const T*)g, (T*)dx, (const T*)add, partial, T_, H, eps)
+    if (nc <= 1) { V_(1); return; }
+    if (nc <= 2) { V_(2); return; }
+#undef V_
+  }
 #define M_(NPL) hipLaunchKernelGGL((ln_bwd_kernel<T, NPL>), grid, dim3(256), 0, st, (const T*)dy, (const T*)x, \
                                    (const T*)g, (T*)dx, (const T*)add, partial, T_, H, eps)
   DISPATCH_NPL(H, M_);
@@ -367,7 +640,13 @@ void softmax_xent(int dtype, void* logits, int64_t ldl, const int32_t* labels, f
                   int T_, int V, int n_valid, hipStream_t st) {
   if (T_ <= 0) return;
   float inv_n = 1.0f / (float)(n_valid > 0 ? n_valid : 1);
-  if (dtype == BF16) hipLaunchKernelGGL(xent_kernel<bf16_t>, dim3(T_), dim3(256), 0, st, (bf16_t*)logits, ldl, labels, row_loss, V, inv_n);
+  const int64_t nch = ldl / 8;
+  if (dtype == BF16 && ldl % 8 == 0 && ((((uintptr_t)logits) & 15) == 0) && nch <= 16 * 1024) {
+    bf16_t* lg = (bf16_t*)logits;
+    if (nch <= 16 * 256) hipLaunchKernelGGL(xent_bf16_kernel<256>, dim3(T_), dim3(256), 0, st, lg, ldl, labels, row_loss, V, inv_n);
+    else if (nch <= 16 * 512) hipLaunchKernelGGL(xent_bf16_kernel<512>, dim3(T_), dim3(512), 0, st, lg, ldl, labels, row_loss, V, inv_n);
+    else hipLaunchKernelGGL(xent_bf16_kernel<1024>, dim3(T_), dim3(1024), 0, st, lg, ldl, labels, row_loss, V, inv_n);
+  } else if (dtype == BF16) hipLaunchKernelGGL(xent_kernel<bf16_t>, dim3(T_), dim3(256), 0, st, (bf16_t*)logits, ldl, labels, row_loss, V, inv_n);
   else hipLaunchKernelGGL(xent_kernel<float>, dim3(T_), dim3(256), 0, st, (float*)logits, ldl, labels, row_loss, V, inv_n);
   hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(256), 0, st, row_loss, T_, inv_n, loss);
 }
