@@ -101,6 +101,9 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers
 
 constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int GROUP_M = 8;                      // row panels per tile group
+constexpr int NCH = BK / 16;                    // 16-byte chunks per thread and operand tile
+constexpr int KCH = BK / 8;                     // chunks along k of a k-major row
 constexpr int LDK = BK + 8;        // row stride of a k-major tile [128 rows][64 k] (144 B: conflict-free 16 B reads)
 constexpr int LDM = 128 + 32;      // row stride of an m-major tile [64 k][128 rows] (320 B: conflict-free transposing reads)
 constexpr int TILE_K_ELEMS = 128 * LDK, TILE_M_ELEMS = BK * LDM;
@@ -115,28 +118,28 @@ struct Tile {
   static constexpr int ELEMS = KM ? TILE_K_ELEMS : TILE_M_ELEMS;
 
   static __device__ __forceinline__ void addr(int c, int r0, int k0, int& gr, int& gk) {
-    const int a = KM ? (c >> 3) : (c >> 4);          // slow index within the tile
-    const int f = KM ? (c & 7) * 8 : (c & 15) * 8;   // fast (contiguous) index
+    const int a = KM ? (c / KCH) : (c >> 4);         // slow index within the tile
+    const int f = KM ? (c % KCH) * 8 : (c & 15) * 8; // fast (contiguous) index
     gr = KM ? r0 + a : r0 + f;                       // row (m or n) of the first element
     gk = KM ? k0 + f : k0 + a;                       // reduction index of the first element
   }
   // tile fully inside the matrix: plain 16-byte loads
-  static __device__ __forceinline__ void load(u32x4 (&v)[4], const bf16_t* __restrict__ X, int64_t ldx, int r0, int k0,
+  static __device__ __forceinline__ void load(u32x4 (&v)[NCH], const bf16_t* __restrict__ X, int64_t ldx, int r0, int k0,
                                               int tid) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < NCH; ++i) {
       int gr, gk;
       addr(tid + i * 256, r0, k0, gr, gk);
       v[i] = *(const u32x4*)(KM ? X + (int64_t)gr * ldx + gk : X + (int64_t)gk * ldx + gr);
     }
   }
   // tile crossing an edge: out-of-range elements read as zero
-  struct Regs { u32x4 v[4]; };
+  struct Regs { u32x4 v[NCH]; };
   static __device__ __forceinline__ Regs load_edge(const bf16_t* __restrict__ X, int64_t ldx, int R, int K, int r0,
                                                 int k0, int tid) {
     Regs out;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < NCH; ++i) {
       int gr, gk;
       addr(tid + i * 256, r0, k0, gr, gk);
       const bf16_t* src = KM ? X + (int64_t)gr * ldx + gk : X + (int64_t)gk * ldx + gr;
@@ -158,11 +161,11 @@ struct Tile {
     }
     return out;
   }
-  static __device__ __forceinline__ void store(const u32x4 (&v)[4], bf16_t* tile, int tid) {
+  static __device__ __forceinline__ void store(const u32x4 (&v)[NCH], bf16_t* tile, int tid) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < NCH; ++i) {
       const int c = tid + i * 256;
-      if (KM) *(u32x4*)&tile[(c >> 3) * LDK + (c & 7) * 8] = v[i];
+      if (KM) *(u32x4*)&tile[(c / KCH) * LDK + (c % KCH) * 8] = v[i];
       else *(u32x4*)&tile[(c >> 4) * LDM + (c & 15) * 8] = v[i];
     }
   }
@@ -180,14 +183,14 @@ struct Tile {
   // sum over the tile's 64 reduction indices of row `row` (partial, see caller)
   static __device__ __forceinline__ float rowsum_part(const bf16_t* tile, int tid) {
     float s = 0.f;
-    if (KM) {                       // two threads per row, 32 indices each
-      const bf16_t* src = &tile[(tid >> 1) * LDK + (tid & 1) * 32];
+    if (KM) {                       // two threads per row, half of the k range each
+      const bf16_t* src = &tile[(tid >> 1) * LDK + (tid & 1) * (BK / 2)];
 #pragma unroll
-      for (int e = 0; e < 32; ++e) s += bf16_to_f32(src[e]);
-    } else {                        // two threads per row: even / odd halves of the 64 k rows
-      const bf16_t* src = &tile[(tid & 1) * 32 * LDM + (tid >> 1)];
+      for (int e = 0; e < BK / 2; ++e) s += bf16_to_f32(src[e]);
+    } else {                        // two threads per row: lower / upper half of the k rows
+      const bf16_t* src = &tile[(tid & 1) * (BK / 2) * LDM + (tid >> 1)];
 #pragma unroll
-      for (int e = 0; e < 32; ++e) s += bf16_to_f32(src[e * LDM]);
+      for (int e = 0; e < BK / 2; ++e) s += bf16_to_f32(src[e * LDM]);
     }
     return s;
   }
@@ -244,8 +247,8 @@ __device__ __forceinline__ void mainloop(const GemmDev& p, bf16_t* As, bf16_t* B
   const bf16_t* A = (const bf16_t*)p.A;
   const bf16_t* B = (const bf16_t*)p.B;
   // two register sets (named, never indexed at run time, so they stay in registers)
-  u32x4 ra0[4], rb0[4], ra1[4], rb1[4];
-  auto fetch = [&](u32x4 (&xa)[4], u32x4 (&xb)[4], int kt) {      // k tile kt (relative) -> register set
+  u32x4 ra0[NCH], rb0[NCH], ra1[NCH], rb1[NCH];
+  auto fetch = [&](u32x4 (&xa)[NCH], u32x4 (&xb)[NCH], int kt) {      // k tile kt (relative) -> register set
     const int k0 = (kt_begin + kt) * BK;
     if (!EDGE) {
       TA::load(xa, A, p.lda, m0, k0, tid);
@@ -254,10 +257,10 @@ __device__ __forceinline__ void mainloop(const GemmDev& p, bf16_t* As, bf16_t* B
       const typename TA::Regs ea = TA::load_edge(A, p.lda, p.M, p.K, m0, k0, tid);
       const typename TB::Regs eb = TB::load_edge(B, p.ldb, p.N, p.K, n0, k0, tid);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { xa[i] = ea.v[i]; xb[i] = eb.v[i]; }
+      for (int i = 0; i < NCH; ++i) { xa[i] = ea.v[i]; xb[i] = eb.v[i]; }
     }
   };
-  auto stash = [&](const u32x4 (&xa)[4], const u32x4 (&xb)[4], int buf) {
+  auto stash = [&](const u32x4 (&xa)[NCH], const u32x4 (&xb)[NCH], int buf) {
     TA::store(xa, As + buf * TA::ELEMS, tid);
     TB::store(xb, Bs + buf * TB::ELEMS, tid);
   };
@@ -332,7 +335,13 @@ __global__ __launch_bounds__(256, 2) void bgemm_kernel(GemmDev p, int tiles_n, i
   const int unit = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (unit >= total) return;
   const int t = unit / p.splits, split = unit - t * p.splits;
-  const int tile_m = t / tiles_n, tile_n = t - tile_m * tiles_n;
+  // tiles run down groups of GROUP_M row panels, so the tiles in flight on one XCD cover a
+  // squarish patch of C and share both A and B panels in its L2
+  const int tiles_m = (p.M + BM - 1) / BM;
+  const int group = t / (GROUP_M * tiles_n), first_m = group * GROUP_M;
+  const int gsize = min(tiles_m - first_m, GROUP_M);
+  const int in_group = t - group * GROUP_M * tiles_n;
+  const int tile_m = first_m + in_group % gsize, tile_n = in_group / gsize;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
@@ -491,7 +500,7 @@ bool gemm(int dtype, const GemmArgs& g, hipStream_t st) {
   if ((g.lda & 7) || (g.ldb & 7) || !aligned16(g.A) || !aligned16(g.B)) return false;
   // few output tiles and a long reduction (weight gradients): cut k so the whole chip works
   if (g.workspace && g.c_f32 && !g.bias && !g.resid && !g.gelu && aligned16(g.workspace)) {
-    const int want = gemm_splits(g.M, g.N), by_k = (g.K + 4 * BK - 1) / (4 * BK);   // >= 4 k tiles per part
+    const int want = gemm_splits(g.M, g.N), by_k = (g.K + 255) / 256;   // >= 256 reduction indices per part
     const int sp = want < by_k ? want : by_k;
     if (sp > 1 && g.workspace_bytes >= ((size_t)sp * g.M * g.N + (size_t)sp * g.M) * 4) {
       p.splits = sp;
