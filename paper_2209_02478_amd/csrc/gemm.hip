@@ -15,33 +15,10 @@
 // bit for bit.
 // fp32: a plain 64x64x16 LDS-tiled kernel (small-model configuration only).
 #include "device_common.h"
+#include "gemm_device.h"
 #include "kernels.h"
 
 namespace mk {
-
-struct GemmDev {
-  const void* A; const void* B; void* C;
-  const void* bias; const void* resid; void* gelu_out; float* a_rowsum;
-  int64_t lda, ldb, ldc, ldr;
-  int M, N, K;
-  int a_k, b_k, c_f32, gelu;
-  int splits;            // > 1: k range cut in `splits` parts, raw fp32 tiles go to `partial`
-  float* partial;        // [splits][M][N] followed by [splits][M] row sums
-};
-
-template <typename T>
-__device__ __forceinline__ void epilogue(const GemmDev& p, int m, int n, float v) {
-  if (m >= p.M || n >= p.N) return;
-  if (p.bias) v += ld<T>((const T*)p.bias + n);
-  if (p.resid) v += ld<T>((const T*)p.resid + (int64_t)m * p.ldr + n);
-  int64_t o = (int64_t)m * p.ldc + n;
-  if (p.c_f32) {
-    ((float*)p.C)[o] = v;
-  } else {
-    st<T>((T*)p.C + o, v);
-    if (p.gelu) st<T>((T*)p.gelu_out + o, p.gelu == GELU_TANH ? gelu_tanh(v) : gelu_erf(v));
-  }
-}
 
 // ------------------------------------------------------------------ fp32
 __global__ __launch_bounds__(256) void sgemm_kernel(GemmDev p) {
@@ -95,11 +72,6 @@ __global__ __launch_bounds__(256) void sgemm_kernel(GemmDev p) {
 }
 
 // ------------------------------------------------------------------ bf16 MFMA
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers
-
 constexpr int BM = 128, BN = 128, BK = 64;
 constexpr int GROUP_M = 8;                      // row panels per tile group
 constexpr int NCH = BK / 16;                    // 16-byte chunks per thread and operand tile
@@ -195,46 +167,6 @@ struct Tile {
     return s;
   }
 };
-
-__device__ __forceinline__ void epilogue4_edge(const GemmDev& p, int m, int n, float v0, float v1, float v2, float v3) {
-  epilogue<bf16_t>(p, m, n, v0); epilogue<bf16_t>(p, m, n + 1, v1);
-  epilogue<bf16_t>(p, m, n + 2, v2); epilogue<bf16_t>(p, m, n + 3, v3);
-}
-
-// epilogue for 4 consecutive columns n..n+3 of row m
-template <bool VEC>
-__device__ __forceinline__ void epilogue4(const GemmDev& p, int m, int n, float v0, float v1, float v2, float v3) {
-  if (m >= p.M || n >= p.N) return;
-  if (!VEC || n + 4 > p.N) { epilogue4_edge(p, m, n, v0, v1, v2, v3); return; }
-  float v[4] = {v0, v1, v2, v3};
-  if (p.bias) {
-    const uint2 b = *(const uint2*)((const bf16_t*)p.bias + n);
-    v[0] += __uint_as_float(b.x << 16); v[1] += __uint_as_float(b.x & 0xFFFF0000u);
-    v[2] += __uint_as_float(b.y << 16); v[3] += __uint_as_float(b.y & 0xFFFF0000u);
-  }
-  if (p.resid) {
-    const uint2 b = *(const uint2*)((const bf16_t*)p.resid + (int64_t)m * p.ldr + n);
-    v[0] += __uint_as_float(b.x << 16); v[1] += __uint_as_float(b.x & 0xFFFF0000u);
-    v[2] += __uint_as_float(b.y << 16); v[3] += __uint_as_float(b.y & 0xFFFF0000u);
-  }
-  const int64_t o = (int64_t)m * p.ldc + n;
-  if (p.c_f32) {
-    *(float4*)((float*)p.C + o) = make_float4(v[0], v[1], v[2], v[3]);
-    return;
-  }
-  uint2 w;
-  w.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-  w.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
-  *(uint2*)((bf16_t*)p.C + o) = w;
-  if (p.gelu) {
-    float g[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) g[e] = p.gelu == GELU_TANH ? gelu_tanh(v[e]) : gelu_erf_bf16(v[e]);
-    w.x = (uint32_t)f32_to_bf16(g[0]) | ((uint32_t)f32_to_bf16(g[1]) << 16);
-    w.y = (uint32_t)f32_to_bf16(g[2]) | ((uint32_t)f32_to_bf16(g[3]) << 16);
-    *(uint2*)((bf16_t*)p.gelu_out + o) = w;
-  }
-}
 
 // k loop of one block.  Global loads run two k tiles ahead of the MFMAs (two register sets), LDS
 // holds two tiles, one barrier per k tile.  EDGE: tile crosses a matrix edge or K has a tail.
@@ -463,6 +395,12 @@ size_t gemm_workspace_bytes(int M, int N) {
   return s > 1 ? ((size_t)s * M * N + (size_t)s * M) * 4 : 0;
 }
 
+static void launch_splitk_reduce(const GemmDev& p, hipStream_t st) {
+  const int64_t MN = (int64_t)p.M * p.N;
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((MN / 4 + 256) / 256)), dim3(256), 0, st, p.partial,
+                     (float*)p.C, p.ldc, p.a_rowsum, p.M, p.N, p.splits);
+}
+
 template <bool AK, bool BKM, bool VEC>
 static void launch_bgemm(const GemmDev& p, hipStream_t st) {
   constexpr int smem = 2 * (Tile<AK>::ELEMS + Tile<BKM>::ELEMS) * 2;
@@ -474,12 +412,11 @@ static void launch_bgemm(const GemmDev& p, hipStream_t st) {
   const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
   const int total = tiles_m * tiles_n * p.splits, per = (total + 7) / 8;
   hipLaunchKernelGGL((bgemm_kernel<AK, BKM, VEC>), dim3(per * 8), dim3(256), smem, st, p, tiles_n, total, per);
-  if (p.splits > 1) {
-    const int64_t MN = (int64_t)p.M * p.N;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((MN / 4 + 256) / 256)), dim3(256), 0, st, p.partial,
-                       (float*)p.C, p.ldc, p.a_rowsum, p.M, p.N, p.splits);
-  }
+  if (p.splits > 1) launch_splitk_reduce(p, st);
 }
+
+// direct-to-LDS pipeline (gemm_dma.hip); false when the operands do not meet its alignment rules
+bool launch_bgemm_dma(const GemmDev& p, bool vec, hipStream_t st);
 
 static bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
 
@@ -513,6 +450,12 @@ bool gemm(int dtype, const GemmArgs& g, hipStream_t st) {
                    (!g.resid || ((g.ldr & 3) == 0 && (((uintptr_t)g.resid) & 7) == 0)) &&
                    (!g.bias || (((uintptr_t)g.bias) & 7) == 0) &&
                    (!g.gelu_out || (((uintptr_t)g.gelu_out) & 7) == 0);
+  // both operands m-major (weight gradients): the direct-to-LDS pipeline measures faster there;
+  // the register-staged kernel below is ahead when a k-major operand is involved
+  if (!g.a_kmajor && !g.b_kmajor && launch_bgemm_dma(p, vec, st)) {
+    if (p.splits > 1) launch_splitk_reduce(p, st);
+    return true;
+  }
 #define LAUNCH_(AKV, BKV) do { if (vec) launch_bgemm<AKV, BKV, true>(p, st); else launch_bgemm<AKV, BKV, false>(p, st); } while (0)
   if (g.a_kmajor && g.b_kmajor) LAUNCH_(true, true);
   else if (g.a_kmajor && !g.b_kmajor) LAUNCH_(true, false);

@@ -1,0 +1,292 @@
+// bf16 GEMM with a direct global -> LDS pipeline (gfx950 global_load_lds_dwordx4).
+//
+// C[M,N] = sum_k A(m,k) B(n,k), 128 x 128 x 32 tiles, 4 waves (2 x 2), each wave 64 x 64 as 2 x 2
+// MFMA 32x32x16 tiles.  Operand tiles never pass through registers: every lane asks the memory
+// pipe to drop 16 bytes straight into LDS, four k tiles deep (a ring of four LDS stages, three
+// tiles in flight while one is multiplied), so two blocks per CU keep ~96 KB of loads in flight.
+//
+// A wave-level direct load writes 64 x 16 bytes contiguously, so tiles are stored unpadded and
+// bank conflicts are avoided by permuting 16-byte chunks inside a row (the lane -> global
+// address map is free, so the permutation costs nothing on the way in):
+//   k-major tile [128 rows][32 k], 64 B rows : chunk kc of row r sits at kc ^ ((r >> 2) & 3)
+//   m-major tile [32 k][128 rows], 256 B rows: chunk mc of k row q sits at mc ^ (4 * (q & 3))
+// k-major fragments are one 16-byte read, m-major fragments two transposing 8-byte reads
+// (ds_read_b64_tr_b16).  Elements outside the matrices are fetched from a 16-byte block of
+// zeros, so edge tiles need no special loop.
+//
+// Synchronisation is explicit (no fences): before the barrier of k tile t every wave waits until
+// its own loads of tile t have landed (s_waitcnt vmcnt leaves the two newer tiles in flight);
+// after the barrier all waves have also finished reading the stage of tile t-1, which is then
+// refilled with tile t+3.  The reduction order over k is fixed by the shape alone.
+#include "gemm_device.h"
+
+namespace mk {
+
+namespace {
+
+constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int STAGES = 4;
+constexpr int TILE_ELEMS = 128 * BK;             // either layout: 8 KB
+constexpr int GROUP_M = 8;
+constexpr int DMA_PER_WAVE = TILE_ELEMS * 2 / 1024 / 4;   // 1 KB direct loads per wave and operand tile: 2
+
+__device__ __attribute__((aligned(16))) uint32_t g_zero_chunk[4] = {0u, 0u, 0u, 0u};
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+// s_waitcnt immediate: at most n vector-memory loads outstanding and no LDS operation pending
+// (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14)
+constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (0 << 8) | ((n >> 4) << 14); }
+
+// Per-thread source of one direct load: where its 16 bytes of k tile 0 live, how far to move
+// per k tile, and up to which k tile the address stays inside the matrix.
+struct Src {
+  const bf16_t* p;     // nullptr-free: points at zeros when the row is outside
+  int64_t step;        // elements per k tile (0 for the zero block)
+  int k_first;         // reduction index of this chunk in k tile 0 (for the tail test)
+};
+
+template <bool KM>
+__device__ __forceinline__ Src make_src(const bf16_t* X, int64_t ldx, int R, int r0, int k_begin, int slot) {
+  Src s;
+  int row, kk;      // row index (m or n) and reduction offset inside the tile of this chunk
+  if (KM) {
+    const int r = slot >> 2, pc = slot & 3;
+    row = r0 + r;
+    kk = (pc ^ ((r >> 2) & 3)) * 8;
+    s.p = X + (int64_t)row * ldx + k_begin + kk;
+    s.step = BK;
+  } else {
+    const int q = slot >> 4, pc = slot & 15;
+    row = r0 + (pc ^ (4 * (q & 3))) * 8;
+    kk = q;
+    s.p = X + (int64_t)(k_begin + kk) * ldx + row;
+    s.step = (int64_t)BK * ldx;
+  }
+  s.k_first = k_begin + kk;
+  if (row >= R) { s.p = (const bf16_t*)g_zero_chunk; s.step = 0; s.k_first = -(1 << 30); }
+  return s;
+}
+
+// fragment for tile rows rbase + lane%32, reduction indices 16*ks + 8*(lane/32) .. +7
+template <bool KM>
+__device__ __forceinline__ bf16x8 frag(const bf16_t* tile, int rbase, int ks, int lane) {
+  if (KM) {
+    const int r = rbase + (lane & 31);
+    const int pc = (2 * ks + (lane >> 5)) ^ ((lane >> 2) & 3);     // (r >> 2) & 3 == (lane >> 2) & 3: rbase % 32 == 0
+    return *(const bf16x8*)&tile[r * BK + pc * 8];
+  }
+  const int kq = (lane & 15) >> 2;                                  // k row & 3 of this lane's source rows
+  const int q = ks * 16 + 8 * (lane >> 5) + kq;
+  const int mc = (rbase >> 3) + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+  const int off = (mc ^ (4 * kq)) * 8 + (lane & 1) * 4;
+  struct { s16x4 lo, hi; } r;
+  r.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)&tile[q * 128 + off]);
+  r.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)&tile[(q + 4) * 128 + off]);
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+// sum over the tile's reduction indices of tile row tid/2 (two threads per row, any fixed order)
+template <bool KM>
+__device__ __forceinline__ float rowsum_part(const bf16_t* tile, int tid) {
+  float s = 0.f;
+  const int r = tid >> 1, half = tid & 1;
+  if (KM) {
+    const bf16_t* src = &tile[r * BK + half * (BK / 2)];            // chunk order inside a row is immaterial
+#pragma unroll
+    for (int e = 0; e < BK / 2; ++e) s += bf16_to_f32(src[e]);
+  } else {
+#pragma unroll
+    for (int e = 0; e < BK / 2; ++e) {
+      const int q = half * (BK / 2) + e;
+      s += bf16_to_f32(tile[q * 128 + (((r >> 3) ^ (4 * (q & 3))) * 8) + (r & 7)]);
+    }
+  }
+  return s;
+}
+
+}  // namespace
+
+template <bool AK, bool BKM, bool VEC, bool KTAIL>
+__global__ __launch_bounds__(256, 2) void bgemm_dma_kernel(GemmDev p, int tiles_n, int total, int per_xcd) {
+  // one named array per ring stage (A tile, then B tile): the compiler then knows which direct
+  // loads a read depends on and leaves the newer ones in flight
+  __shared__ __attribute__((aligned(1024))) bf16_t st0[2 * TILE_ELEMS], st1[2 * TILE_ELEMS], st2[2 * TILE_ELEMS],
+      st3[2 * TILE_ELEMS];
+  const int unit = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (unit >= total) return;
+  const int t = unit / p.splits, split = unit - t * p.splits;
+  const int tiles_m = (p.M + BM - 1) / BM;
+  const int group = t / (GROUP_M * tiles_n), first_m = group * GROUP_M;
+  const int gsize = min(tiles_m - first_m, GROUP_M);
+  const int in_group = t - group * GROUP_M * tiles_n;
+  const int tile_m = first_m + in_group % gsize, tile_n = in_group / gsize;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk_all = (p.K + BK - 1) / BK;
+  const int per_split = (nk_all + p.splits - 1) / p.splits;
+  const int kt_begin = split * per_split;
+  const int nk = max(0, min(nk_all, kt_begin + per_split) - kt_begin);
+  const bool do_rowsum = p.a_rowsum && tile_n == 0;
+  float rs = 0.f;
+
+  // this thread's direct loads: wave w issues loads 2w, 2w+1 of each operand tile, lane = slot
+  Src srcA[DMA_PER_WAVE], srcB[DMA_PER_WAVE];
+#pragma unroll
+  for (int j = 0; j < DMA_PER_WAVE; ++j) {
+    const int slot = (wave * DMA_PER_WAVE + j) * 64 + lane;
+    srcA[j] = make_src<AK>((const bf16_t*)p.A, p.lda, p.M, m0, kt_begin * BK, slot);
+    srcB[j] = make_src<BKM>((const bf16_t*)p.B, p.ldb, p.N, n0, kt_begin * BK, slot);
+  }
+  auto issue = [&](bf16_t* stage, int kt) {                           // k tile kt (relative) -> ring stage
+    bf16_t* a_stage = stage;
+    bf16_t* b_stage = stage + TILE_ELEMS;
+#pragma unroll
+    for (int j = 0; j < DMA_PER_WAVE; ++j) {
+      const bf16_t* ga = srcA[j].p + kt * srcA[j].step;
+      const bf16_t* gb = srcB[j].p + kt * srcB[j].step;
+      if (KTAIL) {                                                    // chunks past K read zeros
+        if (srcA[j].k_first + kt * BK >= p.K) ga = (const bf16_t*)g_zero_chunk;
+        if (srcB[j].k_first + kt * BK >= p.K) gb = (const bf16_t*)g_zero_chunk;
+      }
+      const int off = (wave * DMA_PER_WAVE + j) * 512;                // elements: 1 KB per wave-level load
+      __builtin_amdgcn_global_load_lds(ga, (lds_void*)(a_stage + off), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(gb, (lds_void*)(b_stage + off), 16, 0, 0);
+    }
+  };
+  auto compute = [&](const bf16_t* stage) {
+    const bf16_t* at = stage;
+    const bf16_t* bt = stage + TILE_ELEMS;
+    if (do_rowsum) rs += rowsum_part<AK>(at, tid);
+    __builtin_amdgcn_iglp_opt(0);
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 af[2], bfr[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        af[i] = frag<AK>(at, wm * 64 + i * 32, ks, lane);
+        bfr[i] = frag<BKM>(bt, wn * 64 + i * 32, ks, lane);
+      }
+      // roles swapped (B tile rows feed the MFMA's A side): a lane then owns one output row m
+      // and, per register group, four consecutive columns n
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+    }
+  };
+  // One k tile: wait for own loads of tile kt (leaving up to two newer tiles in flight), meet
+  // the other waves, refill the stage that was multiplied last, multiply.
+  constexpr int PER_TILE = 2 * DMA_PER_WAVE;                          // direct loads per thread and k tile
+#define MIMOSE_GEMM_STEP(KT, CUR, FILL)                                                       \
+  {                                                                                           \
+    if ((KT) + 2 < nk) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * PER_TILE));                   \
+    else if ((KT) + 1 < nk) __builtin_amdgcn_s_waitcnt(vmcnt_imm(PER_TILE));                  \
+    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                                            \
+    __builtin_amdgcn_s_barrier();                                                             \
+    if ((KT) + 3 < nk) issue(FILL, (KT) + 3);                                                 \
+    compute(CUR);                                                                             \
+  }
+
+  if (nk > 0) {
+    issue(st0, 0);
+    if (nk > 1) issue(st1, 1);
+    if (nk > 2) issue(st2, 2);
+    for (int kt = 0; kt < nk; kt += 4) {
+      MIMOSE_GEMM_STEP(kt, st0, st3)
+      if (kt + 1 >= nk) break;
+      MIMOSE_GEMM_STEP(kt + 1, st1, st0)
+      if (kt + 2 >= nk) break;
+      MIMOSE_GEMM_STEP(kt + 2, st2, st1)
+      if (kt + 3 >= nk) break;
+      MIMOSE_GEMM_STEP(kt + 3, st3, st2)
+    }
+  }
+#undef MIMOSE_GEMM_STEP
+
+  if (p.splits > 1) {
+    // raw fp32 tile and row sums of this k range; a second kernel adds the parts in order
+    float* part = p.partial + (int64_t)split * p.M * p.N;
+    float* rpart = p.partial + (int64_t)p.splits * p.M * p.N + (int64_t)split * p.M;
+    if (do_rowsum) {
+      const float tot = rs + __shfl_xor(rs, 1, 64);
+      const int m = m0 + (tid >> 1);
+      if ((tid & 1) == 0 && m < p.M) rpart[m] = tot;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int m = m0 + wm * 64 + i * 32 + (lane & 31);
+          const int n = n0 + wn * 64 + j * 32 + 8 * g + 4 * (lane >> 5);
+          if (m < p.M) {
+            float* dst = part + (int64_t)m * p.N + n;
+            if (n + 4 <= p.N && (p.N & 3) == 0) {
+              *(float4*)dst = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+            } else {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) if (n + e < p.N) dst[e] = acc[i][j][4 * g + e];
+            }
+          }
+        }
+    return;
+  }
+  if (do_rowsum) {
+    const float tot = rs + __shfl_xor(rs, 1, 64);
+    const int m = m0 + (tid >> 1);
+    if ((tid & 1) == 0 && m < p.M) p.a_rowsum[m] = tot;
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int m = m0 + wm * 64 + i * 32 + (lane & 31);
+        const int n = n0 + wn * 64 + j * 32 + 8 * g + 4 * (lane >> 5);
+        epilogue4<VEC>(p, m, n, acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+      }
+}
+
+template <bool AK, bool BKM>
+static void launch_t(const GemmDev& p, bool vec, hipStream_t st) {
+  const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+  const int total = tiles_m * tiles_n * p.splits, per = (total + 7) / 8;
+  const bool ktail = p.K % BK != 0;
+  dim3 grid(per * 8), block(256);
+#define L_(V, KT) hipLaunchKernelGGL((bgemm_dma_kernel<AK, BKM, V, KT>), grid, block, 0, st, p, tiles_n, total, per)
+  if (vec) { if (ktail) L_(true, true); else L_(true, false); }
+  else { if (ktail) L_(false, true); else L_(false, false); }
+#undef L_
+}
+
+// Requirements: 16-byte chunks must be wholly inside or wholly outside the matrix along the
+// reduction index of a k-major operand (K % 8 == 0), and physically present along the rows of an
+// m-major operand (its leading dimension covers the row count rounded up to 8).
+bool launch_bgemm_dma(const GemmDev& p, bool vec, hipStream_t st) {
+  auto up8 = [](int64_t v) { return (v + 7) / 8 * 8; };
+  if ((p.a_k || p.b_k) && (p.K & 7)) return false;
+  if (!p.a_k && p.lda < up8(p.M)) return false;
+  if (!p.b_k && p.ldb < up8(p.N)) return false;
+  if (p.a_k && p.b_k) launch_t<true, true>(p, vec, st);
+  else if (p.a_k && !p.b_k) launch_t<true, false>(p, vec, st);
+  else if (!p.a_k && p.b_k) launch_t<false, true>(p, vec, st);
+  else launch_t<false, false>(p, vec, st);
+  return true;
+}
+
+}  // namespace mk
