@@ -16,6 +16,27 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
+GEMM_SOURCES = ("gemm.hip", "gemm_dma.hip", "gemm_device.h")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "bert_base_gemm_hbm_traffic.txt")
+
+
+def recorded_gemm_traffic(workload):
+    """HBM bytes per GEMM launch from the committed FETCH_SIZE / WRITE_SIZE summary, or None when
+    the GEMM sources have changed since the counters were taken (or another workload runs)."""
+    import hashlib
+    if workload != "bert_base" or not os.path.exists(TRAFFIC_FILE):
+        return None
+    kv = {}
+    for line in open(TRAFFIC_FILE):
+        if "=" in line and not line.startswith("#"):
+            k, v = line.split("=", 1)
+            kv[k.strip()] = v.strip()
+    sha = hashlib.sha256()
+    for f in GEMM_SOURCES:
+        sha.update(open(os.path.join(ROOT, "paper_2209_02478_amd", "csrc", f), "rb").read())
+    if kv.get("sources_sha256") != sha.hexdigest():
+        return None
+    return int(kv["traffic_bytes_per_launch"])
 
 
 def main():
@@ -25,6 +46,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="bert_base")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run three plain 256 MiB element-wise copy kernels (reference for scaling FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
@@ -56,6 +79,13 @@ def main():
     lens = synthdata.seq_lengths(wl.length_recipe, total, wl.seed)
     batches = [synthdata.make_batch(shape, B, L, synthdata.step_seed(wl.seed, i)) for i, L in enumerate(lens)]
 
+    if args.pmc_calibration:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1, out=dst)        # an elementwise kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     for t, l in batches[:sheltered + args.warmup]:
         m.train_step(t, l)
     timed = batches[sheltered + args.warmup:]
@@ -76,8 +106,11 @@ def main():
         m.train_step(t, l)
     torch.cuda.synchronize()
     kernels = {}
+    gemm_flops_per_launch = 0.0
     for i, name in enumerate(mi.KERNEL_CLASSES):
         n, ms, work = mi.mimose_profile_read(m.ctx, i)
+        if n and i == 0:
+            gemm_flops_per_launch = work / n
         if n:
             rate = work / (ms * 1e-3)
             kernels[name] = {"launches": n, "avg_us": round(1e3 * ms / n, 3),
@@ -111,9 +144,12 @@ def main():
         "planner_us_per_step": round((s1["planner_ns_total"] - s0["planner_ns_total"]) / K / 1e3, 2),
         "max_peak_over_budget": round(max_peak / budget, 4),
         "kernels": kernels,
-        "roofline": {"bound": "mfma", "kernel": "bgemm_kernel (all GEMM launches of the timed steps)",
+        "roofline": {"bound": "mfma", "kernel": "bgemm_kernel / bgemm_dma_kernel (every GEMM launch of the timed steps)",
                      "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None},
+                     "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
+                     "avg_launch_us": kernels.get("gemm", {}).get("avg_us"),
+                     "flops_per_launch": round(gemm_flops_per_launch),
+                     "traffic": recorded_gemm_traffic(args.workload)},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
