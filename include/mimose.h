@@ -186,14 +186,17 @@ int mimose_op_gemm(int32_t dtype, const void* A, int64_t lda, int32_t a_kmajor, 
  * into parts that are summed in a fixed order (a function of M and N only; 0 = never needed).
  * Passing NULL workspace to mimose_op_gemm is always allowed. */
 uint64_t mimose_op_gemm_workspace_bytes(int32_t M, int32_t N);
-/* y = LayerNorm(x) * gamma + beta over rows of length H <= 1024. */
-int mimose_op_layernorm_fwd(int32_t dtype, const void* x, const void* gamma, const void* beta,
-                            void* y, int32_t T, int32_t H, float eps, void* stream);
-/* dx (may alias dy) = LayerNorm backward of dy at x (+ add[T,H] when not NULL); dgamma, dbeta
- * fp32[H]; partial: fp32 scratch of mimose_op_partial_rows(T)*2*H elements. */
-int mimose_op_layernorm_bwd(int32_t dtype, const void* dy, const void* x, const void* gamma,
-                            void* dx, const void* add, float* dgamma, float* dbeta, float* partial,
-                            int32_t T, int32_t H, float eps, void* stream);
+/* y = LayerNorm(x) * gamma + beta over rows of length H <= 1024.  x_f32: with dtype bf16 the
+ * input rows are fp32 (an unrounded residual sum); ignored for dtype fp32. */
+int mimose_op_layernorm_fwd(int32_t dtype, const void* x, int32_t x_f32, const void* gamma,
+                            const void* beta, void* y, int32_t T, int32_t H, float eps, void* stream);
+/* dx = LayerNorm backward of dy at x (+ add[T,H] when not NULL); dgamma, dbeta fp32[H]; partial:
+ * fp32 scratch of mimose_op_partial_rows(T)*2*H elements.  dy_f32 / x_f32: with dtype bf16 those
+ * inputs are fp32.  dx may alias dy when both have the storage type. */
+int mimose_op_layernorm_bwd(int32_t dtype, const void* dy, int32_t dy_f32, const void* x,
+                            int32_t x_f32, const void* gamma, void* dx, const void* add,
+                            float* dgamma, float* dbeta, float* partial, int32_t T, int32_t H,
+                            float eps, void* stream);
 int32_t mimose_op_partial_rows(int32_t T);
 /* d[n] (in place) *= gelu'(pre[n]). */
 int mimose_op_gelu_bwd(int32_t dtype, void* d, const void* pre, int64_t n, int32_t tanh_form,

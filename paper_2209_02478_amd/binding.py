@@ -74,8 +74,9 @@ SIGNATURES = {
     "mimose_op_gemm": (C.c_int, [_i32, _vp, _i64, _i32, _vp, _i64, _i32, _vp, _i64, _i32, _i32, _i32, _i32,
                                  _vp, _vp, _i64, _vp, _i32, _vp, _vp, _u64, _vp]),
     "mimose_op_gemm_workspace_bytes": (_u64, [_i32, _i32]),
-    "mimose_op_layernorm_fwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _i32, _i32, _f32, _vp]),
-    "mimose_op_layernorm_bwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _f32, _vp]),
+    "mimose_op_layernorm_fwd": (C.c_int, [_i32, _vp, _i32, _vp, _vp, _vp, _i32, _i32, _f32, _vp]),
+    "mimose_op_layernorm_bwd": (C.c_int, [_i32, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _f32,
+                                          _vp]),
     "mimose_op_partial_rows": (_i32, [_i32]),
     "mimose_op_gelu_bwd": (C.c_int, [_i32, _vp, _vp, _i64, _i32, _vp]),
     "mimose_op_attention_fwd": (C.c_int, [_i32, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp]),
@@ -251,14 +252,16 @@ def mimose_op_gemm_workspace_bytes(M: int, N: int) -> int:
     return load_library().mimose_op_gemm_workspace_bytes(M, N)
 
 
-def mimose_op_layernorm_fwd(dtype, x, gamma, beta, y, T, H, eps, stream=None):
-    _check(load_library().mimose_op_layernorm_fwd(dtype, _ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), T, H, eps,
+def mimose_op_layernorm_fwd(dtype, x, x_f32, gamma, beta, y, T, H, eps, stream=None):
+    _check(load_library().mimose_op_layernorm_fwd(dtype, _ptr(x), x_f32, _ptr(gamma), _ptr(beta), _ptr(y), T, H, eps,
                                                   _ptr(stream)))
 
 
-def mimose_op_layernorm_bwd(dtype, dy, x, gamma, dx, add, dgamma, dbeta, partial, T, H, eps, stream=None):
-    _check(load_library().mimose_op_layernorm_bwd(dtype, _ptr(dy), _ptr(x), _ptr(gamma), _ptr(dx), _ptr(add),
-                                                  _ptr(dgamma), _ptr(dbeta), _ptr(partial), T, H, eps, _ptr(stream)))
+def mimose_op_layernorm_bwd(dtype, dy, dy_f32, x, x_f32, gamma, dx, add, dgamma, dbeta, partial, T, H, eps,
+                            stream=None):
+    _check(load_library().mimose_op_layernorm_bwd(dtype, _ptr(dy), dy_f32, _ptr(x), x_f32, _ptr(gamma), _ptr(dx),
+                                                  _ptr(add), _ptr(dgamma), _ptr(dbeta), _ptr(partial), T, H, eps,
+                                                  _ptr(stream)))
 
 
 def mimose_op_partial_rows(T: int) -> int:

@@ -35,13 +35,15 @@ size_t gemm_workspace_bytes(int M, int N);
 // returns false when the arguments violate the kernel's alignment assumptions
 bool gemm(int dtype, const GemmArgs& g, hipStream_t st);
 
-void layernorm_fwd(int dtype, const void* x, const void* gamma, const void* beta, void* y,
-                   int T, int H, float eps, hipStream_t st);
+// x_f32: in a bf16 configuration the input rows are fp32 (an unrounded residual sum)
+void layernorm_fwd(int dtype, const void* x, bool x_f32, const void* gamma, const void* beta,
+                   void* y, int T, int H, float eps, hipStream_t st);
 // partial: fp32 scratch of partial_rows(T) * 2 * H elements
-// dx = LayerNorm backward (+ add when given); dx may alias dy
-void layernorm_bwd(int dtype, const void* dy, const void* x, const void* gamma, void* dx,
-                   const void* add, float* dgamma, float* dbeta, float* partial, int T, int H,
-                   float eps, hipStream_t st);
+// dx = LayerNorm backward (+ add when given); dx may alias dy when they have the same type;
+// dy_f32 / x_f32: in a bf16 configuration those inputs are fp32
+void layernorm_bwd(int dtype, const void* dy, bool dy_f32, const void* x, bool x_f32,
+                   const void* gamma, void* dx, const void* add, float* dgamma, float* dbeta,
+                   float* partial, int T, int H, float eps, hipStream_t st);
 int partial_rows(int T);
 void gelu_bwd(int dtype, void* d, const void* pre, int64_t n, int tanh_form, hipStream_t st);
 void attention_fwd(int dtype, const void* qkv, void* ctx, float* lse, int B, int L, int nh, int d,

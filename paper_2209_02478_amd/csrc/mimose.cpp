@@ -192,7 +192,11 @@ class Step {
   int dt_, es_;
   // embedding-stage tensors
   int32_t *ids_ = nullptr, *labels_ = nullptr, *order_ = nullptr, *seg_ = nullptr;
-  void *dA_ = nullptr, *dB_ = nullptr, *emb_sum_ = nullptr, *h0_ = nullptr;
+  // Gradient of the residual stream.  Post-LN blocks in bf16 carry it in fp32 (gA_, gB_) and
+  // keep the bf16 copies the products consume in oA_, oB_; otherwise the carriers have the
+  // storage type and oA_/oB_ alias them (LayerNorm backward then works in place).
+  void *gA_ = nullptr, *gB_ = nullptr, *oA_ = nullptr, *oB_ = nullptr, *emb_sum_ = nullptr, *h0_ = nullptr;
+  bool wide_ = false;   // fp32 residual sums and gradient carriers
   int n_seg_ = 0, n_valid_ = 0;
 
   // times everything enqueued during its lifetime as one launch of kernel class `cls`
@@ -213,6 +217,7 @@ class Step {
   void* w(int i) const { return c_->params[i].w; }
   float* g(int i) const { return c_->params[i].g; }
   void* talloc(int64_t elems) { return c_->arena.alloc((uint64_t)elems * es_); }
+  void* walloc(int64_t elems) { return c_->arena.alloc((uint64_t)elems * (wide_ ? 4 : es_)); }
 
   void gemm(const mk::GemmArgs& a) {
     if (dry_) return;
@@ -221,16 +226,17 @@ class Step {
   }
   // Y[T,out] = X[T,in] W[out,in]^T + bias (+ resid) (GELU: Y = pre-activation, act = GELU(Y))
   void linear(const void* X, int in, int wi, int bi, void* Y, int out, int64_t ldy, const void* resid = nullptr,
-              void* act = nullptr, int gelu = 0, int rows = -1) {
-    mk::GemmArgs a{X, in, true, w(wi), in, true, Y, ldy, false, rows < 0 ? T_ : rows, out, in};
+              void* act = nullptr, int gelu = 0, bool out_f32 = false) {
+    mk::GemmArgs a{X, in, true, w(wi), in, true, Y, ldy, out_f32, T_, out, in};
     a.bias = bi >= 0 ? w(bi) : nullptr;
     a.resid = resid; a.ldr = out;
     a.gelu_out = act; a.gelu = gelu;
     gemm(a);
   }
   // dX[T,in] = dY[T,out] W[out,in] (+ resid)
-  void dgrad(const void* dY, int64_t ldy, int out, int wi, void* dX, int in, const void* resid = nullptr) {
-    mk::GemmArgs a{dY, ldy, true, w(wi), in, false, dX, in, false, T_, in, out};
+  void dgrad(const void* dY, int64_t ldy, int out, int wi, void* dX, int in, const void* resid = nullptr,
+             bool out_f32 = false) {
+    mk::GemmArgs a{dY, ldy, true, w(wi), in, false, dX, in, out_f32, T_, in, out};
     a.resid = resid; a.ldr = in;
     gemm(a);
   }
@@ -256,15 +262,18 @@ class Step {
     a.workspace = ws_; a.workspace_bytes = ws_bytes_;
     gemm(a);
   }
-  void ln_fwd(const void* x, int gi, int bi, void* y) {
-    Timed t(this, MIMOSE_K_LN_FWD, 2.0 * T_ * f_.hidden * es_d());
-    if (!dry_) mk::layernorm_fwd(dt_, x, w(gi), w(bi), y, T_, f_.hidden, f_.ln_eps, st_);
+  void ln_fwd(const void* x, int gi, int bi, void* y, bool x_f32 = false) {
+    Timed t(this, MIMOSE_K_LN_FWD, (x_f32 ? 6.0 : 2.0 * es_d()) * T_ * f_.hidden);
+    if (!dry_) mk::layernorm_fwd(dt_, x, x_f32, w(gi), w(bi), y, T_, f_.hidden, f_.ln_eps, st_);
   }
-  void ln_bwd(const void* dy, const void* x, int gi, int bi, void* dx, const void* add) {
+  void ln_bwd(const void* dy, const void* x, int gi, int bi, void* dx, const void* add, bool dy_f32 = false,
+              bool x_f32 = false) {
     const uint64_t m = c_->arena.top();
     float* partial = (float*)c_->arena.alloc((uint64_t)mk::partial_rows(T_) * 2 * f_.hidden * 4);
-    Timed t(this, MIMOSE_K_LN_BWD, (add ? 4.0 : 3.0) * T_ * f_.hidden * es_d());
-    if (!dry_) mk::layernorm_bwd(dt_, dy, x, w(gi), dx, add, g(gi), g(bi), partial, T_, f_.hidden, f_.ln_eps, st_);
+    const double bytes = (dy_f32 ? 4.0 : es_d()) + (x_f32 ? 4.0 : es_d()) + es_d() * (add ? 2.0 : 1.0);
+    Timed t(this, MIMOSE_K_LN_BWD, bytes * T_ * f_.hidden);
+    if (!dry_)
+      mk::layernorm_bwd(dt_, dy, dy_f32, x, x_f32, w(gi), dx, add, g(gi), g(bi), partial, T_, f_.hidden, f_.ln_eps, st_);
     c_->arena.pop_to(m);
   }
 
@@ -281,8 +290,11 @@ void Step::embed_stage(const int32_t* tokens, const int32_t* labels) {
   int32_t* ints = (int32_t*)c_->arena.alloc((uint64_t)(4 * (int64_t)T_ + 1) * 4);
   ids_ = ints; labels_ = ints ? ints + T_ : nullptr; order_ = ints ? ints + 2 * (int64_t)T_ : nullptr;
   seg_ = ints ? ints + 3 * (int64_t)T_ : nullptr;
-  dA_ = talloc((int64_t)T_ * H);
-  dB_ = talloc((int64_t)T_ * H);
+  wide_ = !f_.pre_ln && dt_ == mk::BF16;
+  gA_ = walloc((int64_t)T_ * H);
+  gB_ = walloc((int64_t)T_ * H);
+  oA_ = wide_ ? talloc((int64_t)T_ * H) : gA_;
+  oB_ = wide_ ? talloc((int64_t)T_ * H) : gB_;
   if (!f_.pre_ln) emb_sum_ = talloc((int64_t)T_ * H);
   h0_ = talloc((int64_t)T_ * H);
   if (dry_) return;
@@ -327,11 +339,11 @@ void Step::alloc_layer(int l, LayerActs& A) {
   A.qkv = talloc(3 * TH);
   A.lse = (float*)c_->arena.alloc((uint64_t)B_ * f_.n_heads * L_ * 4);
   A.ctx = talloc(TH);
-  A.s1 = talloc(TH);                  // post-LN: x + proj (LN1 input); pre-LN: u = x + proj
+  A.s1 = walloc(TH);                  // post-LN: x + proj (LN1 input, fp32 when wide); pre-LN: u = x + proj
   A.u = talloc(TH);                   // post-LN: LN1(s1); pre-LN: LN2(u)
   A.pre = talloc(TF);
   A.act = talloc(TF);
-  if (!f_.pre_ln) A.s2 = talloc(TH);  // post-LN: u + ffn (LN2 input)
+  if (!f_.pre_ln) A.s2 = walloc(TH);  // post-LN: u + ffn (LN2 input, fp32 when wide)
 }
 
 void Step::layer_forward(int l, LayerActs& A) {
@@ -345,20 +357,20 @@ void Step::layer_forward(int l, LayerActs& A) {
     Timed t(this, MIMOSE_K_ATTN_FWD, 4.0 * T_ * L_ * H * (f_.causal ? 0.5 : 1.0));
     if (!dry_) mk::attention_fwd(dt_, A.qkv, A.ctx, A.lse, B_, L_, nh, d, f_.causal, st_);
   }
-  linear(A.ctx, H, p.wo, p.bo, A.s1, H, H, A.x);
+  linear(A.ctx, H, p.wo, p.bo, A.s1, H, H, A.x, nullptr, 0, wide_);
   if (f_.pre_ln) {
     ln_fwd(A.s1, p.ln2g, p.ln2b, A.u);
     linear(A.u, H, p.w1, p.b1, A.pre, F, F, nullptr, A.act, gelu);
     linear(A.act, F, p.w2, p.b2, A.out, H, H, A.s1);
   } else {
-    ln_fwd(A.s1, p.ln1g, p.ln1b, A.u);
+    ln_fwd(A.s1, p.ln1g, p.ln1b, A.u, wide_);
     linear(A.u, H, p.w1, p.b1, A.pre, F, F, nullptr, A.act, gelu);
-    linear(A.act, F, p.w2, p.b2, A.s2, H, H, A.u);
-    ln_fwd(A.s2, p.ln2g, p.ln2b, A.out);
+    linear(A.act, F, p.w2, p.b2, A.s2, H, H, A.u, nullptr, 0, wide_);
+    ln_fwd(A.s2, p.ln2g, p.ln2b, A.out, wide_);
   }
 }
 
-// Gradient of the layer output arrives in dA_; the gradient of its input leaves in dA_.
+// Gradient of the layer output arrives in gA_; the gradient of its input leaves in gA_.
 void Step::layer_backward(int l, LayerActs& A) {
   const LayerIdx& p = c_->lidx[l];
   const int H = f_.hidden, F = f_.ffn, nh = f_.n_heads, d = H / nh;
@@ -366,27 +378,29 @@ void Step::layer_backward(int l, LayerActs& A) {
   Arena& ar = c_->arena;
   reserve_workspace({{H, F}, {F, H}, {H, H}, {3 * H, H}});
   const uint64_t m0 = ar.top();
-  if (!f_.pre_ln) ln_bwd(dA_, A.s2, p.ln2g, p.ln2b, dA_, nullptr);           // dA = d s2
-  wgrad(dA_, H, H, A.act, F, p.w2, p.b2);
+  // post-LN: oA = d s2 (LayerNorm 2 backward of the incoming gradient); pre-LN: the incoming
+  // gradient is d s2 itself (oA aliases gA)
+  if (!f_.pre_ln) ln_bwd(gA_, A.s2, p.ln2g, p.ln2b, oA_, nullptr, wide_, wide_);
+  wgrad(oA_, H, H, A.act, F, p.w2, p.b2);
   void* dact = talloc(TF);
-  dgrad(dA_, H, H, p.w2, dact, F);
+  dgrad(oA_, H, H, p.w2, dact, F);
   {
     Timed t(this, MIMOSE_K_GELU_BWD, 3.0 * TF * es_d());
     if (!dry_) mk::gelu_bwd(dt_, dact, A.pre, TF, f_.gelu_tanh, st_);        // dact = d pre
   }
   wgrad(dact, F, F, A.u, H, p.w1, p.b1);
   if (f_.pre_ln) {
-    dgrad(dact, F, F, p.w1, dB_, H);                                          // dB = d LN2(u)
+    dgrad(dact, F, F, p.w1, gB_, H);                                          // gB = d LN2(u)
     ar.pop_to(m0);
-    ln_bwd(dB_, A.s1, p.ln2g, p.ln2b, dB_, dA_);                              // dB = d u
+    ln_bwd(gB_, A.s1, p.ln2g, p.ln2b, gB_, gA_);                              // gB = d u
   } else {
-    dgrad(dact, F, F, p.w1, dB_, H, dA_);                                     // dB = d u
+    dgrad(dact, F, F, p.w1, gB_, H, oA_, wide_);                              // gB = d u = d s2 + FFN path
     ar.pop_to(m0);
-    ln_bwd(dB_, A.s1, p.ln1g, p.ln1b, dB_, nullptr);                          // dB = d s1
+    ln_bwd(gB_, A.s1, p.ln1g, p.ln1b, oB_, nullptr, wide_, wide_);            // oB = d s1
   }
-  wgrad(dB_, H, H, A.ctx, H, p.wo, p.bo);
+  wgrad(oB_, H, H, A.ctx, H, p.wo, p.bo);
   void* dctx = talloc(TH);
-  dgrad(dB_, H, H, p.wo, dctx, H);
+  dgrad(oB_, H, H, p.wo, dctx, H);
   void* dqkv = talloc(3 * TH);
   float* delta = (float*)ar.alloc((uint64_t)B_ * nh * L_ * 4);
   {
@@ -396,16 +410,16 @@ void Step::layer_backward(int l, LayerActs& A) {
   const void* a = f_.pre_ln ? A.n1 : A.x;
   wgrad(dqkv, 3 * H, 3 * H, a, H, p.wqkv, p.bqkv);
   if (f_.pre_ln) {
-    dgrad(dqkv, 3 * H, 3 * H, p.wqkv, dA_, H);                                // dA = d LN1(x)
+    dgrad(dqkv, 3 * H, 3 * H, p.wqkv, gA_, H);                                // gA = d LN1(x)
     ar.pop_to(m0);
-    ln_bwd(dA_, A.x, p.ln1g, p.ln1b, dA_, dB_);                               // dA = d x
+    ln_bwd(gA_, A.x, p.ln1g, p.ln1b, gA_, gB_);                               // gA = d x
   } else {
-    dgrad(dqkv, 3 * H, 3 * H, p.wqkv, dA_, H, dB_);                           // dA = d x
+    dgrad(dqkv, 3 * H, 3 * H, p.wqkv, gA_, H, oB_, wide_);                    // gA = d x = d s1 + attention path
     ar.pop_to(m0);
   }
 }
 
-// Head forward, loss, head backward.  Leaves the gradient of the last layer's output in dA_.
+// Head forward, loss, head backward.  Leaves the gradient of the last layer's output in gA_.
 void Step::head(float* loss_dev) {
   const int H = f_.hidden, V = f_.vocab;
   const int64_t TH = (int64_t)T_ * H, ldv = c_->ldv();
@@ -441,26 +455,26 @@ void Step::head(float* loss_dev) {
     a.a_rowsum = f_.head ? g(c_->i_bdec) : nullptr;
     with_workspace(a);
   }
-  void* dhs = f_.pre_ln ? talloc(TH) : dA_;
+  void* dhs = f_.pre_ln ? talloc(TH) : gA_;            // post-LN: straight into the (possibly fp32) carrier
   if (f_.head) {
     void* dt = talloc(TH);
     { mk::GemmArgs a{logits, ldv, true, w(c_->i_tok), H, false, dt, H, false, T_, H, V}; gemm(a); }
     ln_bwd(dt, gz, c_->i_hg, c_->i_hb, dt, nullptr);                          // dt = d gz
     if (!dry_) mk::gelu_bwd(dt_, dt, z, TH, f_.gelu_tanh, st_);               // dt = d z
     wgrad(dt, H, H, hs, H, c_->i_wt, c_->i_bt);
-    dgrad(dt, H, H, c_->i_wt, dhs, H);
+    dgrad(dt, H, H, c_->i_wt, dhs, H, nullptr, wide_);
   } else {
-    mk::GemmArgs a{logits, ldv, true, w(c_->i_tok), H, false, dhs, H, false, T_, H, V};
+    mk::GemmArgs a{logits, ldv, true, w(c_->i_tok), H, false, dhs, H, wide_, T_, H, V};
     gemm(a);
   }
-  if (f_.pre_ln) ln_bwd(dhs, hlast, c_->i_fg, c_->i_fb, dA_, nullptr);
+  if (f_.pre_ln) ln_bwd(dhs, hlast, c_->i_fg, c_->i_fb, gA_, nullptr);
 }
 
 void Step::embed_backward() {
   const int H = f_.hidden;
-  if (!f_.pre_ln) ln_bwd(dA_, emb_sum_, c_->i_eg, c_->i_eb, dA_, nullptr);
+  if (!f_.pre_ln) ln_bwd(gA_, emb_sum_, c_->i_eg, c_->i_eb, oA_, nullptr, wide_, false);
   if (!dry_)
-    mk::embed_bwd(dt_, dA_, ids_, order_, seg_, n_seg_, g(c_->i_tok), g(c_->i_pos), B_, L_, H, f_.max_seq, st_);
+    mk::embed_bwd(dt_, oA_, ids_, order_, seg_, n_seg_, g(c_->i_tok), g(c_->i_pos), B_, L_, H, f_.max_seq, st_);
 }
 
 void Step::run(const int32_t* tokens, const int32_t* labels, float* loss_out) {

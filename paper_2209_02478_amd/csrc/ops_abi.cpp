@@ -29,20 +29,21 @@ uint64_t mimose_op_gemm_workspace_bytes(int32_t M, int32_t N) {
   return M > 0 && N > 0 ? mk::gemm_workspace_bytes(M, N) : 0;
 }
 
-int mimose_op_layernorm_fwd(int32_t dtype, const void* x, const void* gamma, const void* beta, void* y, int32_t T,
-                            int32_t H, float eps, void* stream) {
+int mimose_op_layernorm_fwd(int32_t dtype, const void* x, int32_t x_f32, const void* gamma, const void* beta, void* y,
+                            int32_t T, int32_t H, float eps, void* stream) {
   if (bad_dtype(dtype) || !x || !gamma || !beta || !y || T < 0 || H < 1 || H > mk::kMaxRowWidth) return MIMOSE_ERR_INVALID_ARG;
-  mk::layernorm_fwd(dtype, x, gamma, beta, y, T, H, eps, (hipStream_t)stream);
+  mk::layernorm_fwd(dtype, x, x_f32 != 0, gamma, beta, y, T, H, eps, (hipStream_t)stream);
   return done();
 }
 
-int mimose_op_layernorm_bwd(int32_t dtype, const void* dy, const void* x, const void* gamma, void* dx,
-                            const void* add, float* dgamma, float* dbeta, float* partial, int32_t T, int32_t H,
-                            float eps, void* stream) {
+int mimose_op_layernorm_bwd(int32_t dtype, const void* dy, int32_t dy_f32, const void* x, int32_t x_f32,
+                            const void* gamma, void* dx, const void* add, float* dgamma, float* dbeta, float* partial,
+                            int32_t T, int32_t H, float eps, void* stream) {
   if (bad_dtype(dtype) || !dy || !x || !gamma || !dx || !dgamma || !dbeta || !partial || T < 0 || H < 1 ||
-      H > mk::kMaxRowWidth || add == dx)
+      H > mk::kMaxRowWidth || add == dx || (dx == dy && dtype == 1 && dy_f32))
     return MIMOSE_ERR_INVALID_ARG;
-  mk::layernorm_bwd(dtype, dy, x, gamma, dx, add, dgamma, dbeta, partial, T, H, eps, (hipStream_t)stream);
+  mk::layernorm_bwd(dtype, dy, dy_f32 != 0, x, x_f32 != 0, gamma, dx, add, dgamma, dbeta, partial, T, H, eps,
+                    (hipStream_t)stream);
   return done();
 }
 

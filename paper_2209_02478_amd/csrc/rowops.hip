@@ -29,16 +29,16 @@ __device__ __forceinline__ void row_stats(const float (&v)[NPL], int H, int lane
   rstd = rsqrtf(wave_sum(q) / (float)H + eps);
 }
 
-template <typename T, int NPL>
-__global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
+template <typename TX, typename T, int NPL>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const TX* __restrict__ x, const T* __restrict__ gamma,
                                                      const T* __restrict__ beta, T* __restrict__ y, int Trows,
                                                      int H, float eps) {
   const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= Trows) return;
-  const T* xr = x + (int64_t)row * H;
+  const TX* xr = x + (int64_t)row * H;
   float v[NPL];
 #pragma unroll
-  for (int i = 0; i < NPL; ++i) { int c = lane + 64 * i; v[i] = c < H ? ld<T>(xr + c) : 0.f; }
+  for (int i = 0; i < NPL; ++i) { int c = lane + 64 * i; v[i] = c < H ? ld<TX>(xr + c) : 0.f; }
   float mean, rstd;
   row_stats<T, NPL>(v, H, lane, mean, rstd, eps);
   T* yr = y + (int64_t)row * H;
@@ -54,8 +54,8 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, co
 // residual-path gradient added to the result.  dx may alias dy; add must not alias dx.  Each wave keeps
 // per-column sums of dy*xhat and dy over its rows; the four waves are combined through LDS
 // in wave order and written as one partial row.
-template <typename T, int NPL>
-__global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+template <typename TD, typename TX, typename T, int NPL>
+__global__ __launch_bounds__(256) void ln_bwd_kernel(const TD* __restrict__ dy, const TX* __restrict__ x,
                                                      const T* __restrict__ gamma, T* __restrict__ dx,
                                                      const T* __restrict__ add, float* __restrict__ partial,
                                                      int Trows, int H, float eps) {
@@ -71,14 +71,14 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
   for (int rr = 0; rr < kRowsPerChunk / 4; ++rr) {
     int row = blockIdx.x * kRowsPerChunk + rr * 4 + wave;
     if (row >= Trows) break;
-    const T* xr = x + (int64_t)row * H;
-    const T* dr = dy + (int64_t)row * H;
+    const TX* xr = x + (int64_t)row * H;
+    const TD* dr = dy + (int64_t)row * H;
     float v[NPL], d[NPL];
 #pragma unroll
     for (int i = 0; i < NPL; ++i) {
       int c = lane + 64 * i;
-      v[i] = c < H ? ld<T>(xr + c) : 0.f;
-      d[i] = c < H ? ld<T>(dr + c) : 0.f;
+      v[i] = c < H ? ld<TX>(xr + c) : 0.f;
+      d[i] = c < H ? ld<TD>(dr + c) : 0.f;
     }
     float mean, rstd;
     row_stats<T, NPL>(v, H, lane, mean, rstd, eps);
@@ -171,6 +171,20 @@ template <> struct Chunk<float> {
   }
 };
 
+// E consecutive elements of type T as floats (E = Chunk<storage type>::N; fp32 sources of a bf16
+// configuration take two 16-byte loads)
+template <typename T, int E>
+__device__ __forceinline__ void load_elems(const T* p, float (&v)[E]) {
+  constexpr int N = Chunk<T>::N;
+#pragma unroll
+  for (int k = 0; k < E / N; ++k) {
+    float t[N];
+    Chunk<T>::load(p + k * N, t);
+#pragma unroll
+    for (int e = 0; e < N; ++e) v[k * N + e] = t[e];
+  }
+}
+
 // mean and 1/std of a row held as NC chunks per lane (chunks >= nchunks hold zeros)
 template <int NC, int E>
 __device__ __forceinline__ void chunk_stats(const float (&v)[NC][E], int nchunks, int lane, int H, float eps,
@@ -190,20 +204,20 @@ __device__ __forceinline__ void chunk_stats(const float (&v)[NC][E], int nchunks
   rstd = rsqrtf(wave_sum(q) / (float)H + eps);
 }
 
-template <typename T, int NC>
-__global__ __launch_bounds__(256) void ln_fwd_vec_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
+template <typename TX, typename T, int NC>
+__global__ __launch_bounds__(256) void ln_fwd_vec_kernel(const TX* __restrict__ x, const T* __restrict__ gamma,
                                                          const T* __restrict__ beta, T* __restrict__ y, int Trows,
                                                          int H, float eps) {
   constexpr int E = Chunk<T>::N;
   const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= Trows) return;
   const int nchunks = H / E;
-  const T* xr = x + (int64_t)row * H;
+  const TX* xr = x + (int64_t)row * H;
   float v[NC][E];
 #pragma unroll
   for (int i = 0; i < NC; ++i) {
     const int c = lane + 64 * i;
-    if (c < nchunks) Chunk<T>::load(xr + c * E, v[i]);
+    if (c < nchunks) load_elems<TX, E>(xr + c * E, v[i]);
     else
 #pragma unroll
       for (int e = 0; e < E; ++e) v[i][e] = 0.f;
@@ -227,8 +241,8 @@ __global__ __launch_bounds__(256) void ln_fwd_vec_kernel(const T* __restrict__ x
 
 // Backward: block = 4 waves = kRowsPerChunk rows, every wave takes 4 rows and issues all their
 // loads before any arithmetic.  Same outputs and the same summation order as ln_bwd_kernel.
-template <typename T, int NC>
-__global__ __launch_bounds__(256) void ln_bwd_vec_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+template <typename TD, typename TX, typename T, int NC>
+__global__ __launch_bounds__(256) void ln_bwd_vec_kernel(const TD* __restrict__ dy, const TX* __restrict__ x,
                                                          const T* __restrict__ gamma, T* __restrict__ dx,
                                                          const T* __restrict__ add, float* __restrict__ partial,
                                                          int Trows, int H, float eps) {
@@ -253,8 +267,8 @@ __global__ __launch_bounds__(256) void ln_bwd_vec_kernel(const T* __restrict__ d
     for (int i = 0; i < NC; ++i) {
       const int c = lane + 64 * i;
       if (row < Trows && c < nchunks) {
-        Chunk<T>::load(x + (int64_t)row * H + c * E, v[rr][i]);
-        Chunk<T>::load(dy + (int64_t)row * H + c * E, d[rr][i]);
+        load_elems<TX, E>(x + (int64_t)row * H + c * E, v[rr][i]);
+        load_elems<TD, E>(dy + (int64_t)row * H + c * E, d[rr][i]);
       } else {
 #pragma unroll
         for (int e = 0; e < E; ++e) { v[rr][i][e] = 0.f; d[rr][i][e] = 0.f; }
@@ -576,53 +590,58 @@ static bool vec_ok(int H, std::initializer_list<const void*> ptrs) {
   return true;
 }
 
-template <typename T>
+template <typename TX, typename T>
 static void ln_fwd_t(const void* x, const void* g, const void* b, void* y, int T_, int H, float eps,
                      hipStream_t st) {
   dim3 grid((T_ + 3) / 4);
   if (vec_ok<T>(H, {x, g, b, y})) {
     const int nc = (H / Chunk<T>::N + 63) / 64;
-#define V_(NC) hipLaunchKernelGGL((ln_fwd_vec_kernel<T, NC>), grid, dim3(256), 0, st, (const T*)x, (const T*)g, \
+#define V_(NC) hipLaunchKernelGGL((ln_fwd_vec_kernel<TX, T, NC>), grid, dim3(256), 0, st, (const TX*)x, (const T*)g, \
                                    (const T*)b, (T*)y, T_, H, eps)
     if (nc <= 1) { V_(1); return; }
     if (nc <= 2) { V_(2); return; }
     if (nc <= 4) { V_(4); return; }
 #undef V_
   }
-#define M_(NPL) hipLaunchKernelGGL((ln_fwd_kernel<T, NPL>), grid, dim3(256), 0, st, (const T*)x, (const T*)g, \
+#define M_(NPL) hipLaunchKernelGGL((ln_fwd_kernel<TX, T, NPL>), grid, dim3(256), 0, st, (const TX*)x, (const T*)g, \
                                    (const T*)b, (T*)y, T_, H, eps)
   DISPATCH_NPL(H, M_);
 #undef M_
 }
-void layernorm_fwd(int dtype, const void* x, const void* gamma, const void* beta, void* y, int T_, int H,
-                   float eps, hipStream_t st) {
+void layernorm_fwd(int dtype, const void* x, bool x_f32, const void* gamma, const void* beta, void* y, int T_,
+                   int H, float eps, hipStream_t st) {
   if (T_ <= 0) return;
-  if (dtype == BF16) ln_fwd_t<bf16_t>(x, gamma, beta, y, T_, H, eps, st);
-  else ln_fwd_t<float>(x, gamma, beta, y, T_, H, eps, st);
+  if (dtype != BF16) ln_fwd_t<float, float>(x, gamma, beta, y, T_, H, eps, st);
+  else if (x_f32) ln_fwd_t<float, bf16_t>(x, gamma, beta, y, T_, H, eps, st);
+  else ln_fwd_t<bf16_t, bf16_t>(x, gamma, beta, y, T_, H, eps, st);
 }
 
-template <typename T>
+template <typename TD, typename TX, typename T>
 static void ln_bwd_t(const void* dy, const void* x, const void* g, void* dx, const void* add, float* partial,
                      int T_, int H, float eps, hipStream_t st) {
   dim3 grid((T_ + kRowsPerChunk - 1) / kRowsPerChunk);
   if (vec_ok<T>(H, {dy, x, g, dx, add})) {
     const int nc = (H / Chunk<T>::N + 63) / 64;
-#define V_(NC) hipLaunchKernelGGL((ln_bwd_vec_kernel<T, NC>), grid, dim3(256), 0, st, (const T*)dy, (const T*)x, \
-                                   (const T*)g, (T*)dx, (const T*)add, partial, T_, H, eps)
+#define V_(NC) hipLaunchKernelGGL((ln_bwd_vec_kernel<TD, TX, T, NC>), grid, dim3(256), 0, st, (const TD*)dy, \
+                                   (const TX*)x, (const T*)g, (T*)dx, (const T*)add, partial, T_, H, eps)
     if (nc <= 1) { V_(1); return; }
     if (nc <= 2) { V_(2); return; }
 #undef V_
   }
-#define M_(NPL) hipLaunchKernelGGL((ln_bwd_kernel<T, NPL>), grid, dim3(256), 0, st, (const T*)dy, (const T*)x, \
-                                   (const T*)g, (T*)dx, (const T*)add, partial, T_, H, eps)
+#define M_(NPL) hipLaunchKernelGGL((ln_bwd_kernel<TD, TX, T, NPL>), grid, dim3(256), 0, st, (const TD*)dy,    \
+                                   (const TX*)x, (const T*)g, (T*)dx, (const T*)add, partial, T_, H, eps)
   DISPATCH_NPL(H, M_);
 #undef M_
 }
-void layernorm_bwd(int dtype, const void* dy, const void* x, const void* gamma, void* dx, const void* add,
-                   float* dgamma, float* dbeta, float* partial, int T_, int H, float eps, hipStream_t st) {
+void layernorm_bwd(int dtype, const void* dy, bool dy_f32, const void* x, bool x_f32, const void* gamma, void* dx,
+                   const void* add, float* dgamma, float* dbeta, float* partial, int T_, int H, float eps,
+                   hipStream_t st) {
   if (T_ <= 0) return;
-  if (dtype == BF16) ln_bwd_t<bf16_t>(dy, x, gamma, dx, add, partial, T_, H, eps, st);
-  else ln_bwd_t<float>(dy, x, gamma, dx, add, partial, T_, H, eps, st);
+  if (dtype != BF16) ln_bwd_t<float, float, float>(dy, x, gamma, dx, add, partial, T_, H, eps, st);
+  else if (dy_f32 && x_f32) ln_bwd_t<float, float, bf16_t>(dy, x, gamma, dx, add, partial, T_, H, eps, st);
+  else if (dy_f32) ln_bwd_t<float, bf16_t, bf16_t>(dy, x, gamma, dx, add, partial, T_, H, eps, st);
+  else if (x_f32) ln_bwd_t<bf16_t, float, bf16_t>(dy, x, gamma, dx, add, partial, T_, H, eps, st);
+  else ln_bwd_t<bf16_t, bf16_t, bf16_t>(dy, x, gamma, dx, add, partial, T_, H, eps, st);
   int P = (T_ + kRowsPerChunk - 1) / kRowsPerChunk;
   hipLaunchKernelGGL(reduce_partials_kernel, dim3((2 * H + 15) / 16), dim3(256), 0, st, partial, P, 2 * H,
                      dgamma, dbeta, H);

@@ -114,37 +114,47 @@ def test_gemm_rejects_misaligned_bf16():
 
 
 # ---------------------------------------------------------------- LayerNorm
-@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("dtype,x_f32,dy_f32", [(0, 0, 0), (1, 0, 0), (1, 1, 1), (1, 1, 0), (1, 0, 1)])
 @pytest.mark.parametrize("T,H", [(37, 64), (130, 768), (5, 1024), (64, 24)])
-def test_layernorm_fwd_bwd(dtype, T, H):
+def test_layernorm_fwd_bwd(dtype, x_f32, dy_f32, T, H):
+    """x_f32 / dy_f32: in a bf16 configuration the input rows / incoming gradients are fp32
+    (unrounded residual sums and the fp32 gradient carrier of the residual stream)."""
     rng = np.random.default_rng(T + H)
     x = (rng.standard_normal((T, H)) * 2 + 0.5).astype(np.float32)
     g = (1 + 0.2 * rng.standard_normal(H)).astype(np.float32)
     b = (0.1 * rng.standard_normal(H)).astype(np.float32)
     dy = rng.standard_normal((T, H)).astype(np.float32)
     add = rng.standard_normal((T, H)).astype(np.float32)
-    xq, gq, bq, dyq, addq = (quant(v, dtype) for v in (x, g, b, dy, add))
+    xq = quant(x, 0 if x_f32 else dtype)
+    dyq = quant(dy, 0 if dy_f32 else dtype)
+    gq, bq, addq = (quant(v, dtype) for v in (g, b, add))
     y_ref, saved = om.layernorm_fwd(xq, gq, bq, 1e-5)
     dx_ref, dg_ref, db_ref = om.layernorm_bwd(dyq, saved, gq)
-    dx_, dg_, db_, ddy, dadd = dev(x, dtype), dev(g, dtype), dev(b, dtype), dev(dy, dtype), dev(add, dtype)
-    y = torch.zeros_like(dx_)
-    mi.mimose_op_layernorm_fwd(dtype, dx_, dg_, db_, y, T, H, 1e-5)
+    dx_ = dev(x, 0 if x_f32 else dtype)
+    ddy = dev(dy, 0 if dy_f32 else dtype)
+    dg_, db_, dadd = dev(g, dtype), dev(b, dtype), dev(add, dtype)
+    y = torch.zeros((T, H), dtype=dg_.dtype, device=DEV)
+    mi.mimose_op_layernorm_fwd(dtype, dx_, x_f32, dg_, db_, y, T, H, 1e-5)
     sync()
     close(host(y), y_ref, dtype, k=2.0)
     P = mi.mimose_op_partial_rows(T)
     partial = torch.zeros(P * 2 * H, dtype=torch.float32, device=DEV)
     dgam = torch.zeros(H, dtype=torch.float32, device=DEV)
     dbet = torch.zeros(H, dtype=torch.float32, device=DEV)
-    out = torch.zeros_like(dx_)
-    mi.mimose_op_layernorm_bwd(dtype, ddy, dx_, dg_, out, dadd, dgam, dbet, partial, T, H, 1e-5)
+    out = torch.zeros_like(y)
+    mi.mimose_op_layernorm_bwd(dtype, ddy, dy_f32, dx_, x_f32, dg_, out, dadd, dgam, dbet, partial, T, H, 1e-5)
     sync()
     close(host(out), dx_ref + addq, dtype, k=3.0)
     close(host(dgam), dg_ref, 0, k=50.0)
     close(host(dbet), db_ref, 0, k=50.0)
-    # in place, no residual input
-    mi.mimose_op_layernorm_bwd(dtype, ddy, dx_, dg_, ddy, None, dgam, dbet, partial, T, H, 1e-5)
-    sync()
-    close(host(ddy), dx_ref, dtype, k=3.0)
+    if not (dtype == 1 and dy_f32):
+        # in place, no residual input
+        mi.mimose_op_layernorm_bwd(dtype, ddy, dy_f32, dx_, x_f32, dg_, ddy, None, dgam, dbet, partial, T, H, 1e-5)
+        sync()
+        close(host(ddy), dx_ref, dtype, k=3.0)
+    else:
+        with pytest.raises(mi.MimoseError):                  # fp32 gradient in, bf16 out cannot alias
+            mi.mimose_op_layernorm_bwd(dtype, ddy, dy_f32, dx_, x_f32, dg_, ddy, None, dgam, dbet, partial, T, H, 1e-5)
 
 
 @pytest.mark.parametrize("dtype", [0, 1])

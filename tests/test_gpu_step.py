@@ -185,3 +185,25 @@ def test_bert_base_full_length_under_budget():
     for k in G0:
         assert np.array_equal(G0[k], G1[k]), k
     big.close()
+
+
+@pytest.mark.parametrize("name,B,L,plan", [
+    ("bert_large", 2, 128, 0), ("bert_large", 2, 304, 0x0F0F0F),
+    ("gpt2_medium", 2, 129, 0), ("gpt2_medium", 2, 300, 0xAAAAAA),
+    ("bert_large_stress", 4, 40, 0), ("bert_large_stress", 2, 384, 0xFFFFFF),
+])
+def test_other_workload_shapes_reduced_batch(name, B, L, plan):
+    """The larger model shapes (BERT-large, GPT-2-medium causal pre-LN) at a reduced batch so the
+    oracle finishes in seconds: loss and every gradient against the oracle, with and without
+    dropped layers."""
+    wl = synthdata.WORKLOADS[name]
+    shape = wl.shape
+    params = synthdata.make_params(shape, wl.seed)
+    tokens, labels = synthdata.make_batch(shape, B, L, 77)
+    m = mi.Mimose(synthdata.shape_dict(shape), 0, arena_bytes=6144 * MiB)
+    m.load_params(params)
+    m.force_plan(plan)
+    loss, peak, got, worst = check_against_oracle(shape, m, params, tokens, labels, 1e-2, 2e-2, np.float32)
+    assert got == plan
+    print(name, B, L, "loss", loss, "worst grad", worst)
+    m.close()
