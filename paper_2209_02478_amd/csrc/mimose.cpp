@@ -81,6 +81,10 @@ struct mimose_ctx {
   uint64_t budget = 0;
   bool has_device = false;
   hipStream_t stream = nullptr;
+  // weight-gradient products run on a second stream, beside the data-gradient chain that
+  // needs the same incoming gradient (fork / join with events; default priority)
+  hipStream_t side = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   Arena arena;
   uint64_t fixed_top = 0;
   std::vector<Param> params;
@@ -260,7 +264,22 @@ class Step {
   }
   void with_workspace(mk::GemmArgs& a) {
     a.workspace = ws_; a.workspace_bytes = ws_bytes_;
-    gemm(a);
+    if (dry_) return;
+    // per-kernel timing brackets work on the main stream only, so it keeps everything there
+    if (!c_->side || c_->prof_on) { gemm(a); return; }
+    if (hipEventRecord(c_->ev_fork, st_) != hipSuccess || hipStreamWaitEvent(c_->side, c_->ev_fork, 0) != hipSuccess)
+      throw StepError{MIMOSE_ERR_HIP, "fork to the weight-gradient stream failed"};
+    if (!mk::gemm(dt_, a, c_->side)) throw StepError{MIMOSE_ERR_INVALID_ARG, "gemm: unsupported alignment"};
+    side_busy_ = true;
+  }
+  // the main stream waits for every weight-gradient product issued so far (before their inputs
+  // or scratch are reused, and before anything reads the gradients)
+  bool side_busy_ = false;
+  void join() {
+    if (!side_busy_) return;
+    if (hipEventRecord(c_->ev_join, c_->side) != hipSuccess || hipStreamWaitEvent(st_, c_->ev_join, 0) != hipSuccess)
+      throw StepError{MIMOSE_ERR_HIP, "join of the weight-gradient stream failed"};
+    side_busy_ = false;
   }
   void ln_fwd(const void* x, int gi, int bi, void* y, bool x_f32 = false) {
     Timed t(this, MIMOSE_K_LN_FWD, (x_f32 ? 6.0 : 2.0 * es_d()) * T_ * f_.hidden);
@@ -391,10 +410,12 @@ void Step::layer_backward(int l, LayerActs& A) {
   wgrad(dact, F, F, A.u, H, p.w1, p.b1);
   if (f_.pre_ln) {
     dgrad(dact, F, F, p.w1, gB_, H);                                          // gB = d LN2(u)
+    join();
     ar.pop_to(m0);
     ln_bwd(gB_, A.s1, p.ln2g, p.ln2b, gB_, gA_);                              // gB = d u
   } else {
     dgrad(dact, F, F, p.w1, gB_, H, oA_, wide_);                              // gB = d u = d s2 + FFN path
+    join();
     ar.pop_to(m0);
     ln_bwd(gB_, A.s1, p.ln1g, p.ln1b, oB_, nullptr, wide_, wide_);            // oB = d s1
   }
@@ -411,10 +432,12 @@ void Step::layer_backward(int l, LayerActs& A) {
   wgrad(dqkv, 3 * H, 3 * H, a, H, p.wqkv, p.bqkv);
   if (f_.pre_ln) {
     dgrad(dqkv, 3 * H, 3 * H, p.wqkv, gA_, H);                                // gA = d LN1(x)
+    join();
     ar.pop_to(m0);
     ln_bwd(gA_, A.x, p.ln1g, p.ln1b, gA_, gB_);                               // gA = d x
   } else {
     dgrad(dqkv, 3 * H, 3 * H, p.wqkv, gA_, H, oB_, wide_);                    // gA = d x = d s1 + attention path
+    join();
     ar.pop_to(m0);
   }
 }
@@ -468,6 +491,7 @@ void Step::head(float* loss_dev) {
     gemm(a);
   }
   if (f_.pre_ln) ln_bwd(dhs, hlast, c_->i_fg, c_->i_fb, gA_, nullptr);
+  join();
 }
 
 void Step::embed_backward() {
@@ -523,6 +547,7 @@ void Step::run(const int32_t* tokens, const int32_t* labels, float* loss_out) {
     w_bytes[l] = ar.section_high() - m;
     ar.pop_to(A.mark);
   }
+  join();
   embed_backward();
   if (!dry_) {
     HIPCHK(c_, hipMemcpyAsync(c_->loss_host, loss_dev, 4, hipMemcpyDeviceToHost, st_));
@@ -599,7 +624,7 @@ int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, int32_t
   } catch (const OomError& e) {
     c->prof_pending.clear(); c->ev_used = 0;
     c->arena.pop_to(c->fixed_top);
-    if (!dry && c->has_device) (void)hipStreamSynchronize(c->stream);
+    if (!dry && c->has_device) { if (c->side) (void)hipStreamSynchronize(c->side); (void)hipStreamSynchronize(c->stream); }
     char buf[160];
     snprintf(buf, sizeof buf, "allocation of %llu bytes at %llu exceeds the budget of %llu bytes",
              (unsigned long long)e.want, (unsigned long long)e.top, (unsigned long long)e.cap);
@@ -607,7 +632,7 @@ int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, int32_t
   } catch (const StepError& e) {
     c->prof_pending.clear(); c->ev_used = 0;
     c->arena.pop_to(c->fixed_top);
-    if (!dry && c->has_device) (void)hipStreamSynchronize(c->stream);
+    if (!dry && c->has_device) { if (c->side) (void)hipStreamSynchronize(c->side); (void)hipStreamSynchronize(c->stream); }
     return fail(c, e.code, e.msg);
   }
   const uint64_t pk = c->arena.high();
@@ -698,6 +723,10 @@ int mimose_init(const mimose_model_cfg* cfg, uint64_t mem_budget_bytes, void* ar
   if (c->has_device) {
     if (hipHostMalloc((void**)&c->loss_host, 256, hipHostMallocDefault) != hipSuccess)
       return fail(nullptr, MIMOSE_ERR_HIP, "hipHostMalloc failed");
+    if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess)
+      return fail(nullptr, MIMOSE_ERR_HIP, "creating the weight-gradient stream failed");
     // gradients start at zero so that a read before the first step is defined
     mk::fill_zero(c->params.front().g, (int64_t)((char*)c->arena.alloc(0) - (char*)c->params.front().g), c->stream);
     if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(nullptr, MIMOSE_ERR_HIP, "device initialisation failed");
@@ -833,7 +862,11 @@ void mimose_destroy(mimose_ctx* c) {
   if (!c) return;
   if (c->has_device) {
     (void)hipStreamSynchronize(c->stream);
+    if (c->side) (void)hipStreamSynchronize(c->side);
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
+    if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+    if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+    if (c->side) (void)hipStreamDestroy(c->side);
     if (c->stage) (void)hipHostFree(c->stage);
     if (c->loss_host) (void)hipHostFree(c->loss_host);
   }
