@@ -22,7 +22,7 @@ paper's order:
     layer of the largest bucket is taken;
   * plan cache (Section 5).
 
-Readings where the paper is silent (documented in the design notes):
+Readings where the paper is silent:
   - the per-layer quantity the algorithm ranks and subtracts is the droppable
     part s_l = a_l - b_l (bytes kept when not checkpointed minus bytes kept when
     checkpointed);
