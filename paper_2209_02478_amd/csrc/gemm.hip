@@ -450,9 +450,9 @@ bool gemm(int dtype, const GemmArgs& g, hipStream_t st) {
                    (!g.resid || ((g.ldr & 3) == 0 && (((uintptr_t)g.resid) & 7) == 0)) &&
                    (!g.bias || (((uintptr_t)g.bias) & 7) == 0) &&
                    (!g.gelu_out || (((uintptr_t)g.gelu_out) & 7) == 0);
-  // both operands m-major (weight gradients): the direct-to-LDS pipeline measures faster there;
-  // the register-staged kernel below is ahead when a k-major operand is involved
-  if (!g.a_kmajor && !g.b_kmajor && launch_bgemm_dma(p, vec, st)) {
+  // B m-major (weight gradients, data gradients): the direct-to-LDS pipeline measures faster there;
+  // the register-staged kernel below is ahead when both operands are k-major (forward)
+  if (!g.b_kmajor && launch_bgemm_dma(p, vec, st)) {
     if (p.splits > 1) launch_splitk_reduce(p, st);
     return true;
   }

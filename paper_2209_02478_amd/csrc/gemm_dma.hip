@@ -35,6 +35,14 @@ __device__ __attribute__((aligned(16))) uint32_t g_zero_chunk[4] = {0u, 0u, 0u, 
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
+// One wave-level direct load: every lane's 16 bytes at `g` land at lds + 16 * lane.  Written as
+// inline assembly so that the compiler does not track it: the ring's waits are placed by hand
+// below (the compiler's own tracking drains the whole ring once per turn).
+__device__ __forceinline__ void direct_load(const bf16_t* g, const bf16_t* lds) {
+  const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void*)lds);
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(base) : "memory", "m0");
+}
+
 // s_waitcnt immediate: at most n vector-memory loads outstanding and no LDS operation pending
 // (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14)
 constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (0 << 8) | ((n >> 4) << 14); }
@@ -161,8 +169,8 @@ __global__ __launch_bounds__(256, 2) void bgemm_dma_kernel(GemmDev p, int tiles_
         if (srcB[j].k_first + kt * BK >= p.K) gb = (const bf16_t*)g_zero_chunk;
       }
       const int off = (wave * DMA_PER_WAVE + j) * 512;                // elements: 1 KB per wave-level load
-      __builtin_amdgcn_global_load_lds(ga, (lds_void*)(a_stage + off), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(gb, (lds_void*)(b_stage + off), 16, 0, 0);
+      direct_load(ga, a_stage + off);
+      direct_load(gb, b_stage + off);
     }
   };
   auto compute = [&](const bf16_t* stage) {
