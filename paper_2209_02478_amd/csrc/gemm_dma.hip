@@ -38,10 +38,13 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 // One wave-level direct load: every lane's 16 bytes at `g` land at lds + 16 * lane.  Written as
 // inline assembly so that the compiler does not track it: the ring's waits are placed by hand
 // below (the compiler's own tracking drains the whole ring once per turn).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"      // m0 is a reserved register: named as clobbered on purpose
 __device__ __forceinline__ void direct_load(const bf16_t* g, const bf16_t* lds) {
   const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void*)lds);
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(base) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 // s_waitcnt immediate: at most n vector-memory loads outstanding and no LDS operation pending
 // (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14)

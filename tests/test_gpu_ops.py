@@ -107,6 +107,45 @@ def test_gemm_epilogues(dtype):
     close(host(rs), quant(dY, dtype).sum(0), 0, k=40.0)
 
 
+@pytest.mark.parametrize("a_k,b_k", [(1, 1), (1, 0), (0, 0), (0, 1)])
+def test_gemm_many_tiles(a_k, b_k):
+    """More output tiles than the chip has block slots (several rounds of the tile -> block map),
+    ragged in every dimension, with bias, residual and A row sums."""
+    dtype, M, N, K = 1, 5001, 4100, 104
+    rng = np.random.default_rng(77 + 2 * a_k + b_k)
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    B = rng.standard_normal((N, K)).astype(np.float32)
+    bias = rng.standard_normal(N).astype(np.float32)
+    resid = rng.standard_normal((M, N)).astype(np.float32)
+    up = lambda v: (v + 7) // 8 * 8
+    def lay(X, kmajor):
+        R, Kk = X.shape
+        if kmajor:
+            buf = np.zeros((R, up(Kk)), np.float32); buf[:, :Kk] = X
+            return buf, up(Kk)
+        buf = np.zeros((Kk, up(R)), np.float32); buf[:, :R] = X.T
+        return buf, up(R)
+    Ab, lda = lay(A, a_k)
+    Bb, ldb = lay(B, b_k)
+    dA, dB, dbias, dres = dev(Ab, dtype), dev(Bb, dtype), dev(bias, dtype), dev(resid, dtype)
+    ldc = up(N) + 8
+    C = torch.full((M, ldc), 7.0, dtype=dA.dtype, device=DEV)
+    rs = torch.full((M,), 9.0, dtype=torch.float32, device=DEV)
+    mi.mimose_op_gemm(dtype, dA, lda, a_k, dB, ldb, b_k, C, ldc, 0, M, N, K, bias=dbias, resid=dres, ldr=N,
+                      a_rowsum=rs)
+    sync()
+    got = host(C)
+    assert np.all(got[:, N:] == 7.0), "wrote outside the N columns"
+    ref = quant(A, dtype).astype(np.float64) @ quant(B, dtype).astype(np.float64).T
+    close(got[:, :N], ref + quant(bias, dtype) + quant(resid, dtype), dtype, k=2.0)
+    close(host(rs), quant(A, dtype).astype(np.float64).sum(1), 0, k=20.0)
+    # plain fp32 output
+    Cf = torch.full((M, N), 7.0, dtype=torch.float32, device=DEV)
+    mi.mimose_op_gemm(dtype, dA, lda, a_k, dB, ldb, b_k, Cf, N, 1, M, N, K)
+    sync()
+    close(host(Cf), ref, 0, k=20.0)
+
+
 def test_gemm_rejects_misaligned_bf16():
     a = torch.zeros(64 * 20, dtype=torch.bfloat16, device=DEV)
     with pytest.raises(mi.MimoseError):
