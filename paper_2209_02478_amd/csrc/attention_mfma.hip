@@ -34,7 +34,7 @@ constexpr int ROWS_PER_BLOCK = 128;
 __device__ __forceinline__ bf16x8 ld_frag(const bf16_t* p) { return *(const bf16x8*)p; }
 
 __device__ __forceinline__ uint32_t pack2(float a, float b) {
-  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+  return pack_bf16x2(a, b);
 }
 // registers 8c .. 8c+7 of an accumulator as a bf16 operand
 __device__ __forceinline__ bf16x8 regs_to_frag(const f32x16& v, int c) {

@@ -62,15 +62,15 @@ __device__ __forceinline__ void epilogue4(const GemmDev& p, int m, int n, float 
     return;
   }
   uint2 w;
-  w.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-  w.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+  w.x = pack_bf16x2(v[0], v[1]);
+  w.y = pack_bf16x2(v[2], v[3]);
   *(uint2*)((bf16_t*)p.C + o) = w;
   if (p.gelu) {
     float g[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) g[e] = p.gelu == GELU_TANH ? gelu_tanh(v[e]) : gelu_erf_bf16(v[e]);
-    w.x = (uint32_t)f32_to_bf16(g[0]) | ((uint32_t)f32_to_bf16(g[1]) << 16);
-    w.y = (uint32_t)f32_to_bf16(g[2]) | ((uint32_t)f32_to_bf16(g[3]) << 16);
+    w.x = pack_bf16x2(g[0], g[1]);
+    w.y = pack_bf16x2(g[2], g[3]);
     *(uint2*)((bf16_t*)p.gelu_out + o) = w;
   }
 }
