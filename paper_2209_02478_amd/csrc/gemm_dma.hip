@@ -119,7 +119,7 @@ __device__ __forceinline__ float rowsum_part(const bf16_t* tile, int tid) {
 
 }  // namespace
 
-template <bool AK, bool BKM, bool VEC, bool KTAIL>
+template <bool AK, bool BKM, bool KTAIL>
 __global__ __launch_bounds__(256, 2) void bgemm_dma_kernel(GemmDev p, int tiles_n, int total, int per_xcd) {
   // one named array per ring stage (A tile, then B tile): the compiler then knows which direct
   // loads a read depends on and leaves the newer ones in flight
@@ -227,76 +227,48 @@ __global__ __launch_bounds__(256, 2) void bgemm_dma_kernel(GemmDev p, int tiles_
   }
 #undef MIMOSE_GEMM_STEP
 
+  GemmDev q = p;
+  float* rowsum = p.a_rowsum;
   if (p.splits > 1) {
-    // raw fp32 tile and row sums of this k range; a second kernel adds the parts in order
-    float* part = p.partial + (int64_t)split * p.M * p.N;
-    float* rpart = p.partial + (int64_t)p.splits * p.M * p.N + (int64_t)split * p.M;
-    if (do_rowsum) {
-      const float tot = rs + __shfl_xor(rs, 1, 64);
-      const int m = m0 + (tid >> 1);
-      if ((tid & 1) == 0 && m < p.M) rpart[m] = tot;
-    }
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int m = m0 + wm * 64 + i * 32 + (lane & 31);
-          const int n = n0 + wn * 64 + j * 32 + 8 * g + 4 * (lane >> 5);
-          if (m < p.M) {
-            float* dst = part + (int64_t)m * p.N + n;
-            if (n + 4 <= p.N && (p.N & 3) == 0) {
-              *(float4*)dst = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-            } else {
-#pragma unroll
-              for (int e = 0; e < 4; ++e) if (n + e < p.N) dst[e] = acc[i][j][4 * g + e];
-            }
-          }
-        }
-    return;
+    // raw fp32 tile and row sums of this k range, as a plain matrix [M][N] in the workspace (which
+    // is 16-byte aligned); a second kernel adds the parts in order
+    q.C = p.partial + (int64_t)split * p.M * p.N;
+    q.ldc = p.N; q.c_f32 = 1; q.bias = nullptr; q.resid = nullptr; q.gelu = GELU_NONE;
+    q.vec = (p.N & 3) == 0;
+    rowsum = p.partial + (int64_t)p.splits * p.M * p.N + (int64_t)split * p.M;
   }
   if (do_rowsum) {
     const float tot = rs + __shfl_xor(rs, 1, 64);
     const int m = m0 + (tid >> 1);
-    if ((tid & 1) == 0 && m < p.M) p.a_rowsum[m] = tot;
+    if ((tid & 1) == 0 && m < p.M) rowsum[m] = tot;
   }
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int m = m0 + wm * 64 + i * 32 + (lane & 31);
-        const int n = n0 + wn * 64 + j * 32 + 8 * g + 4 * (lane >> 5);
-        epilogue4<VEC>(p, m, n, acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-      }
+  static_assert(sizeof(st0) >= 64 * 64 * sizeof(float), "staging needs 16 KB per wave");
+  float* wstage = (float*)(wave == 0 ? st0 : wave == 1 ? st1 : wave == 2 ? st2 : st3);   // 16 KB each
+  store_tile(q, acc, m0 + wm * 64, n0 + wn * 64, lane, wstage);
 }
 
 template <bool AK, bool BKM>
-static void launch_t(const GemmDev& p, bool vec, hipStream_t st) {
+static void launch_t(const GemmDev& p, hipStream_t st) {
   const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
   const int total = tiles_m * tiles_n * p.splits, per = (total + 7) / 8;
   const bool ktail = p.K % BK != 0;
   dim3 grid(per * 8), block(256);
-#define L_(V, KT) hipLaunchKernelGGL((bgemm_dma_kernel<AK, BKM, V, KT>), grid, block, 0, st, p, tiles_n, total, per)
-  if (vec) { if (ktail) L_(true, true); else L_(true, false); }
-  else { if (ktail) L_(false, true); else L_(false, false); }
-#undef L_
+  if (ktail) hipLaunchKernelGGL((bgemm_dma_kernel<AK, BKM, true>), grid, block, 0, st, p, tiles_n, total, per);
+  else hipLaunchKernelGGL((bgemm_dma_kernel<AK, BKM, false>), grid, block, 0, st, p, tiles_n, total, per);
 }
 
 // Requirements: 16-byte chunks must be wholly inside or wholly outside the matrix along the
 // reduction index of a k-major operand (K % 8 == 0), and physically present along the rows of an
 // m-major operand (its leading dimension covers the row count rounded up to 8).
-bool launch_bgemm_dma(const GemmDev& p, bool vec, hipStream_t st) {
+bool launch_bgemm_dma(const GemmDev& p, hipStream_t st) {
   auto up8 = [](int64_t v) { return (v + 7) / 8 * 8; };
   if ((p.a_k || p.b_k) && (p.K & 7)) return false;
   if (!p.a_k && p.lda < up8(p.M)) return false;
   if (!p.b_k && p.ldb < up8(p.N)) return false;
-  if (p.a_k && p.b_k) launch_t<true, true>(p, vec, st);
-  else if (p.a_k && !p.b_k) launch_t<true, false>(p, vec, st);
-  else if (!p.a_k && p.b_k) launch_t<false, true>(p, vec, st);
-  else launch_t<false, false>(p, vec, st);
+  if (p.a_k && p.b_k) launch_t<true, true>(p, st);
+  else if (p.a_k && !p.b_k) launch_t<true, false>(p, st);
+  else if (!p.a_k && p.b_k) launch_t<false, true>(p, st);
+  else launch_t<false, false>(p, st);
   return true;
 }
 
