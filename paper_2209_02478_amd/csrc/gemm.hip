@@ -316,7 +316,7 @@ __global__ __launch_bounds__(256, 2) void bgemm_kernel(GemmDev p, int tiles_n, i
     if ((tid & 1) == 0 && m < p.M) rowsum[m] = tot;
   }
   static_assert(2 * (TA::ELEMS + TB::ELEMS) * sizeof(bf16_t) >= 4 * 64 * 64 * sizeof(float), "staging needs 16 KB per wave");
-  store_tile(q, acc, m0 + wm * 64, n0 + wn * 64, lane, (float*)smem_raw + wave * 4096);
+  store_tile<1>(q, acc, m0 + wm * 64, n0 + wn * 64, lane, (float*)smem_raw + wave * 4096);
 }
 
 // C[m][n] = sum over splits (in order) of partial tiles; row sums likewise.  fp32 output only.

@@ -63,66 +63,76 @@ __device__ __forceinline__ u32x4 pack_bf16x8(const float (&f)[8]) {
   return w;
 }
 
-// m0w, n0w: first row / column of this wave's 64 x 64 part; wstage: 16 KB of LDS owned by this
-// wave.  Every thread of the block must call it.
+// m0w, n0w: first row / column of this wave's 64 x 64 part; wstage: 16 KB / HALVES of LDS owned
+// by this wave (HALVES == 2: the two 32-column halves take turns in 8 KB).  Every thread of the
+// block must call it.
+template <int HALVES>
 __device__ __forceinline__ void store_tile(const GemmDev& p, const f32x16 (&acc)[2][2], int m0w, int n0w, int lane,
                                            float* wstage) {
-  __syncthreads();                                              // all waves are done reading operand tiles
+  constexpr int COLS = 64 / HALVES, CHUNKS = COLS / 4, LPR = COLS / 8;   // staged columns, float4 chunks, lanes per row
+  constexpr int RPI = 64 / LPR;                                          // rows per loop iteration
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int h = 0; h < HALVES; ++h) {
+    __syncthreads();                                            // operand tiles / the previous half are dead
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int row = i * 32 + (lane & 31), c = j * 8 + 2 * g + (lane >> 5);
-        *(float4*)&wstage[row * 64 + ((c ^ (row & 15)) << 2)] =
-            make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+      for (int jj = 0; jj < 2 / HALVES; ++jj)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int j = HALVES == 2 ? h : jj;
+          const int row = i * 32 + (lane & 31), c = jj * 8 + 2 * g + (lane >> 5);
+          *(float4*)&wstage[row * COLS + ((c ^ (row & (CHUNKS - 1))) << 2)] =
+              make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+        }
+    __syncthreads();
+    const int nh = n0w + h * COLS;
+    if (!p.vec) {                                               // unaligned operands: one element at a time
+      for (int idx = lane; idx < 64 * COLS; idx += 64) {
+        const int row = idx / COLS, col = idx % COLS;
+        epilogue<bf16_t>(p, m0w + row, nh + col,
+                         wstage[row * COLS + ((((col >> 2) ^ (row & (CHUNKS - 1))) << 2) | (col & 3))]);
       }
-  __syncthreads();
-  if (!p.vec) {                                                 // unaligned operands: one element at a time
-    for (int idx = lane; idx < 64 * 64; idx += 64) {
-      const int row = idx >> 6, col = idx & 63;
-      epilogue<bf16_t>(p, m0w + row, n0w + col, wstage[row * 64 + ((((col >> 2) ^ (row & 15)) << 2) | (col & 3))]);
-    }
-    return;
-  }
-  const int n = n0w + (lane & 7) * 8, c0 = 2 * (lane & 7);
-  for (int it = 0; it < 8; ++it) {
-    const int row = it * 8 + (lane >> 3), m = m0w + row;
-    if (m >= p.M || n >= p.N) continue;
-    const float4 lo = *(const float4*)&wstage[row * 64 + ((c0 ^ (row & 15)) << 2)];
-    const float4 hi = *(const float4*)&wstage[row * 64 + (((c0 + 1) ^ (row & 15)) << 2)];
-    float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-    if (n + 8 > p.N) {                                          // ragged end of the row
-      for (int e = 0; e < 8; ++e) epilogue<bf16_t>(p, m, n + e, v[e]);
       continue;
     }
-    float f[8];
-    if (p.bias) {
-      unpack_bf16x8(*(const u32x4*)((const bf16_t*)p.bias + n), f);
+    const int n = nh + (lane % LPR) * 8, c0 = 2 * (lane % LPR);
+    for (int it = 0; it < 64 / RPI; ++it) {
+      const int row = it * RPI + lane / LPR, m = m0w + row;
+      if (m >= p.M || n >= p.N) continue;
+      const float4 lo = *(const float4*)&wstage[row * COLS + ((c0 ^ (row & (CHUNKS - 1))) << 2)];
+      const float4 hi = *(const float4*)&wstage[row * COLS + (((c0 + 1) ^ (row & (CHUNKS - 1))) << 2)];
+      float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+      if (n + 8 > p.N) {                                        // ragged end of the row
+        for (int e = 0; e < 8; ++e) epilogue<bf16_t>(p, m, n + e, v[e]);
+        continue;
+      }
+      float f[8];
+      if (p.bias) {
+        unpack_bf16x8(*(const u32x4*)((const bf16_t*)p.bias + n), f);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] += f[e];
-    }
-    if (p.resid) {
-      unpack_bf16x8(*(const u32x4*)((const bf16_t*)p.resid + (int64_t)m * p.ldr + n), f);
+        for (int e = 0; e < 8; ++e) v[e] += f[e];
+      }
+      if (p.resid) {
+        unpack_bf16x8(*(const u32x4*)((const bf16_t*)p.resid + (int64_t)m * p.ldr + n), f);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] += f[e];
-    }
-    const int64_t o = (int64_t)m * p.ldc + n;
-    if (p.c_f32) {
-      *(float4*)((float*)p.C + o) = make_float4(v[0], v[1], v[2], v[3]);
-      *(float4*)((float*)p.C + o + 4) = make_float4(v[4], v[5], v[6], v[7]);
-      continue;
-    }
-    *(u32x4*)((bf16_t*)p.C + o) = pack_bf16x8(v);
-    if (p.gelu == GELU_ERF) {
+        for (int e = 0; e < 8; ++e) v[e] += f[e];
+      }
+      const int64_t o = (int64_t)m * p.ldc + n;
+      if (p.c_f32) {
+        *(float4*)((float*)p.C + o) = make_float4(v[0], v[1], v[2], v[3]);
+        *(float4*)((float*)p.C + o + 4) = make_float4(v[4], v[5], v[6], v[7]);
+        continue;
+      }
+      *(u32x4*)((bf16_t*)p.C + o) = pack_bf16x8(v);
+      if (p.gelu == GELU_ERF) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) f[e] = gelu_erf_bf16(v[e]);
-      *(u32x4*)((bf16_t*)p.gelu_out + o) = pack_bf16x8(f);
-    } else if (p.gelu == GELU_TANH) {
+        for (int e = 0; e < 8; ++e) f[e] = gelu_erf_bf16(v[e]);
+        *(u32x4*)((bf16_t*)p.gelu_out + o) = pack_bf16x8(f);
+      } else if (p.gelu == GELU_TANH) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) f[e] = gelu_tanh_bf16(v[e]);
-      *(u32x4*)((bf16_t*)p.gelu_out + o) = pack_bf16x8(f);
+        for (int e = 0; e < 8; ++e) f[e] = gelu_tanh_bf16(v[e]);
+        *(u32x4*)((bf16_t*)p.gelu_out + o) = pack_bf16x8(f);
+      }
     }
   }
 }

@@ -2,8 +2,9 @@
 //
 // C[M,N] = sum_k A(m,k) B(n,k), 128 x 128 x 32 tiles, 4 waves (2 x 2), each wave 64 x 64 as 2 x 2
 // MFMA 32x32x16 tiles.  Operand tiles never pass through registers: every lane asks the memory
-// pipe to drop 16 bytes straight into LDS, four k tiles deep (a ring of four LDS stages, three
-// tiles in flight while one is multiplied), so two blocks per CU keep ~96 KB of loads in flight.
+// pipe to drop 16 bytes straight into LDS, into a ring of three stages (two tiles in flight while
+// one is multiplied).  The kernel needs ~140 registers and 48 KB of LDS, so three blocks share a
+// CU and fill each other's waits.
 //
 // A wave-level direct load writes 64 x 16 bytes contiguously, so tiles are stored unpadded and
 // bank conflicts are avoided by permuting 16-byte chunks inside a row (the lane -> global
@@ -15,9 +16,9 @@
 // zeros, so edge tiles need no special loop.
 //
 // Synchronisation is explicit (no fences): before the barrier of k tile t every wave waits until
-// its own loads of tile t have landed (s_waitcnt vmcnt leaves the two newer tiles in flight);
-// after the barrier all waves have also finished reading the stage of tile t-1, which is then
-// refilled with tile t+3.  The reduction order over k is fixed by the shape alone.
+// its own loads of tile t have landed (s_waitcnt vmcnt leaves the newer tile in flight); after
+// the barrier all waves have also finished reading the stage of tile t-1, which is then refilled
+// with tile t+2.  The reduction order over k is fixed by the shape alone.
 #include "gemm_device.h"
 
 namespace mk {
@@ -25,7 +26,7 @@ namespace mk {
 namespace {
 
 constexpr int BM = 128, BN = 128, BK = 32;
-constexpr int STAGES = 4;
+constexpr int STAGES = 3;
 constexpr int TILE_ELEMS = 128 * BK;             // either layout: 8 KB
 constexpr int GROUP_M = 8;
 constexpr int DMA_PER_WAVE = TILE_ELEMS * 2 / 1024 / 4;   // 1 KB direct loads per wave and operand tile: 2
@@ -80,22 +81,28 @@ __device__ __forceinline__ Src make_src(const bf16_t* X, int64_t ldx, int R, int
   return s;
 }
 
-// fragment for tile rows rbase + lane%32, reduction indices 16*ks + 8*(lane/32) .. +7
+// Fragment for tile rows rbase + lane%32, reduction indices 16*ks + 8*(lane/32) .. +7: element
+// offset of its first read inside the tile (computed once per thread; the stage base and, for
+// the second read of an m-major fragment, a constant are added at the read), then the read.
 template <bool KM>
-__device__ __forceinline__ bf16x8 frag(const bf16_t* tile, int rbase, int ks, int lane) {
+__device__ __forceinline__ int frag_offset(int rbase, int ks, int lane) {
   if (KM) {
     const int r = rbase + (lane & 31);
     const int pc = (2 * ks + (lane >> 5)) ^ ((lane >> 2) & 3);     // (r >> 2) & 3 == (lane >> 2) & 3: rbase % 32 == 0
-    return *(const bf16x8*)&tile[r * BK + pc * 8];
+    return r * BK + pc * 8;
   }
   const int kq = (lane & 15) >> 2;                                  // k row & 3 of this lane's source rows
   const int q = ks * 16 + 8 * (lane >> 5) + kq;
   const int mc = (rbase >> 3) + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
-  const int off = (mc ^ (4 * kq)) * 8 + (lane & 1) * 4;
-  struct { s16x4 lo, hi; } r;
-  r.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)&tile[q * 128 + off]);
-  r.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)&tile[(q + 4) * 128 + off]);
-  return __builtin_bit_cast(bf16x8, r);
+  return q * 128 + (mc ^ (4 * kq)) * 8 + (lane & 1) * 4;
+}
+template <bool KM>
+__device__ __forceinline__ bf16x8 frag_read(const bf16_t* at) {
+  if (KM) return *(const bf16x8*)at;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)at);
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(at + 4 * 128));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
 // sum over the tile's reduction indices of tile row tid/2 (two threads per row, any fixed order)
@@ -120,11 +127,11 @@ __device__ __forceinline__ float rowsum_part(const bf16_t* tile, int tid) {
 }  // namespace
 
 template <bool AK, bool BKM, bool KTAIL>
-__global__ __launch_bounds__(256, 2) void bgemm_dma_kernel(GemmDev p, int tiles_n, int total, int per_xcd) {
-  // one named array per ring stage (A tile, then B tile): the compiler then knows which direct
-  // loads a read depends on and leaves the newer ones in flight
-  __shared__ __attribute__((aligned(1024))) bf16_t st0[2 * TILE_ELEMS], st1[2 * TILE_ELEMS], st2[2 * TILE_ELEMS],
-      st3[2 * TILE_ELEMS];
+__global__ __launch_bounds__(256, 3) void bgemm_dma_kernel(GemmDev p, int tiles_n, int total, int per_xcd) {
+  // ring of STAGES stages, each an A tile followed by a B tile; the stage of a k tile is chosen at
+  // run time, so fragment addresses are a per-thread offset plus the stage base (few registers)
+  constexpr int STAGE_ELEMS = 2 * TILE_ELEMS;
+  __shared__ __attribute__((aligned(1024))) bf16_t ring[STAGES * STAGE_ELEMS];
   const int unit = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (unit >= total) return;
   const int t = unit / p.splits, split = unit - t * p.splits;
@@ -176,56 +183,65 @@ __global__ __launch_bounds__(256, 2) void bgemm_dma_kernel(GemmDev p, int tiles_
       direct_load(gb, b_stage + off);
     }
   };
-  auto compute = [&](const bf16_t* stage) {
-    const bf16_t* at = stage;
-    const bf16_t* bt = stage + TILE_ELEMS;
-    if (do_rowsum) rs += rowsum_part<AK>(at, tid);
-    __builtin_amdgcn_iglp_opt(0);
+  // The MFMAs of a tile's second k half are held back until the next tile's first fragments have
+  // been requested (after that tile's barrier), so the matrix pipe has work while they travel.
+  bf16x8 pa[2], pb[2];                                                // fragments of the pending half
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 af[2], bfr[2];
+  for (int i = 0; i < 2; ++i) { pa[i] = bf16x8{}; pb[i] = bf16x8{}; } // zeros: the first round adds nothing
+  auto mfma4 = [&](const bf16x8 (&af)[2], const bf16x8 (&bfr)[2]) {
+    // roles swapped (B tile rows feed the MFMA's A side): a lane then owns one output row m
+    // and, per register group, four consecutive columns n
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        af[i] = frag<AK>(at, wm * 64 + i * 32, ks, lane);
-        bfr[i] = frag<BKM>(bt, wn * 64 + i * 32, ks, lane);
-      }
-      // roles swapped (B tile rows feed the MFMA's A side): a lane then owns one output row m
-      // and, per register group, four consecutive columns n
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
-    }
+      for (int j = 0; j < 2; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
   };
-  // One k tile: wait for own loads of tile kt (leaving up to two newer tiles in flight), meet
-  // the other waves, refill the stage that was multiplied last, multiply.
-  constexpr int PER_TILE = 2 * DMA_PER_WAVE;                          // direct loads per thread and k tile
-#define MIMOSE_GEMM_STEP(KT, CUR, FILL)                                                       \
-  {                                                                                           \
-    if ((KT) + 2 < nk) __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * PER_TILE));                   \
-    else if ((KT) + 1 < nk) __builtin_amdgcn_s_waitcnt(vmcnt_imm(PER_TILE));                  \
-    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                                            \
-    __builtin_amdgcn_s_barrier();                                                             \
-    if ((KT) + 3 < nk) issue(FILL, (KT) + 3);                                                 \
-    compute(CUR);                                                                             \
-  }
-
-  if (nk > 0) {
-    issue(st0, 0);
-    if (nk > 1) issue(st1, 1);
-    if (nk > 2) issue(st2, 2);
-    for (int kt = 0; kt < nk; kt += 4) {
-      MIMOSE_GEMM_STEP(kt, st0, st3)
-      if (kt + 1 >= nk) break;
-      MIMOSE_GEMM_STEP(kt + 1, st1, st0)
-      if (kt + 2 >= nk) break;
-      MIMOSE_GEMM_STEP(kt + 2, st2, st1)
-      if (kt + 3 >= nk) break;
-      MIMOSE_GEMM_STEP(kt + 3, st3, st2)
+  int a_off[2][2], b_off[2][2];                                       // [k half][32-row block]
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      a_off[ks][i] = frag_offset<AK>(wm * 64 + i * 32, ks, lane);
+      b_off[ks][i] = TILE_ELEMS + frag_offset<BKM>(wn * 64 + i * 32, ks, lane);
     }
+  auto compute = [&](const bf16_t* stage) {
+    static_assert(BK == 32, "two k halves per tile");
+    if (do_rowsum) rs += rowsum_part<AK>(stage, tid);
+    __builtin_amdgcn_iglp_opt(0);
+    bf16x8 af[2], bfr[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      af[i] = frag_read<AK>(stage + a_off[0][i]);
+      bfr[i] = frag_read<BKM>(stage + b_off[0][i]);
+    }
+    mfma4(pa, pb);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      pa[i] = frag_read<AK>(stage + a_off[1][i]);
+      pb[i] = frag_read<BKM>(stage + b_off[1][i]);
+    }
+    mfma4(af, bfr);
+  };
+  // One k tile: wait for own loads of tile kt (leaving the newer tile in flight), meet the other
+  // waves, refill the stage that was multiplied last, multiply.
+  constexpr int PER_TILE = 2 * DMA_PER_WAVE;                          // direct loads per thread and k tile
+  static_assert(STAGES == 3, "one newer tile in flight while a tile is multiplied");
+  if (nk > 0) {
+    issue(ring, 0);
+    if (nk > 1) issue(ring + STAGE_ELEMS, 1);
+    int cur = 0;                                                      // stage of tile kt
+    for (int kt = 0; kt < nk; ++kt) {
+      if (kt + 1 < nk) __builtin_amdgcn_s_waitcnt(vmcnt_imm(PER_TILE));
+      else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+      __builtin_amdgcn_s_barrier();
+      const int fill = cur == 0 ? 2 : cur - 1;                        // stage of tile kt - 1 == stage of tile kt + 2
+      if (kt + 2 < nk) issue(ring + fill * STAGE_ELEMS, kt + 2);
+      compute(ring + cur * STAGE_ELEMS);
+      cur = cur == 2 ? 0 : cur + 1;
+    }
+    mfma4(pa, pb);
   }
-#undef MIMOSE_GEMM_STEP
 
   GemmDev q = p;
   float* rowsum = p.a_rowsum;
@@ -242,9 +258,9 @@ __global__ __launch_bounds__(256, 2) void bgemm_dma_kernel(GemmDev p, int tiles_
     const int m = m0 + (tid >> 1);
     if ((tid & 1) == 0 && m < p.M) rowsum[m] = tot;
   }
-  static_assert(sizeof(st0) >= 64 * 64 * sizeof(float), "staging needs 16 KB per wave");
-  float* wstage = (float*)(wave == 0 ? st0 : wave == 1 ? st1 : wave == 2 ? st2 : st3);   // 16 KB each
-  store_tile(q, acc, m0 + wm * 64, n0 + wn * 64, lane, wstage);
+  static_assert(sizeof(ring) >= 4 * 64 * 32 * sizeof(float), "staging needs 8 KB per wave");
+  float* wstage = (float*)ring + wave * 64 * 32;
+  store_tile<2>(q, acc, m0 + wm * 64, n0 + wn * 64, lane, wstage);
 }
 
 template <bool AK, bool BKM>
