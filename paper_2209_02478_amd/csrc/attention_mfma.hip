@@ -31,6 +31,11 @@ constexpr int TK = 64;         // rows of a streamed tile
 constexpr int LDT = 72;        // LDS row stride in elements (144 bytes)
 constexpr int ROWS_PER_BLOCK = 128;
 
+constexpr float LOG2E = 1.44269504088896340736f;
+// 2^x on the transcendental unit (v_exp_f32), no range fix-ups: arguments here are <= ~0 or the
+// result is multiplied by zero-gradient terms; -inf gives 0
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 __device__ __forceinline__ bf16x8 ld_frag(const bf16_t* p) { return *(const bf16x8*)p; }
 
 __device__ __forceinline__ uint32_t pack2(float a, float b) {
@@ -55,16 +60,18 @@ __device__ __forceinline__ bf16x8 ld_frag_t(const bf16_t (*tile)[LDT], int row, 
 
 // 128 threads bring one 64 x 64 tile (rows r0.., row stride ld, rows clamped to last) into LDS,
 // as is ([row][d]) and / or transposed ([d][row]).  t in [0,128): 4 rows x 8 columns each.
-template <bool NORMAL, bool TRANSPOSED>
-__device__ __forceinline__ void stage_tile(const bf16_t* src, int64_t ld, int r0, int last, int t,
-                                           bf16_t (*normal)[LDT], bf16_t (*transposed)[LDT]) {
+// Two steps, so that the loads of the next tile can fly while the current one is multiplied.
+__device__ __forceinline__ void fetch_tile(const bf16_t* src, int64_t ld, int r0, int last, int t, uint4 (&v)[4]) {
   const int rq = t >> 3, cb = t & 7;
-  uint4 v[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     int r = min(r0 + 4 * rq + j, last);
     v[j] = *(const uint4*)(src + (int64_t)r * ld + 8 * cb);
   }
+}
+template <bool NORMAL, bool TRANSPOSED>
+__device__ __forceinline__ void stash_tile(const uint4 (&v)[4], int t, bf16_t (*normal)[LDT], bf16_t (*transposed)[LDT]) {
+  const int rq = t >> 3, cb = t & 7;
   if (NORMAL) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) *(uint4*)&normal[4 * rq + j][8 * cb] = v[j];
@@ -112,7 +119,7 @@ __device__ __forceinline__ void store_rows(bf16_t* dst, const f32x16 (&acc)[2], 
 
 // ------------------------------------------------------------------ forward
 template <bool CAUSAL>
-__global__ __launch_bounds__(256) void fa_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
+__global__ __launch_bounds__(256, 2) void fa_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
                                                      float* __restrict__ lse, int L, int nh) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[TK][LDT];   // [key][d]
   __shared__ __attribute__((aligned(16))) bf16_t Vt[D][LDT];    // [d][key]
@@ -123,21 +130,27 @@ __global__ __launch_bounds__(256) void fa_fwd_kernel(const bf16_t* __restrict__ 
   const bf16_t* base = qkv + (int64_t)b * L * ld3 + hh * D;
   const int qi = blockIdx.x * ROWS_PER_BLOCK + wave * 32 + ql;
   const int qc = min(qi, L - 1);
-  const float scale = 0.125f;
+  const float scale = 0.125f, c2 = scale * LOG2E;    // exp(scale * s - x) == exp2(c2 * s - LOG2E * x)
 
   bf16x8 qf[4];
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) qf[kk] = ld_frag(base + (int64_t)qc * ld3 + 16 * kk + 8 * h);
   f32x16 o[2];
   zero(o[0]); zero(o[1]);
-  float m = -INFINITY, l = 0.f;
+  float m = -INFINITY, l = 0.f;                       // running maximum of the raw (unscaled) scores, sum of exps
   const int kend = CAUSAL ? min(L, (int)(blockIdx.x + 1) * ROWS_PER_BLOCK) : L;
 
+  // threads 0..127 stage K, the others V; the next tile's loads are in flight during the MFMAs
+  const bf16_t* mine = tid < 128 ? base + H : base + 2 * H;
+  const int t128 = tid & 127;
+  uint4 pre[4];
+  fetch_tile(mine, ld3, 0, L - 1, t128, pre);
   for (int k0 = 0; k0 < kend; k0 += TK) {
     __syncthreads();
-    if (tid < 128) stage_tile<true, false>(base + H, ld3, k0, L - 1, tid, Ks, nullptr);
-    else stage_tile<false, true>(base + 2 * H, ld3, k0, L - 1, tid - 128, nullptr, Vt);
+    if (tid < 128) stash_tile<true, false>(pre, t128, Ks, nullptr);
+    else stash_tile<false, true>(pre, t128, nullptr, Vt);
     __syncthreads();
+    if (k0 + TK < kend) fetch_tile(mine, ld3, k0 + TK, L - 1, t128, pre);
     f32x16 s[2];
     float mx = -INFINITY;
 #pragma unroll
@@ -146,24 +159,26 @@ __global__ __launch_bounds__(256) void fa_fwd_kernel(const bf16_t* __restrict__ 
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
         s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(&Ks[32 * kb + ql][16 * kk + 8 * h]), qf[kk], s[kb], 0, 0, 0);
+      if (CAUSAL || k0 + TK > L) {                    // only tiles that touch the mask pay for it
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = k0 + 32 * kb + 8 * (r >> 2) + 4 * h + (r & 3);
-        float v = s[kb][r] * scale;
-        if (key >= L || (CAUSAL && key > qi)) v = -INFINITY;
-        s[kb][r] = v;
-        mx = fmaxf(mx, v);
+        for (int r = 0; r < 16; ++r) {
+          const int key = k0 + 32 * kb + 8 * (r >> 2) + 4 * h + (r & 3);
+          if (key >= L || (CAUSAL && key > qi)) s[kb][r] = -INFINITY;
+        }
       }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float mnew = fmaxf(m, mx);
-    const float alpha = __expf(m - mnew);
+    const float mnew = fmaxf(m, mx);                  // finite: key 0 is visible to every query
+    const float alpha = fast_exp2((m - mnew) * c2);
+    const float off = -mnew * c2;
     float rs = 0.f;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float p = __expf(s[kb][r] - mnew);
+        const float p = fast_exp2(fmaf(s[kb][r], c2, off));
         s[kb][r] = p;
         rs += p;
       }
@@ -186,13 +201,13 @@ __global__ __launch_bounds__(256) void fa_fwd_kernel(const bf16_t* __restrict__ 
   }
   if (qi < L) {
     store_rows(ctx + ((int64_t)b * L + qi) * H + hh * D, o, h, 1.f / l);
-    if (h == 0) lse[(int64_t)bh * L + qi] = m + __logf(l);
+    if (h == 0) lse[(int64_t)bh * L + qi] = m * scale + __logf(l);
   }
 }
 
 // ------------------------------------------------------------------ dQ
 template <bool CAUSAL>
-__global__ __launch_bounds__(256) void fa_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
+__global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
                                                         const float* __restrict__ lse, const float* __restrict__ delta,
                                                         bf16_t* __restrict__ dqkv, int L, int nh) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[TK][LDT];   // [key][d]
@@ -213,16 +228,22 @@ __global__ __launch_bounds__(256) void fa_bwd_dq_kernel(const bf16_t* __restrict
     qf[kk] = ld_frag(base + (int64_t)qc * ld3 + 16 * kk + 8 * h);
     gf[kk] = ld_frag(dctx + ((int64_t)b * L + qc) * H + hh * D + 16 * kk + 8 * h);
   }
-  const float lse_q = lse[(int64_t)bh * L + qc], delta_q = delta[(int64_t)bh * L + qc];
+  const float c2 = scale * LOG2E;
+  const float nlse_q = -LOG2E * lse[(int64_t)bh * L + qc], delta_q = delta[(int64_t)bh * L + qc];
   f32x16 dq[2];
   zero(dq[0]); zero(dq[1]);
   const int kend = CAUSAL ? min(L, (int)(blockIdx.x + 1) * ROWS_PER_BLOCK) : L;
 
+  const bf16_t* mine = tid < 128 ? base + H : base + 2 * H;     // threads 0..127 stage K, the others V
+  const int t128 = tid & 127;
+  uint4 pre[4];
+  fetch_tile(mine, ld3, 0, L - 1, t128, pre);
   for (int k0 = 0; k0 < kend; k0 += TK) {
     __syncthreads();
-    if (tid < 128) stage_tile<true, true>(base + H, ld3, k0, L - 1, tid, Ks, Kt);
-    else stage_tile<true, false>(base + 2 * H, ld3, k0, L - 1, tid - 128, Vs, nullptr);
+    if (tid < 128) stash_tile<true, true>(pre, t128, Ks, Kt);
+    else stash_tile<true, false>(pre, t128, Vs, nullptr);
     __syncthreads();
+    if (k0 + TK < kend) fetch_tile(mine, ld3, k0 + TK, L - 1, t128, pre);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       f32x16 s, dp;
@@ -233,11 +254,13 @@ __global__ __launch_bounds__(256) void fa_bwd_dq_kernel(const bf16_t* __restrict
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(&Vs[32 * kb + ql][16 * kk + 8 * h]), gf[kk], dp, 0, 0, 0);
       }
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = k0 + 32 * kb + 8 * (r >> 2) + 4 * h + (r & 3);
-        const bool masked = key >= L || (CAUSAL && key > qi);
-        const float p = masked ? 0.f : __expf(s[r] * scale - lse_q);
-        s[r] = p * (dp[r] - delta_q);
+      for (int r = 0; r < 16; ++r) s[r] = fast_exp2(fmaf(s[r], c2, nlse_q)) * (dp[r] - delta_q);
+      if (CAUSAL || k0 + TK > L) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = k0 + 32 * kb + 8 * (r >> 2) + 4 * h + (r & 3);
+          if (key >= L || (CAUSAL && key > qi)) s[r] = 0.f;
+        }
       }
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
@@ -253,14 +276,14 @@ __global__ __launch_bounds__(256) void fa_bwd_dq_kernel(const bf16_t* __restrict
 
 // ------------------------------------------------------------------ dK, dV
 template <bool CAUSAL>
-__global__ __launch_bounds__(256) void fa_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
+__global__ __launch_bounds__(256, 2) void fa_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
                                                          const float* __restrict__ lse, const float* __restrict__ delta,
                                                          bf16_t* __restrict__ dqkv, int L, int nh) {
   __shared__ __attribute__((aligned(16))) bf16_t Qs[TK][LDT];   // [query][d]
   __shared__ __attribute__((aligned(16))) bf16_t Qt[D][LDT];    // [d][query]
   __shared__ __attribute__((aligned(16))) bf16_t Gs[TK][LDT];   // dO [query][d]
   __shared__ __attribute__((aligned(16))) bf16_t Gt[D][LDT];    // dO [d][query]
-  __shared__ float lse_s[TK], delta_s[TK];
+  __shared__ __attribute__((aligned(16))) float lse_s[TK], delta_s[TK];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, kl = lane & 31, h = lane >> 5;
   const int bh = blockIdx.y, b = bh / nh, hh = bh - b * nh;
   const int H = nh * D;
@@ -269,7 +292,7 @@ __global__ __launch_bounds__(256) void fa_bwd_dkv_kernel(const bf16_t* __restric
   const bf16_t* gbase = dctx + (int64_t)b * L * H + hh * D;
   const int ki = blockIdx.x * ROWS_PER_BLOCK + wave * 32 + kl;
   const int kc = min(ki, L - 1);
-  const float scale = 0.125f;
+  const float scale = 0.125f, c2 = scale * LOG2E;
 
   bf16x8 kf[4], vf[4];
 #pragma unroll
@@ -281,16 +304,27 @@ __global__ __launch_bounds__(256) void fa_bwd_dkv_kernel(const bf16_t* __restric
   zero(dk[0]); zero(dk[1]); zero(dv[0]); zero(dv[1]);
   const int qstart = CAUSAL ? blockIdx.x * ROWS_PER_BLOCK : 0;     // earlier queries never see these keys
 
-  for (int q0 = qstart; q0 < L; q0 += TK) {
-    __syncthreads();
-    if (tid < 128) stage_tile<true, true>(base, ld3, q0, L - 1, tid, Qs, Qt);
-    else stage_tile<true, true>(gbase, H, q0, L - 1, tid - 128, Gs, Gt);
+  const bf16_t* mine = tid < 128 ? base : gbase;                 // threads 0..127 stage Q, the others dO
+  const int64_t mine_ld = tid < 128 ? ld3 : (int64_t)H;
+  const int t128 = tid & 127;
+  uint4 pre[4];
+  float pre_lse = 0.f, pre_delta = 0.f;
+  auto fetch = [&](int q0) {
+    fetch_tile(mine, mine_ld, q0, L - 1, t128, pre);
     if (tid < TK) {
       const int q = min(q0 + tid, L - 1);
-      lse_s[tid] = lse[(int64_t)bh * L + q];
-      delta_s[tid] = delta[(int64_t)bh * L + q];
+      pre_lse = lse[(int64_t)bh * L + q];
+      pre_delta = delta[(int64_t)bh * L + q];
     }
+  };
+  if (qstart < L) fetch(qstart);
+  for (int q0 = qstart; q0 < L; q0 += TK) {
     __syncthreads();
+    if (tid < 128) stash_tile<true, true>(pre, t128, Qs, Qt);
+    else stash_tile<true, true>(pre, t128, Gs, Gt);
+    if (tid < TK) { lse_s[tid] = -LOG2E * pre_lse; delta_s[tid] = pre_delta; }   // lse_s: ready for exp2
+    __syncthreads();
+    if (q0 + TK < L) fetch(q0 + TK);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       f32x16 s, dp;
@@ -301,13 +335,24 @@ __global__ __launch_bounds__(256) void fa_bwd_dkv_kernel(const bf16_t* __restric
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(&Gs[32 * qb + kl][16 * kk + 8 * h]), vf[kk], dp, 0, 0, 0);
       }
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int qq = 32 * qb + 8 * (r >> 2) + 4 * h + (r & 3);
-        const int q = q0 + qq;
-        const bool masked = q >= L || (CAUSAL && ki > q);
-        const float p = masked ? 0.f : __expf(s[r] * scale - lse_s[qq]);
-        s[r] = p;
-        dp[r] = p * (dp[r] - delta_s[qq]);
+      for (int g = 0; g < 4; ++g) {
+        const int qq = 32 * qb + 8 * g + 4 * h;
+        const float4 nl = *(const float4*)&lse_s[qq], dl = *(const float4*)&delta_s[qq];
+        const float nls[4] = {nl.x, nl.y, nl.z, nl.w}, dls[4] = {dl.x, dl.y, dl.z, dl.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = 4 * g + e;
+          const float p = fast_exp2(fmaf(s[r], c2, nls[e]));
+          s[r] = p;
+          dp[r] = p * (dp[r] - dls[e]);
+        }
+      }
+      if (CAUSAL || q0 + TK > L) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int q = q0 + 32 * qb + 8 * (r >> 2) + 4 * h + (r & 3);
+          if (q >= L || (CAUSAL && ki > q)) { s[r] = 0.f; dp[r] = 0.f; }
+        }
       }
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
