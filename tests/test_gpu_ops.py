@@ -24,7 +24,8 @@ def close(got, ref, dtype, scale=None, k=1.0):
 
 
 # ---------------------------------------------------------------- GEMM
-GEMM_SHAPES = [(130, 70, 40), (257, 129, 96), (64, 64, 64), (1, 8, 8), (300, 200, 136), (128, 256, 520)]
+GEMM_SHAPES = [(130, 70, 40), (257, 129, 96), (64, 64, 64), (1, 8, 8), (300, 200, 136), (128, 256, 520),
+               (100, 72, 50), (257, 130, 77)]     # reduction lengths off the 8-element grid: general kernel
 
 
 @pytest.mark.parametrize("dtype", [0, 1])
