@@ -46,6 +46,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="bert_base")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--plan-mode", default="input_aware", choices=["input_aware", "static_max", "all", "none"],
+                    help="planning policy of the responsive phase (default: the paper's input-aware planner; "
+                         "static_max = one plan for the longest sequence, as a static planner would make; "
+                         "none ignores the budget)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 256 MiB element-wise copy kernels (reference for scaling FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -72,7 +76,11 @@ def main():
     cal.close()
     budget = int(wl.budget_frac * peak0)
 
-    m = mi.Mimose(d, budget)
+    if args.plan_mode == "none":                      # the no-checkpoint limit needs the whole peak
+        m = mi.Mimose(d, 0, arena_bytes=peak0 + (1 << 20))
+    else:
+        m = mi.Mimose(d, budget)
+    m.set_plan_mode(args.plan_mode)
     m.load_params(synthdata.make_params(shape, wl.seed))
     sheltered = 10
     total = sheltered + args.warmup + args.steps
@@ -133,7 +141,7 @@ def main():
                                f"vocab {shape.vocab}, batch {B}, per-batch length {wl.length_recipe}, "
                                f"budget {wl.budget_frac:.2f} x no-checkpoint peak at L={shape.max_seq}",
                    "global_batch": B, "mean_seq_len": round(float(np.mean([t.shape[1] for t, _ in timed])), 1),
-                   "budget_bytes": budget, "sheltered_steps": sheltered},
+                   "budget_bytes": budget, "sheltered_steps": sheltered, "plan_mode": args.plan_mode},
         "tokens_per_s": round(sum(t.size for t, _ in timed) / dt, 1),
         "useful_tflops": round(useful / dt / 1e12, 2), "recompute_tflops": round(recompute / dt / 1e12, 2),
         "mfma_frac_useful": round(useful / dt / 1e12 / PEAK_BF16_TFLOPS, 4),

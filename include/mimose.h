@@ -127,6 +127,21 @@ int mimose_get_grad(mimose_ctx* ctx, int32_t i, float* host_fp32, uint64_t n_ele
  * and suspends the phase logic; -1 returns control to the planner. */
 int mimose_force_plan(mimose_ctx* ctx, int64_t plan_or_minus1);
 
+/* Planning policy of the responsive phase.  The sheltered phase (Section 4.1) is the same for
+ * modes 0 and 1; modes 2 and 3 never consult the planner and collect nothing.
+ *   MIMOSE_PLAN_INPUT_AWARE  plan for the size of the batch at hand (Sections 4.1, 4.4): default
+ *   MIMOSE_PLAN_STATIC_MAX   one plan, made for the largest admissible input (B * max_seq tokens
+ *                            at the batch size of the step) and applied to every batch: what a
+ *                            static planner does when input sizes vary (Section 3.2)
+ *   MIMOSE_PLAN_ALL          every layer checkpointed: the lower memory limit of Section 6.2
+ *   MIMOSE_PLAN_NONE         nothing checkpointed: the upper memory limit of Section 6.2
+ * A plan forced with mimose_force_plan takes precedence over the mode.  Unknown mode: INVALID_ARG. */
+#define MIMOSE_PLAN_INPUT_AWARE 0
+#define MIMOSE_PLAN_STATIC_MAX 1
+#define MIMOSE_PLAN_ALL 2
+#define MIMOSE_PLAN_NONE 3
+int mimose_set_plan_mode(mimose_ctx* ctx, int32_t mode);
+
 /* Host-only planner access (Section 4.2-4.4): inject a collected sample / ask for a plan. */
 int mimose_planner_feed(mimose_ctx* ctx, int32_t B, int32_t L, int32_t quantity, int32_t layer,
                         uint64_t bytes);

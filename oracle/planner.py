@@ -244,10 +244,12 @@ class Planner:
         q = self.quantum
         return ((int(x) + q - 1) // q) * q
 
-    def query(self, x: int) -> PlanResult:
+    def query(self, x: int, static_x: Optional[int] = None) -> PlanResult:
+        """Plan for input size x.  static_x: a static planner's behaviour (Section 3.2): the plan
+        is made for that fixed, largest input size whatever x is."""
         if self.models is None:
             self.fit()
-        key = self.key_of(x)
+        key = self.key_of(x if static_x is None else static_x)
         if key in self.cache:
             self.hits += 1
             return self.cache[key]

@@ -62,6 +62,7 @@ SIGNATURES = {
     "mimose_dry_step": (C.c_int, [_vp, _i32, _i32, C.POINTER(_u64), C.POINTER(_u64)]),
     "mimose_get_grad": (C.c_int, [_vp, _i32, _vp, _u64]),
     "mimose_force_plan": (C.c_int, [_vp, _i64]),
+    "mimose_set_plan_mode": (C.c_int, [_vp, _i32]),
     "mimose_planner_feed": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _u64]),
     "mimose_planner_end_step": (C.c_int, [_vp, _i32, _i32]),
     "mimose_planner_query": (C.c_int, [_vp, _i32, _i32, C.POINTER(_u64), C.POINTER(_u64)]),
@@ -186,6 +187,13 @@ def mimose_get_grad(ctx, i: int, n_elems: int) -> np.ndarray:
 
 def mimose_force_plan(ctx, plan: int):
     _check(load_library().mimose_force_plan(ctx, plan), ctx)
+
+
+PLAN_MODES = {"input_aware": 0, "static_max": 1, "all": 2, "none": 3}
+
+
+def mimose_set_plan_mode(ctx, mode: int):
+    _check(load_library().mimose_set_plan_mode(ctx, mode), ctx)
 
 
 def mimose_planner_feed(ctx, B: int, L: int, quantity: int, layer: int, nbytes: int):
@@ -346,6 +354,9 @@ class Mimose:
     def force_plan(self, plan: int):
         mimose_force_plan(self.ctx, plan)
 
+    def set_plan_mode(self, mode):
+        mimose_set_plan_mode(self.ctx, PLAN_MODES[mode] if isinstance(mode, str) else int(mode))
+
     def stats(self) -> dict:
         return mimose_get_stats(self.ctx)
 
@@ -365,4 +376,4 @@ class Mimose:
 
 
 __all__ = [n for n in dir() if n.startswith("mimose_") or n.startswith("MIMOSE_") or n.startswith("Q_")] + \
-          ["Mimose", "MimoseError", "make_cfg", "load_library", "LIB_PATH", "SIGNATURES", "ERR_NAMES", "KERNEL_CLASSES"]
+          ["Mimose", "MimoseError", "make_cfg", "load_library", "LIB_PATH", "SIGNATURES", "ERR_NAMES", "KERNEL_CLASSES", "PLAN_MODES"]

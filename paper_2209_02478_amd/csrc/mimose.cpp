@@ -93,6 +93,7 @@ struct mimose_ctx {
       i_hb = -1, i_bdec = -1;
   std::unique_ptr<mimose::Planner> planner;
   int64_t forced_plan = -1;
+  int plan_mode = MIMOSE_PLAN_INPUT_AWARE;
   mimose_stats stats;
   std::string err;
   // pinned host staging for ids / labels / sort order / segments and the loss
@@ -598,13 +599,19 @@ int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, int32_t
   int64_t predicted = 0;
   if (c->forced_plan >= 0) {
     plan = (uint64_t)c->forced_plan & all;
+  } else if (c->plan_mode == MIMOSE_PLAN_ALL) {
+    plan = all;
+  } else if (c->plan_mode == MIMOSE_PLAN_NONE) {
+    plan = 0;
   } else if (c->planner->sheltered()) {
     plan = all;
     collect = true;
   } else {
+    // a static planner sizes its one plan for the largest input it may meet (Section 3.2)
+    const int64_t xq = c->plan_mode == MIMOSE_PLAN_STATIC_MAX ? (int64_t)B * f.max_seq : x;
     mimose::PlanOut po;
     bool hit = false;
-    const int rc = c->planner->query(x, &po, &hit);
+    const int rc = c->planner->query(xq, &po, &hit);
     if (rc == -1) return fail(c, MIMOSE_ERR_NOT_READY, "estimator could not be fitted");
     predicted = po.predicted_peak;
     if (rc == -2) {
@@ -789,6 +796,13 @@ int mimose_get_grad(mimose_ctx* c, int32_t i, float* host, uint64_t n) {
 int mimose_force_plan(mimose_ctx* c, int64_t plan) {
   if (!c || plan < -1) return fail(c, MIMOSE_ERR_INVALID_ARG, "plan must be -1 or a bitmask");
   c->forced_plan = plan;
+  return MIMOSE_OK;
+}
+
+int mimose_set_plan_mode(mimose_ctx* c, int32_t mode) {
+  if (!c || mode < MIMOSE_PLAN_INPUT_AWARE || mode > MIMOSE_PLAN_NONE)
+    return fail(c, MIMOSE_ERR_INVALID_ARG, "unknown plan mode");
+  c->plan_mode = mode;
   return MIMOSE_OK;
 }
 

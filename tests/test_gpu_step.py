@@ -124,6 +124,40 @@ def test_tiny_workload_every_step():
     m.close()
 
 
+def test_static_plan_mode_same_gradients_more_recompute():
+    """One plan for the longest input (the static planner of Section 3.2) against the input-aware
+    planner on the small workload: bit-identical losses and gradients on every step, never fewer
+    recomputed layers, both under the budget."""
+    wl = synthdata.WORKLOADS["tiny"]
+    shape, B, n = wl.shape, wl.batch, wl.shape.n_layers
+    d = synthdata.shape_dict(shape)
+    cal = mi.Mimose(d, 0, device=None)
+    cal.force_plan(0)
+    peak0, _ = cal.dry_step(B, shape.max_seq)
+    cal.close()
+    budget = int(wl.budget_frac * peak0)
+    params = synthdata.make_params(shape, wl.seed)
+    aware, static = mi.Mimose(d, budget), mi.Mimose(d, budget)
+    static.set_plan_mode("static_max")
+    for m in (aware, static):
+        m.load_params(params)
+    lens = synthdata.seq_lengths(wl.length_recipe, wl.steps, wl.seed)
+    fewer = 0
+    for i, L in enumerate(lens):
+        tokens, labels = synthdata.make_batch(shape, B, L, synthdata.step_seed(wl.seed, i))
+        la, pa, plan_a = aware.train_step(tokens, labels)
+        ls, ps, plan_s = static.train_step(tokens, labels)
+        assert la == ls and pa <= budget and ps <= budget
+        ga, gs = aware.grads(), static.grads()
+        for k in ga:
+            assert np.array_equal(ga[k], gs[k]), k
+        assert bin(plan_a).count("1") <= bin(plan_s).count("1")
+        fewer += bin(plan_a).count("1") < bin(plan_s).count("1")
+    assert fewer > 0
+    assert static.stats()["cache_misses"] == 1
+    aware.close(); static.close()
+
+
 def test_bert_base_shape_step():
     """BERT-base shape, bf16, full batch of 32 at the shortest length: parity with the oracle
     (float32 build, bf16-rounded weights)."""

@@ -245,3 +245,61 @@ def test_budget_below_all_checkpointed_floor_is_an_error_and_context_survives():
     peak, plan = m.dry_step(wl.batch, 16)                    # a smaller batch still runs
     assert peak <= floor - 4096 and plan == 3
     m.close()
+
+
+@pytest.mark.parametrize("name", ["tiny", "bert_base"])
+def test_static_plan_mode_plans_for_the_largest_input(name):
+    """A static planner makes one plan for the largest input and applies it to every batch
+    (Section 3.2); the input-aware planner recomputes no more than it on any batch and strictly
+    less over the workload."""
+    wl, budget, _, _ = budget_for(name)
+    n = wl.shape.n_layers
+    cfg = synthdata.shape_dict(wl.shape)
+    aware = mi.Mimose(cfg, budget, device=None)
+    static = mi.Mimose(cfg, budget, device=None)
+    static.set_plan_mode("static_max")
+    ref = op.Planner(n, budget, guard=4096)
+    steps = min(wl.steps, 60)
+    lens = synthdata.seq_lengths(wl.length_recipe, steps, wl.seed)
+    x_max = wl.batch * wl.shape.max_seq
+    static_plans = set()
+    for L in lens:
+        x = wl.batch * L
+        sheltered = ref.sheltered()
+        peak_s, plan_s = static.dry_step(wl.batch, L)
+        peak_a, plan_a = aware.dry_step(wl.batch, L)
+        assert peak_s <= budget and peak_a <= budget
+        if sheltered:
+            assert plan_s == plan_a == (1 << n) - 1
+            c = components_of(static)
+            for l in range(n):
+                ref.feed(x, op.Q_A, l, c.a[l]); ref.feed(x, op.Q_B, l, c.b[l]); ref.feed(x, op.Q_W, l, c.w[l])
+            ref.feed(x, op.Q_E, -1, c.e); ref.feed(x, op.Q_G, -1, c.g); ref.feed(x, op.Q_F, -1, c.F)
+            ref.end_sheltered_step(x)
+        else:
+            assert plan_s == ref.query(x, static_x=x_max).plan
+            assert plan_a == ref.query(x).plan
+            assert bin(plan_a).count("1") <= bin(plan_s).count("1")
+            static_plans.add(plan_s)
+    assert len(static_plans) == 1 and static_plans.pop() != 0
+    sa, ss = aware.stats(), static.stats()
+    assert sa["recompute_flops_total"] < ss["recompute_flops_total"]
+    assert ss["cache_misses"] == 1                               # one plan, made once
+    aware.close(); static.close()
+
+
+def test_all_and_none_modes_bypass_the_planner():
+    wl, budget, peak0, floor = budget_for("tiny")
+    n = wl.shape.n_layers
+    m = mi.Mimose(synthdata.shape_dict(wl.shape), 0, device=None)
+    m.set_plan_mode("all")
+    peak, plan = m.dry_step(wl.batch, wl.shape.max_seq)
+    assert plan == (1 << n) - 1 and peak == floor
+    m.set_plan_mode("none")
+    peak, plan = m.dry_step(wl.batch, wl.shape.max_seq)
+    assert plan == 0 and peak == peak0
+    assert m.stats()["sheltered_steps"] == 0                     # nothing was collected
+    with pytest.raises(mi.MimoseError) as e:
+        m.set_plan_mode(7)
+    assert e.value.code == mi.MIMOSE_ERR_INVALID_ARG
+    m.close()

@@ -102,7 +102,7 @@ def torch_loss(shape, params, tokens, labels):
         logits = F.linear(h, P["tok_emb"])
     loss = F.cross_entropy(logits, torch.tensor(labels.reshape(-1), dtype=torch.long), ignore_index=-1)
     loss.backward()
-    return float(loss), {k: v.grad.numpy() for k, v in P.items()}
+    return float(loss.detach()), {k: v.grad.numpy() for k, v in P.items()}
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
