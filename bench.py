@@ -50,6 +50,8 @@ def main():
                     help="planning policy of the responsive phase (default: the paper's input-aware planner; "
                          "static_max = one plan for the longest sequence, as a static planner would make; "
                          "none ignores the budget)")
+    ap.add_argument("--no-update", action="store_true",
+                    help="leave the parameter update (AdamW) out of the iteration: forward, loss and backward only")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 256 MiB element-wise copy kernels (reference for scaling FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -70,7 +72,11 @@ def main():
     shape, B, N = wl.shape, wl.batch, wl.shape.n_layers
     d = synthdata.shape_dict(shape)
 
+    update = not args.no_update
+    adamw = dict(lr=1e-5, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
     cal = mi.Mimose(d, 0, device=None)
+    if update:
+        cal.optimizer_init(**adamw)           # its state is part of the fixed memory the budget is a fraction of
     cal.force_plan(0)
     peak0, _ = cal.dry_step(B, shape.max_seq)
     cal.close()
@@ -82,6 +88,15 @@ def main():
         m = mi.Mimose(d, budget)
     m.set_plan_mode(args.plan_mode)
     m.load_params(synthdata.make_params(shape, wl.seed))
+    if update:
+        m.optimizer_init(**adamw)
+
+    def iteration(t, l):
+        r = m.train_step(t, l)
+        if update:
+            m.optimizer_step()
+        return r
+
     sheltered = 10
     total = sheltered + args.warmup + args.steps
     lens = synthdata.seq_lengths(wl.length_recipe, total, wl.seed)
@@ -95,14 +110,14 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     for t, l in batches[:sheltered + args.warmup]:
-        m.train_step(t, l)
+        iteration(t, l)
     timed = batches[sheltered + args.warmup:]
     s0 = m.stats()
     max_peak = 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for t, l in timed:
-        _, pk, _ = m.train_step(t, l)
+        _, pk, _ = iteration(t, l)
         max_peak = max(max_peak, pk)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -111,8 +126,21 @@ def main():
     # same steps again with per-kernel events on the work stream
     mi.mimose_profile_enable(m.ctx, 1)
     for t, l in timed:
-        m.train_step(t, l)
+        iteration(t, l)
     torch.cuda.synchronize()
+    upd = None
+    if update:                                # the update alone, back to back, on the context's stream
+        n_elems = sum(int(np.prod(sh)) for sh in m.shapes.values())
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            m.optimizer_step()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 100.0
+        per_elem = 28 + (2 if shape.dtype == "bf16" else 0)     # read g, m, v, p; write m, v, p (+ bf16 copy)
+        upd = {"kind": "adamw, one launch over all tensors, inside the timed iteration", "avg_us": round(us, 1),
+               "gbs": round(n_elems * per_elem / (us * 1e-6) / 1e9, 1)}
     kernels = {}
     gemm_flops_per_launch = 0.0
     for i, name in enumerate(mi.KERNEL_CLASSES):
@@ -152,6 +180,7 @@ def main():
         "planner_us_per_step": round((s1["planner_ns_total"] - s0["planner_ns_total"]) / K / 1e3, 2),
         "max_peak_over_budget": round(max_peak / budget, 4),
         "kernels": kernels,
+        "update": upd,
         "roofline": {"bound": "mfma", "kernel": "bgemm_kernel / bgemm_dma_kernel (every GEMM launch of the timed steps)",
                      "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),

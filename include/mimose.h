@@ -123,6 +123,26 @@ int mimose_dry_step(mimose_ctx* ctx, int32_t B, int32_t L, uint64_t* peak_bytes,
 /* Gradient of parameter i from the last completed step, as fp32 to host. Synchronous. */
 int mimose_get_grad(mimose_ctx* ctx, int32_t i, float* host_fp32, uint64_t n_elems);
 
+/* Parameter i as the kernels use it (storage type widened to fp32), to host.  Synchronous. */
+int mimose_get_param(mimose_ctx* ctx, int32_t i, float* host_fp32, uint64_t n_elems);
+
+/* Parameter update that ends a training iteration (Section 2.1); its state counts towards the
+ * input-independent memory of Section 3.1.  The paper names no optimizer: this is Adam with
+ * decoupled weight decay, p -= lr * (m_hat / (sqrt(v_hat) + eps) + weight_decay * p), the decay
+ * applied to tensors of two or more dimensions only.  State comes out of the arena's persistent
+ * region: two fp32 moments per element, plus an fp32 master copy when dtype is bf16 (the bf16
+ * parameter is then the master rounded to nearest-even after every update).
+ * mimose_optimizer_init: once, before the first step (NOT_READY after), also on host-only
+ * contexts (bookkeeping only); OOM_BUDGET if the state does not fit, the context stays usable.
+ * mimose_optimizer_step: one update from the gradients of the last completed step, enqueued on
+ * the context's stream (asynchronous); NOT_READY without a preceding step or on host-only
+ * contexts.  Parameters loaded afterwards with mimose_load_param refresh the master copy. */
+typedef struct {
+  float lr, beta1, beta2, eps, weight_decay;
+} mimose_adamw_cfg;
+int mimose_optimizer_init(mimose_ctx* ctx, const mimose_adamw_cfg* cfg);
+int mimose_optimizer_step(mimose_ctx* ctx);
+
 /* Test hook: plan >= 0 forces that bitmask on every following step (0 = keep everything)
  * and suspends the phase logic; -1 returns control to the planner. */
 int mimose_force_plan(mimose_ctx* ctx, int64_t plan_or_minus1);

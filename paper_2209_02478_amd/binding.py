@@ -43,6 +43,10 @@ class mimose_stats(C.Structure):
         return {n: getattr(self, n) for n, _ in self._fields_}
 
 
+class mimose_adamw_cfg(C.Structure):
+    _fields_ = [(n, C.c_float) for n in ("lr", "beta1", "beta2", "eps", "weight_decay")]
+
+
 class MimoseError(RuntimeError):
     def __init__(self, code: int, msg: str):
         super().__init__(f"libmimose: {ERR_NAMES.get(code, code)}: {msg}")
@@ -61,6 +65,9 @@ SIGNATURES = {
     "mimose_train_step": (C.c_int, [_vp, _vp, _vp, _i32, _i32, C.POINTER(_f32), C.POINTER(_u64), C.POINTER(_u64)]),
     "mimose_dry_step": (C.c_int, [_vp, _i32, _i32, C.POINTER(_u64), C.POINTER(_u64)]),
     "mimose_get_grad": (C.c_int, [_vp, _i32, _vp, _u64]),
+    "mimose_get_param": (C.c_int, [_vp, _i32, _vp, _u64]),
+    "mimose_optimizer_init": (C.c_int, [_vp, _vp]),
+    "mimose_optimizer_step": (C.c_int, [_vp]),
     "mimose_force_plan": (C.c_int, [_vp, _i64]),
     "mimose_set_plan_mode": (C.c_int, [_vp, _i32]),
     "mimose_planner_feed": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _u64]),
@@ -183,6 +190,21 @@ def mimose_get_grad(ctx, i: int, n_elems: int) -> np.ndarray:
     out = np.empty(n_elems, dtype=np.float32)
     _check(load_library().mimose_get_grad(ctx, i, out.ctypes.data, n_elems), ctx)
     return out
+
+
+def mimose_get_param(ctx, i: int, n_elems: int) -> np.ndarray:
+    out = np.empty(n_elems, dtype=np.float32)
+    _check(load_library().mimose_get_param(ctx, i, out.ctypes.data, n_elems), ctx)
+    return out
+
+
+def mimose_optimizer_init(ctx, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01):
+    cfg = mimose_adamw_cfg(lr, beta1, beta2, eps, weight_decay)
+    _check(load_library().mimose_optimizer_init(ctx, C.addressof(cfg)), ctx)
+
+
+def mimose_optimizer_step(ctx):
+    _check(load_library().mimose_optimizer_step(ctx), ctx)
 
 
 def mimose_force_plan(ctx, plan: int):
@@ -353,6 +375,16 @@ class Mimose:
 
     def force_plan(self, plan: int):
         mimose_force_plan(self.ctx, plan)
+
+    def optimizer_init(self, **hyper):
+        mimose_optimizer_init(self.ctx, **hyper)
+
+    def optimizer_step(self):
+        mimose_optimizer_step(self.ctx)
+
+    def params(self) -> Dict[str, np.ndarray]:
+        return {n: mimose_get_param(self.ctx, i, int(np.prod(self.shapes[n]))).reshape(self.shapes[n])
+                for i, n in enumerate(self.names)}
 
     def set_plan_mode(self, mode):
         mimose_set_plan_mode(self.ctx, PLAN_MODES[mode] if isinstance(mode, str) else int(mode))

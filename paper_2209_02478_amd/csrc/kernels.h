@@ -63,4 +63,18 @@ void embed_bwd(int dtype, const void* d, const int32_t* ids, const int32_t* orde
 void convert_from_f32(int dtype, const float* src, void* dst, int64_t n, hipStream_t st);
 void fill_zero(void* p, int64_t bytes, hipStream_t st);
 
+// AdamW over a list of tensors in one launch.  Device-resident tables, one entry per tensor
+// (master fp32 values, optional low-precision copy, gradient, first and second moment, element
+// count, whether weight decay applies) and one per chunk of kAdamChunk elements (tensor, start).
+constexpr int kAdamChunk = 16384;
+struct AdamTensor {
+  float* master; void* lowp; const float* grad; float* m; float* v; int64_t n; int32_t decay; int32_t pad;
+};
+struct AdamChunk { int32_t tensor; int32_t pad; int64_t start; };
+struct AdamHyper { float lr, beta1, beta2, eps, weight_decay, inv_c1, inv_c2; };   // inv_c = 1 / (1 - beta^t)
+void adamw_update(int lowp_dtype, const AdamTensor* tensors, const AdamChunk* chunks, int n_chunks, AdamHyper h,
+                  hipStream_t st);
+// dst fp32 = src (storage dtype)
+void convert_to_f32(int dtype, const void* src, float* dst, int64_t n, hipStream_t st);
+
 }  // namespace mk

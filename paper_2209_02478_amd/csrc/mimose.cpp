@@ -11,6 +11,7 @@
 #include <algorithm>
 #include <chrono>
 #include <cstdio>
+#include <cmath>
 #include <cstring>
 #include <memory>
 #include <string>
@@ -60,6 +61,11 @@ struct Param {
   int64_t n = 0;
   void* w = nullptr;    // storage dtype
   float* g = nullptr;   // fp32 gradient
+  // optimizer state (after mimose_optimizer_init): moments, and an fp32 master copy when the
+  // storage type is narrower than fp32 (for fp32 storage the parameter itself is the master)
+  float* m = nullptr;
+  float* v = nullptr;
+  float* master = nullptr;
 };
 
 struct LayerIdx { int wqkv, bqkv, wo, bo, ln1g, ln1b, w1, b1, w2, b2, ln2g, ln2b; };
@@ -94,6 +100,14 @@ struct mimose_ctx {
   std::unique_ptr<mimose::Planner> planner;
   int64_t forced_plan = -1;
   int plan_mode = MIMOSE_PLAN_INPUT_AWARE;
+  // parameter update (Section 2.1: the iteration ends with it; its state is part of the
+  // input-independent memory of Section 3.1)
+  bool opt_on = false;
+  mimose_adamw_cfg opt;
+  uint64_t opt_t = 0;
+  mk::AdamTensor* opt_tensors = nullptr;   // device tables
+  mk::AdamChunk* opt_chunks = nullptr;
+  int opt_n_chunks = 0;
   mimose_stats stats;
   std::string err;
   // pinned host staging for ids / labels / sort order / segments and the loss
@@ -766,6 +780,7 @@ int mimose_load_param(mimose_ctx* c, int32_t i, const float* host, uint64_t n) {
   if (hipMemcpyAsync(p.g, host, n * 4, hipMemcpyHostToDevice, c->stream) != hipSuccess)
     return fail(c, MIMOSE_ERR_HIP, "copy of " + p.name + " failed");
   mk::convert_from_f32(c->cfg.dtype, p.g, p.w, p.n, c->stream);
+  if (c->opt_on && p.master != (float*)p.w) mk::convert_to_f32(c->cfg.dtype, p.w, p.master, p.n, c->stream);
   mk::fill_zero(p.g, p.n * 4, c->stream);
   if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(c, MIMOSE_ERR_HIP, "load of " + p.name + " failed");
   return MIMOSE_OK;
@@ -790,6 +805,100 @@ int mimose_get_grad(mimose_ctx* c, int32_t i, float* host, uint64_t n) {
   if (hipMemcpyAsync(host, p.g, n * 4, hipMemcpyDeviceToHost, c->stream) != hipSuccess ||
       hipStreamSynchronize(c->stream) != hipSuccess)
     return fail(c, MIMOSE_ERR_HIP, "copy of gradient " + p.name + " failed");
+  return MIMOSE_OK;
+}
+
+int mimose_get_param(mimose_ctx* c, int32_t i, float* host, uint64_t n) {
+  if (!c || i < 0 || i >= (int)c->params.size() || !host) return fail(c, MIMOSE_ERR_INVALID_ARG, "bad parameter index or pointer");
+  if (!c->has_device) return fail(c, MIMOSE_ERR_NOT_READY, "host-only context");
+  const Param& p = c->params[i];
+  if ((int64_t)n != p.n) return fail(c, MIMOSE_ERR_INVALID_ARG, "element count does not match " + p.name);
+  // the values the kernels compute with: the storage-type parameter, widened
+  if (c->cfg.dtype == mk::F32) {
+    if (hipMemcpyAsync(host, p.w, n * 4, hipMemcpyDeviceToHost, c->stream) != hipSuccess)
+      return fail(c, MIMOSE_ERR_HIP, "copy of " + p.name + " failed");
+  } else {
+    // widen into scratch taken from the top of the stack, which is free between steps
+    float* tmp = nullptr;
+    try { tmp = (float*)c->arena.alloc(n * 4); } catch (const OomError&) {
+      return fail(c, MIMOSE_ERR_OOM_BUDGET, "no room to stage " + p.name);
+    }
+    mk::convert_to_f32(c->cfg.dtype, p.w, tmp, p.n, c->stream);
+    const hipError_t e = hipMemcpyAsync(host, tmp, n * 4, hipMemcpyDeviceToHost, c->stream);
+    const hipError_t e2 = hipStreamSynchronize(c->stream);
+    c->arena.pop_to(c->fixed_top);
+    if (e != hipSuccess || e2 != hipSuccess) return fail(c, MIMOSE_ERR_HIP, "copy of " + p.name + " failed");
+    return MIMOSE_OK;
+  }
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(c, MIMOSE_ERR_HIP, "copy of " + p.name + " failed");
+  return MIMOSE_OK;
+}
+
+int mimose_optimizer_init(mimose_ctx* c, const mimose_adamw_cfg* o) {
+  if (!c || !o) return fail(c, MIMOSE_ERR_INVALID_ARG, "ctx and cfg must be given");
+  if (c->opt_on) return fail(c, MIMOSE_ERR_INVALID_ARG, "the optimizer is already initialised");
+  if (c->stats.steps != 0) return fail(c, MIMOSE_ERR_NOT_READY, "initialise the optimizer before the first step");
+  if (!(o->lr >= 0.f) || !(o->beta1 >= 0.f && o->beta1 < 1.f) || !(o->beta2 >= 0.f && o->beta2 < 1.f) || !(o->eps >= 0.f) ||
+      !(o->weight_decay >= 0.f))
+    return fail(c, MIMOSE_ERR_INVALID_ARG, "hyper-parameters out of range");
+  const bool narrow = c->cfg.dtype != mk::F32;
+  std::vector<mk::AdamTensor> tens;
+  std::vector<mk::AdamChunk> chunks;
+  const uint64_t mark = c->arena.top();
+  try {
+    for (auto& p : c->params) {
+      p.m = (float*)c->arena.alloc((uint64_t)p.n * 4);
+      p.v = (float*)c->arena.alloc((uint64_t)p.n * 4);
+      p.master = narrow ? (float*)c->arena.alloc((uint64_t)p.n * 4) : (float*)p.w;
+    }
+    for (size_t i = 0; i < c->params.size(); ++i) {
+      const Param& p = c->params[i];
+      mk::AdamTensor t;
+      t.master = p.master; t.lowp = narrow ? p.w : nullptr; t.grad = p.g; t.m = p.m; t.v = p.v; t.n = p.n;
+      t.decay = p.ndim >= 2 ? 1 : 0; t.pad = 0;
+      tens.push_back(t);
+      for (int64_t s0 = 0; s0 < p.n; s0 += mk::kAdamChunk) chunks.push_back(mk::AdamChunk{(int32_t)i, 0, s0});
+    }
+    c->opt_tensors = (mk::AdamTensor*)c->arena.alloc(tens.size() * sizeof(mk::AdamTensor));
+    c->opt_chunks = (mk::AdamChunk*)c->arena.alloc(chunks.size() * sizeof(mk::AdamChunk));
+  } catch (const OomError&) {
+    c->arena.pop_to(mark);
+    for (auto& p : c->params) p.m = p.v = p.master = nullptr;
+    return fail(c, MIMOSE_ERR_OOM_BUDGET, "optimizer state does not fit in the budget");
+  }
+  c->opt_n_chunks = (int)chunks.size();
+  if (c->has_device) {
+    mk::fill_zero(c->params.front().m, (int64_t)((char*)c->opt_tensors - (char*)c->params.front().m), c->stream);
+    if (narrow)
+      for (auto& p : c->params) mk::convert_to_f32(c->cfg.dtype, p.w, p.master, p.n, c->stream);
+    if (hipMemcpyAsync(c->opt_tensors, tens.data(), tens.size() * sizeof(mk::AdamTensor), hipMemcpyHostToDevice, c->stream) != hipSuccess ||
+        hipMemcpyAsync(c->opt_chunks, chunks.data(), chunks.size() * sizeof(mk::AdamChunk), hipMemcpyHostToDevice, c->stream) != hipSuccess ||
+        hipStreamSynchronize(c->stream) != hipSuccess) {
+      c->arena.pop_to(mark);
+      for (auto& p : c->params) p.m = p.v = p.master = nullptr;
+      return fail(c, MIMOSE_ERR_HIP, "optimizer initialisation failed");
+    }
+  }
+  c->opt = *o;
+  c->opt_t = 0;
+  c->opt_on = true;
+  c->fixed_top = c->arena.top();
+  c->stats.fixed_bytes = c->fixed_top;
+  return MIMOSE_OK;
+}
+
+int mimose_optimizer_step(mimose_ctx* c) {
+  if (!c) return MIMOSE_ERR_INVALID_ARG;
+  if (!c->opt_on) return fail(c, MIMOSE_ERR_NOT_READY, "the optimizer is not initialised");
+  if (!c->has_device) return fail(c, MIMOSE_ERR_NOT_READY, "host-only context");
+  if (c->stats.steps == 0) return fail(c, MIMOSE_ERR_NOT_READY, "no gradients yet: run a training step first");
+  c->opt_t += 1;
+  mk::AdamHyper h;
+  h.lr = c->opt.lr; h.beta1 = c->opt.beta1; h.beta2 = c->opt.beta2; h.eps = c->opt.eps; h.weight_decay = c->opt.weight_decay;
+  h.inv_c1 = (float)(1.0 / (1.0 - std::pow((double)c->opt.beta1, (double)c->opt_t)));
+  h.inv_c2 = (float)(1.0 / (1.0 - std::pow((double)c->opt.beta2, (double)c->opt_t)));
+  mk::adamw_update(c->cfg.dtype, c->opt_tensors, c->opt_chunks, c->opt_n_chunks, h, c->stream);
+  if (hipGetLastError() != hipSuccess) return fail(c, MIMOSE_ERR_HIP, "update launch failed");
   return MIMOSE_OK;
 }
 

@@ -565,6 +565,59 @@ __global__ __launch_bounds__(256) void convert_kernel(const float* __restrict__ 
   if (i < n) st<T>(dst + i, src[i]);
 }
 
+template <typename T>
+__global__ __launch_bounds__(256) void widen_kernel(const T* __restrict__ src, float* __restrict__ dst, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = ld<T>(src + i);
+}
+
+// One block per chunk of kAdamChunk elements of one tensor; element-wise, fp32 arithmetic:
+//   m = b1 m + (1-b1) g;  v = b2 v + (1-b2) g^2
+//   p = p - lr * ( (m / c1) / (sqrt(v / c2) + eps) + wd p )      (decoupled weight decay)
+// The low-precision copy, when there is one, is the new master value rounded to nearest-even.
+__global__ __launch_bounds__(256) void adamw_kernel(const AdamTensor* __restrict__ tensors,
+                                                    const AdamChunk* __restrict__ chunks, AdamHyper h) {
+  const AdamChunk ck = chunks[blockIdx.x];
+  const AdamTensor t = tensors[ck.tensor];
+  const float wd = t.decay ? h.weight_decay : 0.f;
+  const int64_t end = min(t.n, ck.start + (int64_t)kAdamChunk);
+  bf16_t* lowp = (bf16_t*)t.lowp;
+  // 4 elements per thread and pass while the chunk allows (tensor starts are 256-byte aligned)
+  for (int64_t i = ck.start + 4 * (int64_t)threadIdx.x; i < end; i += 4 * 256) {
+    if (i + 4 <= end) {
+      const float4 g = *(const float4*)(t.grad + i);
+      float4 m = *(const float4*)(t.m + i), v = *(const float4*)(t.v + i), p = *(const float4*)(t.master + i);
+      const float gs[4] = {g.x, g.y, g.z, g.w};
+      float ms[4] = {m.x, m.y, m.z, m.w}, vs[4] = {v.x, v.y, v.z, v.w}, ps[4] = {p.x, p.y, p.z, p.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        ms[e] = h.beta1 * ms[e] + (1.f - h.beta1) * gs[e];
+        vs[e] = h.beta2 * vs[e] + (1.f - h.beta2) * gs[e] * gs[e];
+        ps[e] -= h.lr * ((ms[e] * h.inv_c1) / (sqrtf(vs[e] * h.inv_c2) + h.eps) + wd * ps[e]);
+      }
+      *(float4*)(t.m + i) = make_float4(ms[0], ms[1], ms[2], ms[3]);
+      *(float4*)(t.v + i) = make_float4(vs[0], vs[1], vs[2], vs[3]);
+      *(float4*)(t.master + i) = make_float4(ps[0], ps[1], ps[2], ps[3]);
+      if (lowp) {
+        uint2 w;
+        w.x = pack_bf16x2(ps[0], ps[1]);
+        w.y = pack_bf16x2(ps[2], ps[3]);
+        *(uint2*)(lowp + i) = w;
+      }
+    } else {
+      for (int64_t j = i; j < end; ++j) {
+        const float g = t.grad[j];
+        const float m = h.beta1 * t.m[j] + (1.f - h.beta1) * g;
+        const float v = h.beta2 * t.v[j] + (1.f - h.beta2) * g * g;
+        float pv = t.master[j];
+        pv -= h.lr * ((m * h.inv_c1) / (sqrtf(v * h.inv_c2) + h.eps) + wd * pv);
+        t.m[j] = m; t.v[j] = v; t.master[j] = pv;
+        if (lowp) lowp[j] = f32_to_bf16(pv);
+      }
+    }
+  }
+}
+
 __global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* __restrict__ p, int64_t n) {
   int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i < n) p[i] = 0u;
@@ -707,6 +760,20 @@ void convert_from_f32(int dtype, const float* src, void* dst, int64_t n, hipStre
   dim3 grid((unsigned)((n + 255) / 256));
   if (dtype == BF16) hipLaunchKernelGGL(convert_kernel<bf16_t>, grid, dim3(256), 0, st, src, (bf16_t*)dst, n);
   else hipLaunchKernelGGL(convert_kernel<float>, grid, dim3(256), 0, st, src, (float*)dst, n);
+}
+
+void convert_to_f32(int dtype, const void* src, float* dst, int64_t n, hipStream_t st) {
+  if (n <= 0) return;
+  dim3 grid((unsigned)((n + 255) / 256));
+  if (dtype == BF16) hipLaunchKernelGGL(widen_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)src, dst, n);
+  else hipLaunchKernelGGL(widen_kernel<float>, grid, dim3(256), 0, st, (const float*)src, dst, n);
+}
+
+void adamw_update(int lowp_dtype, const AdamTensor* tensors, const AdamChunk* chunks, int n_chunks, AdamHyper h,
+                  hipStream_t st) {
+  (void)lowp_dtype;                                  // the only low-precision storage type is bf16
+  if (n_chunks <= 0) return;
+  hipLaunchKernelGGL(adamw_kernel, dim3((unsigned)n_chunks), dim3(256), 0, st, tensors, chunks, h);
 }
 
 void fill_zero(void* p, int64_t bytes, hipStream_t st) {

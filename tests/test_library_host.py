@@ -303,3 +303,42 @@ def test_all_and_none_modes_bypass_the_planner():
         m.set_plan_mode(7)
     assert e.value.code == mi.MIMOSE_ERR_INVALID_ARG
     m.close()
+
+
+def test_optimizer_state_counts_as_fixed_memory():
+    """Two fp32 moments per element, plus an fp32 master copy for bf16 storage, join the
+    input-independent bytes (Section 3.1) that the planner sees as F."""
+    for name, per_elem in (("tiny", 8), ("bert_base", 12)):
+        wl, m = host_ctx(name)
+        n_elems = sum(int(np.prod(s)) for s in m.shapes.values())
+        before = m.stats()["fixed_bytes"]
+        m.optimizer_init(lr=1e-3)
+        after = m.stats()["fixed_bytes"]
+        grew = after - before
+        assert per_elem * n_elems <= grew <= per_elem * n_elems + 256 * 3 * len(m.names) + (1 << 20)
+        m.force_plan(0)
+        peak, _ = m.dry_step(wl.batch, 16)
+        assert m.step_memory()["F"] == after and peak > after
+        with pytest.raises(mi.MimoseError) as e:             # no device: nothing to update
+            m.optimizer_step()
+        assert e.value.code == mi.MIMOSE_ERR_NOT_READY
+        with pytest.raises(mi.MimoseError) as e:
+            m.optimizer_init()
+        assert e.value.code == mi.MIMOSE_ERR_INVALID_ARG     # already initialised
+        m.close()
+    wl, m = host_ctx("tiny")
+    m.dry_step(wl.batch, 16)
+    with pytest.raises(mi.MimoseError) as e:
+        m.optimizer_init()
+    assert e.value.code == mi.MIMOSE_ERR_NOT_READY           # must precede the first step
+    m.close()
+    wl, m = host_ctx("tiny")
+    fixed = m.stats()["fixed_bytes"]
+    m.close()
+    wl, m = host_ctx("tiny", budget=fixed + 65536)           # parameters fit, the state does not
+    with pytest.raises(mi.MimoseError) as e:
+        m.optimizer_init()
+    assert e.value.code == mi.MIMOSE_ERR_OOM_BUDGET
+    peak, _ = m.dry_step(wl.batch, 1)                        # the context survives
+    assert peak > fixed
+    m.close()
