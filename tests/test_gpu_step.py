@@ -124,6 +124,36 @@ def test_tiny_workload_every_step():
     m.close()
 
 
+@pytest.mark.parametrize("name", ["fp32_postln", "bf16_preln_causal", "bf16_postln"])
+def test_degenerate_batches(name):
+    """One token; the longest admissible sequence; a batch in which no position is scored."""
+    shape = SMALL[name]
+    fp32 = shape.dtype == "fp32"
+    params = synthdata.make_params(shape, 21, perturb=True)
+    m = mi.Mimose(synthdata.shape_dict(shape), 0, arena_bytes=256 * MiB)
+    m.load_params(params)
+    m.force_plan(1)
+    for B, L in ((1, 1), (1, 2), (3, shape.max_seq)):
+        tokens, labels = synthdata.make_batch(shape, B, L, 30 + L)
+        if shape.causal and L == 1:
+            continue                                   # a causal batch of length 1 has no scored position: below
+        check_against_oracle(shape, m, params, tokens, labels, 1e-4 if fp32 else 1e-2, 1e-3 if fp32 else 2e-2)
+    tokens, labels = synthdata.make_batch(shape, 2, 5, 44)
+    labels = np.full_like(labels, -1)
+    loss, _, _ = m.train_step(tokens, labels)
+    assert loss == 0.0
+    for k, g in m.grads().items():
+        assert not np.any(g), k
+    if shape.causal:
+        tokens, labels = synthdata.make_batch(shape, 2, 1, 45)
+        loss, _, _ = m.train_step(tokens, labels)
+        assert loss == 0.0
+    with pytest.raises(mi.MimoseError) as e:
+        m.train_step(*synthdata.make_batch(shape, 1, shape.max_seq + 1, 46))      # longer than the position table
+    assert e.value.code == mi.MIMOSE_ERR_INVALID_ARG
+    m.close()
+
+
 def test_static_plan_mode_same_gradients_more_recompute():
     """One plan for the longest input (the static planner of Section 3.2) against the input-aware
     planner on the small workload: bit-identical losses and gradients on every step, never fewer
