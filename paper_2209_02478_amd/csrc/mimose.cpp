@@ -71,6 +71,7 @@ struct Param {
 struct LayerIdx { int wqkv, bqkv, wo, bo, ln1g, ln1b, w1, b1, w2, b2, ln2g, ln2b; };
 
 struct LayerActs {       // device tensors of one layer, in allocation order
+  bool has_out = false;  // the boundary tensor is allocated (survives a drop)
   uint64_t mark = 0;     // stack top before the layer
   uint64_t after_out = 0;
   bool dropped = false;
@@ -364,10 +365,11 @@ void Step::embed_stage(const int32_t* tokens, const int32_t* labels) {
 void Step::alloc_layer(int l, LayerActs& A) {
   (void)l;
   const int64_t TH = (int64_t)T_ * f_.hidden, TF = (int64_t)T_ * f_.ffn;
-  if (!A.out) {                       // first pass: the boundary tensor goes first
+  if (!A.has_out) {                   // first pass: the boundary tensor goes first
     A.mark = c_->arena.top();
     A.out = talloc(TH);
     A.after_out = c_->arena.top();
+    A.has_out = true;                 // (not the pointer: a host-only context hands out null)
   }
   if (f_.pre_ln) A.n1 = talloc(TH);   // LN1(x)
   A.qkv = talloc(3 * TH);
@@ -423,15 +425,13 @@ void Step::layer_backward(int l, LayerActs& A) {
     if (!dry_) mk::gelu_bwd(dt_, dact, A.pre, TF, f_.gelu_tanh, st_);        // dact = d pre
   }
   wgrad(dact, F, F, A.u, H, p.w1, p.b1);
+  // dact stays allocated until the end of the layer: the weight-gradient stream may still read
+  // it, and waiting for that stream here would idle the chip for the length of the hand-over
   if (f_.pre_ln) {
     dgrad(dact, F, F, p.w1, gB_, H);                                          // gB = d LN2(u)
-    join();
-    ar.pop_to(m0);
     ln_bwd(gB_, A.s1, p.ln2g, p.ln2b, gB_, gA_);                              // gB = d u
   } else {
     dgrad(dact, F, F, p.w1, gB_, H, oA_, wide_);                              // gB = d u = d s2 + FFN path
-    join();
-    ar.pop_to(m0);
     ln_bwd(gB_, A.s1, p.ln1g, p.ln1b, oB_, nullptr, wide_, wide_);            // oB = d s1
   }
   wgrad(oB_, H, H, A.ctx, H, p.wo, p.bo);
