@@ -117,6 +117,7 @@ struct mimose_ctx {
   float* loss_host = nullptr;
   bool dry = false;
   std::vector<LayerActs> acts;
+  std::vector<int32_t> sort_count;       // reused scratch of the per-step counting sort
   // memory components measured in the last completed step
   uint64_t last_e = 0, last_g = 0;
   std::vector<uint64_t> last_a, last_b, last_w;
@@ -313,6 +314,7 @@ class Step {
   }
 
   void embed_stage(const int32_t* tokens, const int32_t* labels);
+  void embed_sort(const int32_t* tokens);
   void alloc_layer(int l, LayerActs& A);
   void layer_forward(int l, LayerActs& A);
   void layer_backward(int l, LayerActs& A);
@@ -345,18 +347,7 @@ void Step::embed_stage(const int32_t* tokens, const int32_t* labels) {
   int32_t* s = c_->stage;
   std::memcpy(s, tokens, (size_t)T_ * 4);
   std::memcpy(s + T_, labels, (size_t)T_ * 4);
-  std::vector<int32_t> count((size_t)f_.vocab + 1, 0);
-  for (int t = 0; t < T_; ++t) ++count[(size_t)tokens[t] + 1];
-  n_seg_ = 0;
-  int32_t* seg = s + 3 * (size_t)T_;
-  for (int v = 0; v < f_.vocab; ++v) {
-    if (count[v + 1]) seg[n_seg_++] = count[v];
-    count[v + 1] += count[v];
-  }
-  seg[n_seg_] = T_;
-  int32_t* order = s + 2 * (size_t)T_;
-  for (int t = 0; t < T_; ++t) order[count[tokens[t]]++] = t;
-  HIPCHK(c_, hipMemcpyAsync(ints, s, need * 4, hipMemcpyHostToDevice, st_));
+  HIPCHK(c_, hipMemcpyAsync(ints, s, 2 * (size_t)T_ * 4, hipMemcpyHostToDevice, st_));
   Timed t(this, MIMOSE_K_EMBED_FWD, (f_.pre_ln ? 3.0 : 4.0) * T_ * H * es_d());
   mk::embed_fwd(dt_, ids_, w(c_->i_tok), w(c_->i_pos), f_.pre_ln ? nullptr : w(c_->i_eg),
                 f_.pre_ln ? nullptr : w(c_->i_eb), emb_sum_, h0_, B_, L_, H, f_.ln_eps, !f_.pre_ln, st_);
@@ -509,6 +500,28 @@ void Step::head(float* loss_dev) {
   join();
 }
 
+// Host side of the embedding backward: stable sort of positions by token id and the run
+// boundaries of equal ids.  Only the last kernels of the step read them, so this runs after the
+// forward launches are queued, while the device is busy (second half of the pinned staging
+// buffer; the first half is still being read by the copy of the ids).
+void Step::embed_sort(const int32_t* tokens) {
+  if (dry_) return;
+  int32_t* s = c_->stage;
+  std::vector<int32_t>& count = c_->sort_count;
+  count.assign((size_t)f_.vocab + 1, 0);
+  for (int t = 0; t < T_; ++t) ++count[(size_t)tokens[t] + 1];
+  n_seg_ = 0;
+  int32_t* seg = s + 3 * (size_t)T_;
+  for (int v = 0; v < f_.vocab; ++v) {
+    if (count[v + 1]) seg[n_seg_++] = count[v];
+    count[v + 1] += count[v];
+  }
+  seg[n_seg_] = T_;
+  int32_t* order = s + 2 * (size_t)T_;
+  for (int t = 0; t < T_; ++t) order[count[tokens[t]]++] = t;
+  HIPCHK(c_, hipMemcpyAsync(order_, order, (2 * (size_t)T_ + 1) * 4, hipMemcpyHostToDevice, st_));
+}
+
 void Step::embed_backward() {
   const int H = f_.hidden;
   if (!f_.pre_ln) ln_bwd(gA_, emb_sum_, c_->i_eg, c_->i_eb, oA_, nullptr, wide_, false);
@@ -544,6 +557,7 @@ void Step::run(const int32_t* tokens, const int32_t* labels, float* loss_out) {
     x = A.out;
   }
 
+  embed_sort(tokens);                     // host work hidden behind the queued forward
   const uint64_t m_head = ar.top();
   ar.begin_section();
   head(loss_dev);
