@@ -204,8 +204,12 @@ def cpu_baseline(wl, update, adamw):
     except Exception:
         cores = os.cpu_count() or 1
     shape = wl.shape
-    Bs, L = 8, min(200, shape.max_seq)
+    L = min(200, shape.max_seq)
     cfg = om.Cfg.from_shape(synthdata.shape_dict(shape))
+    # bounded sample: about 4 TFLOP of the same model (a full BERT-base batch at L=200), never
+    # more than the workload's batch
+    per_sample = om.flops_per_step(cfg, 1, L)[0]
+    Bs = int(max(1, min(wl.batch, round(4.3e12 / per_sample))))
     params = synthdata.make_params(shape, wl.seed)
     tokens, labels = synthdata.make_batch(shape, Bs, L, 1)
     t0 = time.perf_counter()
