@@ -130,14 +130,20 @@ def merge_heads(x):
     return x.transpose(0, 2, 1, 3).reshape(B * L, h * d)
 
 
-def attention_fwd(q, k, v, causal):
-    """q, k, v: [B,h,L,d].  Returns o and the probability matrix."""
+def attention_fwd(q, k, v, causal, lengths=None):
+    """q, k, v: [B,h,L,d].  Returns o and the probability matrix.
+
+    lengths (optional, [B]): sample b has lengths[b] real tokens, the rest of its row is padding
+    (the batch is padded to its longest sample, Section 2.1); padded keys get no weight."""
     d = q.shape[-1]
     s = (q @ k.transpose(0, 1, 3, 2)) / np.sqrt(float(d))
+    L = q.shape[2]
     if causal:
-        L = q.shape[2]
         mask = np.triu(np.ones((L, L), dtype=bool), k=1)
         s = np.where(mask, -np.inf, s)
+    if lengths is not None:
+        pad = np.arange(L)[None, :] >= np.asarray(lengths)[:, None]          # [B, L] keys that are padding
+        s = np.where(pad[:, None, None, :], -np.inf, s)
     s = s - s.max(axis=-1, keepdims=True)
     e = np.exp(s)
     p = e / e.sum(axis=-1, keepdims=True)
@@ -174,7 +180,7 @@ def cross_entropy(logits, labels):
 # --------------------------------------------------------------------------
 # One transformer block.
 # --------------------------------------------------------------------------
-def layer_forward(cfg: Cfg, P: Dict[str, np.ndarray], l: int, h, B: int, L: int):
+def layer_forward(cfg: Cfg, P: Dict[str, np.ndarray], l: int, h, B: int, L: int, lengths=None):
     pre = f"layer{l}."
     H, nh = cfg.hidden, cfg.n_heads
     S = {"h": h}
@@ -186,7 +192,7 @@ def layer_forward(cfg: Cfg, P: Dict[str, np.ndarray], l: int, h, B: int, L: int)
     q = split_heads(qkv[:, :H], B, L, nh)
     k = split_heads(qkv[:, H:2 * H], B, L, nh)
     v = split_heads(qkv[:, 2 * H:], B, L, nh)
-    o, p = attention_fwd(q, k, v, cfg.causal)
+    o, p = attention_fwd(q, k, v, cfg.causal, lengths)
     S.update(q=q, k=k, v=v, p=p)
     ctx = merge_heads(o)
     S["ctx"] = ctx
@@ -242,11 +248,13 @@ def layer_backward(cfg: Cfg, P, l: int, S, dout, G: Dict[str, np.ndarray]):
 # --------------------------------------------------------------------------
 def train_step(cfg: Cfg, params: Dict[str, np.ndarray], tokens: np.ndarray,
                labels: np.ndarray, plan: int = 0, dtype=np.float64,
-               return_logits: bool = False):
+               return_logits: bool = False, lengths=None):
     """Loss and gradients for one mini-batch.
 
     plan: bitmask, bit l set = layer l drops its activations after its forward
     (only its input survives) and rebuilds them at the start of its backward.
+    lengths (optional, [B]): real tokens per sample of a batch padded to L; padded keys are
+    masked in every attention and padded positions carry no label.
     """
     P = {k: np.asarray(v, dtype=dtype) for k, v in params.items()}
     B, L = tokens.shape
@@ -254,6 +262,9 @@ def train_step(cfg: Cfg, params: Dict[str, np.ndarray], tokens: np.ndarray,
     H = cfg.hidden
     ids = tokens.reshape(T)
     lab = labels.reshape(T)
+    if lengths is not None:
+        lengths = np.asarray(lengths)
+        lab = np.where((np.arange(L)[None, :] >= lengths[:, None]).reshape(T), -1, lab)
     pos = np.tile(np.arange(L), B)
 
     # embedding stage
@@ -269,7 +280,7 @@ def train_step(cfg: Cfg, params: Dict[str, np.ndarray], tokens: np.ndarray,
     saved: List[Optional[dict]] = []
     for l in range(cfg.n_layers):
         inputs.append(h)
-        h, S = layer_forward(cfg, P, l, h, B, L)
+        h, S = layer_forward(cfg, P, l, h, B, L, lengths)
         saved.append(None if (plan >> l) & 1 else S)
 
     # head and loss
@@ -304,7 +315,7 @@ def train_step(cfg: Cfg, params: Dict[str, np.ndarray], tokens: np.ndarray,
     for l in reversed(range(cfg.n_layers)):
         S = saved[l]
         if S is None:
-            _, S = layer_forward(cfg, P, l, inputs[l], B, L)
+            _, S = layer_forward(cfg, P, l, inputs[l], B, L, lengths)
         dh = layer_backward(cfg, P, l, S, dh, G)
         saved[l] = None
 

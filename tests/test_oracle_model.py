@@ -219,3 +219,58 @@ def test_all_plans_bitwise_identical(variant):
         assert l1 == l0
         for k in G0:
             assert np.array_equal(G0[k], G1[k]), (plan, k)
+
+
+# ---------------------------------------------------------------- padded batches
+def _padded_case(causal):
+    import synthdata
+    shape = synthdata.ModelShape(2, 32, 2, 64, 50, 12, "fp32", causal=int(causal), pre_ln=int(causal),
+                                 gelu_tanh=int(causal), head=0 if causal else 1)
+    cfg = om.Cfg.from_shape(synthdata.shape_dict(shape))
+    params = {k: v.astype(np.float64) for k, v in synthdata.make_params(shape, 3, perturb=True).items()}
+    tokens, labels = synthdata.make_batch(shape, 3, 9, 5)
+    return shape, cfg, params, tokens, labels, np.array([9, 4, 6])
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_padded_batch_equals_samples_run_alone(causal):
+    """A batch padded to its longest sample with lengths given must be the samples run one by one
+    at their own lengths: loss = label-count-weighted mean, gradients = label-count-weighted sum
+    (a definition that involves no mask at all)."""
+    shape, cfg, params, tokens, labels, lengths = _padded_case(causal)
+    loss, G = om.train_step(cfg, params, tokens, labels, lengths=lengths)
+    tot_n, tot_loss, tot_G = 0, 0.0, None
+    for b, n in enumerate(lengths):
+        t1, l1 = tokens[b:b + 1, :n], labels[b:b + 1, :n].copy()
+        if causal:
+            l1[0, n - 1] = -1                                       # the last real token has no successor
+        nv = int((l1 >= 0).sum())
+        ls, g = om.train_step(cfg, params, t1, l1)
+        tot_n += nv; tot_loss += ls * nv
+        tot_G = {k: v * nv for k, v in g.items()} if tot_G is None else {k: tot_G[k] + g[k] * nv for k in g}
+    if causal:                                                      # same labels in the padded run
+        lab2 = labels.copy()
+        for b, n in enumerate(lengths):
+            lab2[b, n - 1:] = -1
+        loss, G = om.train_step(cfg, params, tokens, lab2, lengths=lengths)
+    assert abs(loss - tot_loss / tot_n) < 1e-12
+    for k in G:
+        if k == "pos_emb":                                          # rows past a sample's length get nothing from it
+            pass
+        np.testing.assert_allclose(G[k], tot_G[k] / tot_n, rtol=1e-9, atol=1e-13, err_msg=k)
+
+
+def test_padding_content_does_not_matter():
+    shape, cfg, params, tokens, labels, lengths = _padded_case(False)
+    loss, G = om.train_step(cfg, params, tokens, labels, lengths=lengths)
+    t2 = tokens.copy()
+    for b, n in enumerate(lengths):
+        t2[b, n:] = (t2[b, n:] + 7) % shape.vocab
+    loss2, G2 = om.train_step(cfg, params, t2, labels, lengths=lengths)
+    assert loss == loss2
+    for k in G:
+        np.testing.assert_array_equal(G[k], G2[k])
+    # full lengths are the unpadded definition
+    loss3, G3 = om.train_step(cfg, params, tokens, labels, lengths=np.full(3, tokens.shape[1]))
+    loss4, G4 = om.train_step(cfg, params, tokens, labels)
+    assert loss3 == loss4 and all(np.array_equal(G3[k], G4[k]) for k in G3)
