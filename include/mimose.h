@@ -116,6 +116,21 @@ int mimose_load_param(mimose_ctx* ctx, int32_t i, const float* host_fp32, uint64
 int mimose_train_step(mimose_ctx* ctx, const int32_t* tokens_host, const int32_t* labels_host,
                       int32_t B, int32_t L, float* loss, uint64_t* peak_bytes, uint64_t* plan_id);
 
+/*
+ * The same iteration on a batch whose samples were padded to the longest one
+ * (Section 3.1: the input tensor of a batch has the size of its longest
+ * sample; the planner's x stays B*L, padding included).
+ *   lengths_host [B] real tokens of each sample, 1 <= lengths[b] <= L; borrowed.
+ * Positions from lengths[b] on are padding: no query gives them attention
+ * weight, their labels are ignored, and no gradient reaches them; their token
+ * ids must still lie in [0,vocab).  Memory use, plan and error behaviour are
+ * those of mimose_train_step at the same B and L.
+ * Errors: as mimose_train_step, plus INVALID_ARG for a length outside [1, L].
+ */
+int mimose_train_step_padded(mimose_ctx* ctx, const int32_t* tokens_host, const int32_t* labels_host,
+                             const int32_t* lengths_host, int32_t B, int32_t L, float* loss,
+                             uint64_t* peak_bytes, uint64_t* plan_id);
+
 /* Same planning, allocation and bookkeeping as mimose_train_step but no device work:
  * reports the peak the step would reach.  Works on host-only contexts. */
 int mimose_dry_step(mimose_ctx* ctx, int32_t B, int32_t L, uint64_t* peak_bytes, uint64_t* plan_id);
@@ -237,14 +252,18 @@ int32_t mimose_op_partial_rows(int32_t T);
 int mimose_op_gelu_bwd(int32_t dtype, void* d, const void* pre, int64_t n, int32_t tanh_form,
                        void* stream);
 /* qkv [B*L, 3*H] (q | k | v, heads contiguous inside each) -> ctx [B*L, H], lse fp32 [B, h, L].
- * head_dim must be 32 or 64. */
-int mimose_op_attention_fwd(int32_t dtype, const void* qkv, void* ctx, float* lse, int32_t B,
-                            int32_t L, int32_t n_heads, int32_t head_dim, int32_t causal,
-                            void* stream);
-/* dqkv from qkv, ctx, dctx, lse; delta: fp32 scratch [B, h, L]. */
+ * head_dim must be 32 or 64.  lengths: NULL, or device int32 [B] with 1 <= lengths[b] <= L (not
+ * checked: the caller guarantees it): keys of sample b from lengths[b] on are padding and get
+ * no weight. */
+int mimose_op_attention_fwd(int32_t dtype, const void* qkv, void* ctx, float* lse,
+                            const int32_t* lengths, int32_t B, int32_t L, int32_t n_heads,
+                            int32_t head_dim, int32_t causal, void* stream);
+/* dqkv from qkv, ctx, dctx, lse; delta: fp32 scratch [B, h, L]; lengths as in the forward (dK, dV
+ * of padded keys are written as zeros). */
 int mimose_op_attention_bwd(int32_t dtype, const void* qkv, const void* ctx, const void* dctx,
-                            const float* lse, float* delta, void* dqkv, int32_t B, int32_t L,
-                            int32_t n_heads, int32_t head_dim, int32_t causal, void* stream);
+                            const float* lse, float* delta, void* dqkv, const int32_t* lengths,
+                            int32_t B, int32_t L, int32_t n_heads, int32_t head_dim,
+                            int32_t causal, void* stream);
 /* logits [T, ld] (first V columns valid) -> in place d loss / d logits (columns >= V zeroed);
  * row_loss fp32[T]; loss: device fp32 scalar = sum(row_loss)/n_valid. */
 int mimose_op_softmax_xent(int32_t dtype, void* logits, int64_t ld, const int32_t* labels,

@@ -63,6 +63,8 @@ SIGNATURES = {
     "mimose_param_info": (C.c_int, [_vp, _i32, C.POINTER(C.c_char_p), C.POINTER(_i64), C.POINTER(_i32)]),
     "mimose_load_param": (C.c_int, [_vp, _i32, _vp, _u64]),
     "mimose_train_step": (C.c_int, [_vp, _vp, _vp, _i32, _i32, C.POINTER(_f32), C.POINTER(_u64), C.POINTER(_u64)]),
+    "mimose_train_step_padded": (C.c_int, [_vp, _vp, _vp, _vp, _i32, _i32, C.POINTER(_f32), C.POINTER(_u64),
+                                           C.POINTER(_u64)]),
     "mimose_dry_step": (C.c_int, [_vp, _i32, _i32, C.POINTER(_u64), C.POINTER(_u64)]),
     "mimose_get_grad": (C.c_int, [_vp, _i32, _vp, _u64]),
     "mimose_get_param": (C.c_int, [_vp, _i32, _vp, _u64]),
@@ -87,8 +89,8 @@ SIGNATURES = {
                                           _vp]),
     "mimose_op_partial_rows": (_i32, [_i32]),
     "mimose_op_gelu_bwd": (C.c_int, [_i32, _vp, _vp, _i64, _i32, _vp]),
-    "mimose_op_attention_fwd": (C.c_int, [_i32, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp]),
-    "mimose_op_attention_bwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp]),
+    "mimose_op_attention_fwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp]),
+    "mimose_op_attention_bwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp]),
     "mimose_op_softmax_xent": (C.c_int, [_i32, _vp, _i64, _vp, _vp, _vp, _i32, _i32, _i32, _vp]),
     "mimose_op_embed_fwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _f32, _i32, _vp]),
     "mimose_op_embed_bwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32, _i32, _i32, _i32, _vp]),
@@ -177,6 +179,19 @@ def mimose_train_step(ctx, tokens: np.ndarray, labels: np.ndarray) -> Tuple[floa
     loss, peak, plan = _f32(), _u64(), _u64()
     _check(load_library().mimose_train_step(ctx, t.ctypes.data, l.ctypes.data, B, L, C.byref(loss), C.byref(peak),
                                             C.byref(plan)), ctx)
+    return loss.value, peak.value, plan.value
+
+
+def mimose_train_step_padded(ctx, tokens: np.ndarray, labels: np.ndarray, lengths: np.ndarray) -> Tuple[float, int, int]:
+    t = np.ascontiguousarray(tokens, dtype=np.int32)
+    l = np.ascontiguousarray(labels, dtype=np.int32)
+    n = np.ascontiguousarray(lengths, dtype=np.int32)
+    B, L = t.shape
+    if n.shape != (B,):
+        raise ValueError("lengths must have one entry per sample")
+    loss, peak, plan = _f32(), _u64(), _u64()
+    _check(load_library().mimose_train_step_padded(ctx, t.ctypes.data, l.ctypes.data, n.ctypes.data, B, L,
+                                                   C.byref(loss), C.byref(peak), C.byref(plan)), ctx)
     return loss.value, peak.value, plan.value
 
 
@@ -302,14 +317,16 @@ def mimose_op_gelu_bwd(dtype, d, pre, n, tanh_form, stream=None):
     _check(load_library().mimose_op_gelu_bwd(dtype, _ptr(d), _ptr(pre), n, tanh_form, _ptr(stream)))
 
 
-def mimose_op_attention_fwd(dtype, qkv, ctx_out, lse, B, L, n_heads, head_dim, causal, stream=None):
-    _check(load_library().mimose_op_attention_fwd(dtype, _ptr(qkv), _ptr(ctx_out), _ptr(lse), B, L, n_heads, head_dim,
-                                                  causal, _ptr(stream)))
+def mimose_op_attention_fwd(dtype, qkv, ctx_out, lse, B, L, n_heads, head_dim, causal, stream=None, lengths=None):
+    _check(load_library().mimose_op_attention_fwd(dtype, _ptr(qkv), _ptr(ctx_out), _ptr(lse), _ptr(lengths), B, L,
+                                                  n_heads, head_dim, causal, _ptr(stream)))
 
 
-def mimose_op_attention_bwd(dtype, qkv, ctx_in, dctx, lse, delta, dqkv, B, L, n_heads, head_dim, causal, stream=None):
+def mimose_op_attention_bwd(dtype, qkv, ctx_in, dctx, lse, delta, dqkv, B, L, n_heads, head_dim, causal, stream=None,
+                            lengths=None):
     _check(load_library().mimose_op_attention_bwd(dtype, _ptr(qkv), _ptr(ctx_in), _ptr(dctx), _ptr(lse), _ptr(delta),
-                                                  _ptr(dqkv), B, L, n_heads, head_dim, causal, _ptr(stream)))
+                                                  _ptr(dqkv), _ptr(lengths), B, L, n_heads, head_dim, causal,
+                                                  _ptr(stream)))
 
 
 def mimose_op_softmax_xent(dtype, logits, ld, labels, row_loss, loss, T, V, n_valid, stream=None):
@@ -363,7 +380,9 @@ class Mimose:
             assert tuple(a.shape) == self.shapes[n], (n, a.shape, self.shapes[n])
             mimose_load_param(self.ctx, i, a)
 
-    def train_step(self, tokens, labels):
+    def train_step(self, tokens, labels, lengths=None):
+        if lengths is not None:
+            return mimose_train_step_padded(self.ctx, tokens, labels, lengths)
         return mimose_train_step(self.ctx, tokens, labels)
 
     def dry_step(self, B, L):

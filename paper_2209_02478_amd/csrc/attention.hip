@@ -47,14 +47,16 @@ __device__ __forceinline__ float dot_row(const T* p, const float (&q)[D]) {
 constexpr int kRowsPerBlock = 16;   // 4 waves x 4 rows
 
 // bf16, head size 64: MFMA kernels
-void attention_fwd_mfma(const void* qkv, void* ctx, float* lse, int B, int L, int nh, int causal, hipStream_t st);
-void attention_bwd_mfma(const void* qkv, const void* dctx, const float* lse, const float* delta, void* dqkv, int B,
-                        int L, int nh, int causal, hipStream_t st);
+void attention_fwd_mfma(const void* qkv, void* ctx, float* lse, const int32_t* lens, int B, int L, int nh, int causal,
+                        hipStream_t st);
+void attention_bwd_mfma(const void* qkv, const void* dctx, const float* lse, const float* delta, void* dqkv,
+                        const int32_t* lens, int B, int L, int nh, int causal, hipStream_t st);
 
 // qkv row stride is 3*H; head hh of token t: q at t*3H + hh*D, k at +H, v at +2H.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void attn_fwd_kernel(const T* __restrict__ qkv, T* __restrict__ ctx,
-                                                       float* __restrict__ lse, int L, int nh, int causal) {
+                                                       float* __restrict__ lse, const int32_t* __restrict__ lens,
+                                                       int L, int nh, int causal) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int bh = blockIdx.y, b = bh / nh, hh = bh - b * nh;
   const int H = nh * D;
@@ -66,7 +68,8 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const T* __restrict__ qkv
     if (i >= L) break;
     float q[D];
     load_row<D>(base + (int64_t)i * ld3, q);
-    const int jmax = causal ? i + 1 : L;
+    const int Lb = lens ? lens[b] : L;                 // keys from Lb on are padding
+    const int jmax = min(causal ? i + 1 : L, Lb);
     float m = -INFINITY, l = 0.f, o = 0.f;
     for (int j0 = 0; j0 < jmax; j0 += 64) {
       const int j = j0 + lane;
@@ -109,13 +112,14 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const T* __restrict__ qkv, const T* __restrict__ dctx,
                                                           const float* __restrict__ lse,
                                                           const float* __restrict__ delta, T* __restrict__ dqkv,
-                                                          int L, int nh, int causal) {
+                                                          const int32_t* __restrict__ lens, int L, int nh, int causal) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int bh = blockIdx.y, b = bh / nh, hh = bh - b * nh;
   const int H = nh * D;
   const int64_t ld3 = 3 * (int64_t)H;
   const T* base = qkv + (int64_t)b * L * ld3 + hh * D;
   const float scale = rsqrtf((float)D);
+  const int Lb = lens ? lens[b] : L;
   for (int rr = 0; rr < kRowsPerBlock / 4; ++rr) {
     const int i = blockIdx.x * kRowsPerBlock + wave * (kRowsPerBlock / 4) + rr;
     if (i >= L) break;
@@ -123,7 +127,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const T* __restrict__ 
     load_row<D>(base + (int64_t)i * ld3, q);
     load_row<D>(dctx + ((int64_t)b * L + i) * H + hh * D, go);
     const float lse_i = lse[(int64_t)bh * L + i], delta_i = delta[(int64_t)bh * L + i];
-    const int jmax = causal ? i + 1 : L;
+    const int jmax = min(causal ? i + 1 : L, Lb);
     float dq = 0.f;
     for (int j0 = 0; j0 < jmax; j0 += 64) {
       const int j = j0 + lane;
@@ -146,7 +150,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const T* __restrict__ qkv, const T* __restrict__ dctx,
                                                            const float* __restrict__ lse,
                                                            const float* __restrict__ delta, T* __restrict__ dqkv,
-                                                           int L, int nh, int causal) {
+                                                           const int32_t* __restrict__ lens, int L, int nh, int causal) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int bh = blockIdx.y, b = bh / nh, hh = bh - b * nh;
   const int H = nh * D;
@@ -162,7 +166,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const T* __restrict__
     load_row<D>(base + (int64_t)j * ld3 + 2 * H, v);
     float dk = 0.f, dv = 0.f;
     const int istart = causal ? j : 0;
-    for (int i0 = istart; i0 < L; i0 += 64) {
+    const int iend = (lens && j >= lens[b]) ? 0 : L;     // a padded key gets no weight from any query
+    for (int i0 = istart; i0 < iend; i0 += 64) {
       const int i = i0 + lane;
       float p = 0.f, ds = 0.f;
       if (i < L) {
@@ -189,21 +194,22 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const T* __restrict__
 }
 
 template <typename T, int D>
-static void fwd_t(const void* qkv, void* ctx, float* lse, int B, int L, int nh, int causal, hipStream_t st) {
+static void fwd_t(const void* qkv, void* ctx, float* lse, const int32_t* lens, int B, int L, int nh, int causal,
+                  hipStream_t st) {
   dim3 grid((L + kRowsPerBlock - 1) / kRowsPerBlock, B * nh);
-  hipLaunchKernelGGL((attn_fwd_kernel<T, D>), grid, dim3(256), 0, st, (const T*)qkv, (T*)ctx, lse, L, nh, causal);
+  hipLaunchKernelGGL((attn_fwd_kernel<T, D>), grid, dim3(256), 0, st, (const T*)qkv, (T*)ctx, lse, lens, L, nh, causal);
 }
 template <typename T, int D>
 static void bwd_t(const void* qkv, const void* ctx, const void* dctx, const float* lse, float* delta, void* dqkv,
-                  int B, int L, int nh, int causal, hipStream_t st) {
+                  const int32_t* lens, int B, int L, int nh, int causal, hipStream_t st) {
   int64_t n = (int64_t)B * L * nh;
   hipLaunchKernelGGL((attn_delta_kernel<T, D>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
                      (const T*)ctx, (const T*)dctx, delta, B, L, nh);
   dim3 grid((L + kRowsPerBlock - 1) / kRowsPerBlock, B * nh);
   hipLaunchKernelGGL((attn_bwd_dq_kernel<T, D>), grid, dim3(256), 0, st, (const T*)qkv, (const T*)dctx, lse,
-                     delta, (T*)dqkv, L, nh, causal);
+                     delta, (T*)dqkv, lens, L, nh, causal);
   hipLaunchKernelGGL((attn_bwd_dkv_kernel<T, D>), grid, dim3(256), 0, st, (const T*)qkv, (const T*)dctx, lse,
-                     delta, (T*)dqkv, L, nh, causal);
+                     delta, (T*)dqkv, lens, L, nh, causal);
 }
 
 #define DISPATCH_TD(CALL_F32, CALL_BF16)                         \
@@ -213,29 +219,29 @@ static void bwd_t(const void* qkv, const void* ctx, const void* dctx, const floa
     if (d == 32) { CALL_F32(32); } else { CALL_F32(64); } \
   }
 
-void attention_fwd(int dtype, const void* qkv, void* ctx, float* lse, int B, int L, int nh, int d, int causal,
-                   hipStream_t st) {
+void attention_fwd(int dtype, const void* qkv, void* ctx, float* lse, const int32_t* lens, int B, int L, int nh, int d,
+                   int causal, hipStream_t st) {
   if (B * L <= 0) return;
-  if (dtype == BF16 && d == 64) { attention_fwd_mfma(qkv, ctx, lse, B, L, nh, causal, st); return; }
-#define F32_(DD) fwd_t<float, DD>(qkv, ctx, lse, B, L, nh, causal, st)
-#define BF_(DD) fwd_t<bf16_t, DD>(qkv, ctx, lse, B, L, nh, causal, st)
+  if (dtype == BF16 && d == 64) { attention_fwd_mfma(qkv, ctx, lse, lens, B, L, nh, causal, st); return; }
+#define F32_(DD) fwd_t<float, DD>(qkv, ctx, lse, lens, B, L, nh, causal, st)
+#define BF_(DD) fwd_t<bf16_t, DD>(qkv, ctx, lse, lens, B, L, nh, causal, st)
   DISPATCH_TD(F32_, BF_)
 #undef F32_
 #undef BF_
 }
 
 void attention_bwd(int dtype, const void* qkv, const void* ctx, const void* dctx, const float* lse, float* delta,
-                   void* dqkv, int B, int L, int nh, int d, int causal, hipStream_t st) {
+                   void* dqkv, const int32_t* lens, int B, int L, int nh, int d, int causal, hipStream_t st) {
   if (B * L <= 0) return;
   if (dtype == BF16 && d == 64) {
     int64_t n = (int64_t)B * L * nh;
     hipLaunchKernelGGL((attn_delta_kernel<bf16_t, 64>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
                        (const bf16_t*)ctx, (const bf16_t*)dctx, delta, B, L, nh);
-    attention_bwd_mfma(qkv, dctx, lse, delta, dqkv, B, L, nh, causal, st);
+    attention_bwd_mfma(qkv, dctx, lse, delta, dqkv, lens, B, L, nh, causal, st);
     return;
   }
-#define F32_(DD) bwd_t<float, DD>(qkv, ctx, dctx, lse, delta, dqkv, B, L, nh, causal, st)
-#define BF_(DD) bwd_t<bf16_t, DD>(qkv, ctx, dctx, lse, delta, dqkv, B, L, nh, causal, st)
+#define F32_(DD) bwd_t<float, DD>(qkv, ctx, dctx, lse, delta, dqkv, lens, B, L, nh, causal, st)
+#define BF_(DD) bwd_t<bf16_t, DD>(qkv, ctx, dctx, lse, delta, dqkv, lens, B, L, nh, causal, st)
   DISPATCH_TD(F32_, BF_)
 #undef F32_
 #undef BF_

@@ -120,7 +120,8 @@ __device__ __forceinline__ void store_rows(bf16_t* dst, const f32x16 (&acc)[2], 
 // ------------------------------------------------------------------ forward
 template <bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
-                                                     float* __restrict__ lse, int L, int nh) {
+                                                     float* __restrict__ lse, const int32_t* __restrict__ lens,
+                                                     int L, int nh) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[TK][LDT];   // [key][d]
   __shared__ __attribute__((aligned(16))) bf16_t Vt[D][LDT];    // [d][key]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, ql = lane & 31, h = lane >> 5;
@@ -138,7 +139,8 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(const bf16_t* __restrict
   f32x16 o[2];
   zero(o[0]); zero(o[1]);
   float m = -INFINITY, l = 0.f;                       // running maximum of the raw (unscaled) scores, sum of exps
-  const int kend = CAUSAL ? min(L, (int)(blockIdx.x + 1) * ROWS_PER_BLOCK) : L;
+  const int Lk = lens ? lens[b] : L;                  // keys from Lk on are padding (1 <= Lk <= L)
+  const int kend = CAUSAL ? min(Lk, (int)(blockIdx.x + 1) * ROWS_PER_BLOCK) : Lk;
 
   // threads 0..127 stage K, the others V; the next tile's loads are in flight during the MFMAs
   const bf16_t* mine = tid < 128 ? base + H : base + 2 * H;
@@ -159,11 +161,11 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(const bf16_t* __restrict
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
         s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(&Ks[32 * kb + ql][16 * kk + 8 * h]), qf[kk], s[kb], 0, 0, 0);
-      if (CAUSAL || k0 + TK > L) {                    // only tiles that touch the mask pay for it
+      if (CAUSAL || k0 + TK > Lk) {                   // only tiles that touch the mask pay for it
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int key = k0 + 32 * kb + 8 * (r >> 2) + 4 * h + (r & 3);
-          if (key >= L || (CAUSAL && key > qi)) s[kb][r] = -INFINITY;
+          if (key >= Lk || (CAUSAL && key > qi)) s[kb][r] = -INFINITY;
         }
       }
 #pragma unroll
@@ -209,7 +211,8 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(const bf16_t* __restrict
 template <bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
                                                         const float* __restrict__ lse, const float* __restrict__ delta,
-                                                        bf16_t* __restrict__ dqkv, int L, int nh) {
+                                                        bf16_t* __restrict__ dqkv, const int32_t* __restrict__ lens, int L,
+                                                        int nh) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[TK][LDT];   // [key][d]
   __shared__ __attribute__((aligned(16))) bf16_t Kt[D][LDT];    // [d][key]
   __shared__ __attribute__((aligned(16))) bf16_t Vs[TK][LDT];   // [key][d]
@@ -232,7 +235,8 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(const bf16_t* __restr
   const float nlse_q = -LOG2E * lse[(int64_t)bh * L + qc], delta_q = delta[(int64_t)bh * L + qc];
   f32x16 dq[2];
   zero(dq[0]); zero(dq[1]);
-  const int kend = CAUSAL ? min(L, (int)(blockIdx.x + 1) * ROWS_PER_BLOCK) : L;
+  const int Lk = lens ? lens[b] : L;                  // keys from Lk on are padding (1 <= Lk <= L)
+  const int kend = CAUSAL ? min(Lk, (int)(blockIdx.x + 1) * ROWS_PER_BLOCK) : Lk;
 
   const bf16_t* mine = tid < 128 ? base + H : base + 2 * H;     // threads 0..127 stage K, the others V
   const int t128 = tid & 127;
@@ -255,11 +259,11 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(const bf16_t* __restr
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = fast_exp2(fmaf(s[r], c2, nlse_q)) * (dp[r] - delta_q);
-      if (CAUSAL || k0 + TK > L) {
+      if (CAUSAL || k0 + TK > Lk) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int key = k0 + 32 * kb + 8 * (r >> 2) + 4 * h + (r & 3);
-          if (key >= L || (CAUSAL && key > qi)) s[r] = 0.f;
+          if (key >= Lk || (CAUSAL && key > qi)) s[r] = 0.f;
         }
       }
 #pragma unroll
@@ -278,7 +282,8 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(const bf16_t* __restr
 template <bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void fa_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
                                                          const float* __restrict__ lse, const float* __restrict__ delta,
-                                                         bf16_t* __restrict__ dqkv, int L, int nh) {
+                                                         bf16_t* __restrict__ dqkv, const int32_t* __restrict__ lens, int L,
+                                                        int nh) {
   __shared__ __attribute__((aligned(16))) bf16_t Qs[TK][LDT];   // [query][d]
   __shared__ __attribute__((aligned(16))) bf16_t Qt[D][LDT];    // [d][query]
   __shared__ __attribute__((aligned(16))) bf16_t Gs[TK][LDT];   // dO [query][d]
@@ -303,6 +308,8 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dkv_kernel(const bf16_t* __rest
   f32x16 dk[2], dv[2];
   zero(dk[0]); zero(dk[1]); zero(dv[0]); zero(dv[1]);
   const int qstart = CAUSAL ? blockIdx.x * ROWS_PER_BLOCK : 0;     // earlier queries never see these keys
+  const int Lk = lens ? lens[b] : L;                               // keys from Lk on are padding: their dK, dV are zero
+  const int qend = (int)blockIdx.x * ROWS_PER_BLOCK >= Lk ? 0 : L; // a block of padded keys only writes zeros
 
   const bf16_t* mine = tid < 128 ? base : gbase;                 // threads 0..127 stage Q, the others dO
   const int64_t mine_ld = tid < 128 ? ld3 : (int64_t)H;
@@ -317,14 +324,14 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dkv_kernel(const bf16_t* __rest
       pre_delta = delta[(int64_t)bh * L + q];
     }
   };
-  if (qstart < L) fetch(qstart);
-  for (int q0 = qstart; q0 < L; q0 += TK) {
+  if (qstart < qend) fetch(qstart);
+  for (int q0 = qstart; q0 < qend; q0 += TK) {
     __syncthreads();
     if (tid < 128) stash_tile<true, true>(pre, t128, Qs, Qt);
     else stash_tile<true, true>(pre, t128, Gs, Gt);
     if (tid < TK) { lse_s[tid] = -LOG2E * pre_lse; delta_s[tid] = pre_delta; }   // lse_s: ready for exp2
     __syncthreads();
-    if (q0 + TK < L) fetch(q0 + TK);
+    if (q0 + TK < qend) fetch(q0 + TK);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       f32x16 s, dp;
@@ -366,27 +373,29 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dkv_kernel(const bf16_t* __rest
     }
   }
   if (ki < L) {
+    if (ki >= Lk) { zero(dk[0]); zero(dk[1]); zero(dv[0]); zero(dv[1]); }   // whatever the lane's column held
     bf16_t* out = dqkv + ((int64_t)b * L + ki) * ld3 + hh * D;
     store_rows(out + H, dk, h, scale);
     store_rows(out + 2 * H, dv, h, 1.f);
   }
 }
 
-void attention_fwd_mfma(const void* qkv, void* ctx, float* lse, int B, int L, int nh, int causal, hipStream_t st) {
+void attention_fwd_mfma(const void* qkv, void* ctx, float* lse, const int32_t* lens, int B, int L, int nh, int causal,
+                        hipStream_t st) {
   dim3 grid((L + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, B * nh);
-  if (causal) hipLaunchKernelGGL(fa_fwd_kernel<true>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (bf16_t*)ctx, lse, L, nh);
-  else hipLaunchKernelGGL(fa_fwd_kernel<false>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (bf16_t*)ctx, lse, L, nh);
+  if (causal) hipLaunchKernelGGL(fa_fwd_kernel<true>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (bf16_t*)ctx, lse, lens, L, nh);
+  else hipLaunchKernelGGL(fa_fwd_kernel<false>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (bf16_t*)ctx, lse, lens, L, nh);
 }
 
-void attention_bwd_mfma(const void* qkv, const void* dctx, const float* lse, const float* delta, void* dqkv, int B,
-                        int L, int nh, int causal, hipStream_t st) {
+void attention_bwd_mfma(const void* qkv, const void* dctx, const float* lse, const float* delta, void* dqkv,
+                        const int32_t* lens, int B, int L, int nh, int causal, hipStream_t st) {
   dim3 grid((L + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, B * nh);
   if (causal) {
-    hipLaunchKernelGGL(fa_bwd_dq_kernel<true>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, L, nh);
-    hipLaunchKernelGGL(fa_bwd_dkv_kernel<true>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, L, nh);
+    hipLaunchKernelGGL(fa_bwd_dq_kernel<true>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, lens, L, nh);
+    hipLaunchKernelGGL(fa_bwd_dkv_kernel<true>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, lens, L, nh);
   } else {
-    hipLaunchKernelGGL(fa_bwd_dq_kernel<false>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, L, nh);
-    hipLaunchKernelGGL(fa_bwd_dkv_kernel<false>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, L, nh);
+    hipLaunchKernelGGL(fa_bwd_dq_kernel<false>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, lens, L, nh);
+    hipLaunchKernelGGL(fa_bwd_dkv_kernel<false>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, lens, L, nh);
   }
 }
 

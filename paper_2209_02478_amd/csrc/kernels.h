@@ -46,10 +46,12 @@ void layernorm_bwd(int dtype, const void* dy, bool dy_f32, const void* x, bool x
                    float* partial, int T, int H, float eps, hipStream_t st);
 int partial_rows(int T);
 void gelu_bwd(int dtype, void* d, const void* pre, int64_t n, int tanh_form, hipStream_t st);
-void attention_fwd(int dtype, const void* qkv, void* ctx, float* lse, int B, int L, int nh, int d,
+// lens (optional, device, [B]): real tokens per sample of a padded batch; keys from lens[b] on get
+// no weight.  nullptr: every sample fills its row.
+void attention_fwd(int dtype, const void* qkv, void* ctx, float* lse, const int32_t* lens, int B, int L, int nh, int d,
                    int causal, hipStream_t st);
 void attention_bwd(int dtype, const void* qkv, const void* ctx, const void* dctx, const float* lse,
-                   float* delta, void* dqkv, int B, int L, int nh, int d, int causal,
+                   float* delta, void* dqkv, const int32_t* lens, int B, int L, int nh, int d, int causal,
                    hipStream_t st);
 void softmax_xent(int dtype, void* logits, int64_t ld, const int32_t* labels, float* row_loss,
                   float* loss, int T, int V, int n_valid, hipStream_t st);

@@ -198,6 +198,7 @@ class Step {
         st_(c->stream), dt_(c->cfg.dtype), es_(c->elt()) {}
 
   void run(const int32_t* tokens, const int32_t* labels, float* loss_out);
+  const int32_t* lens_host = nullptr;   // padded batch: real tokens per sample ([B], host), else null
 
   // collected bytes (valid after run)
   uint64_t e_bytes = 0, g_bytes = 0;
@@ -212,7 +213,7 @@ class Step {
   hipStream_t st_;
   int dt_, es_;
   // embedding-stage tensors
-  int32_t *ids_ = nullptr, *labels_ = nullptr, *order_ = nullptr, *seg_ = nullptr;
+  int32_t *ids_ = nullptr, *labels_ = nullptr, *order_ = nullptr, *seg_ = nullptr, *lens_ = nullptr;
   // Gradient of the residual stream.  Post-LN blocks in bf16 carry it in fp32 (gA_, gB_) and
   // keep the bf16 copies the products consume in oA_, oB_; otherwise the carriers have the
   // storage type and oA_/oB_ alias them (LayerNorm backward then works in place).
@@ -324,9 +325,11 @@ class Step {
 
 void Step::embed_stage(const int32_t* tokens, const int32_t* labels) {
   const int H = f_.hidden;
-  int32_t* ints = (int32_t*)c_->arena.alloc((uint64_t)(4 * (int64_t)T_ + 1) * 4);
+  // ids, labels, sort order, run boundaries, per-sample lengths (the last B only read for padded batches)
+  int32_t* ints = (int32_t*)c_->arena.alloc((uint64_t)(4 * (int64_t)T_ + 1 + B_) * 4);
   ids_ = ints; labels_ = ints ? ints + T_ : nullptr; order_ = ints ? ints + 2 * (int64_t)T_ : nullptr;
   seg_ = ints ? ints + 3 * (int64_t)T_ : nullptr;
+  lens_ = ints && lens_host ? ints + 4 * (int64_t)T_ + 1 : nullptr;
   wide_ = !f_.pre_ln && dt_ == mk::BF16;
   gA_ = walloc((int64_t)T_ * H);
   gB_ = walloc((int64_t)T_ * H);
@@ -337,7 +340,7 @@ void Step::embed_stage(const int32_t* tokens, const int32_t* labels) {
   if (dry_) return;
 
   // host side: stable sort of positions by token id, run boundaries of equal ids
-  const size_t need = 4 * (size_t)T_ + 1;
+  const size_t need = 4 * (size_t)T_ + 1 + (size_t)B_;
   if (c_->stage_ints < need) {
     if (c_->stage) HIPCHK(c_, hipHostFree(c_->stage));
     c_->stage = nullptr;
@@ -347,6 +350,12 @@ void Step::embed_stage(const int32_t* tokens, const int32_t* labels) {
   int32_t* s = c_->stage;
   std::memcpy(s, tokens, (size_t)T_ * 4);
   std::memcpy(s + T_, labels, (size_t)T_ * 4);
+  if (lens_host) {                        // padded positions are never scored
+    for (int b = 0; b < B_; ++b)
+      for (int p = lens_host[b]; p < L_; ++p) s[T_ + (size_t)b * L_ + p] = -1;
+    std::memcpy(s + 4 * (size_t)T_ + 1, lens_host, (size_t)B_ * 4);
+    HIPCHK(c_, hipMemcpyAsync(lens_, s + 4 * (size_t)T_ + 1, (size_t)B_ * 4, hipMemcpyHostToDevice, st_));
+  }
   HIPCHK(c_, hipMemcpyAsync(ints, s, 2 * (size_t)T_ * 4, hipMemcpyHostToDevice, st_));
   Timed t(this, MIMOSE_K_EMBED_FWD, (f_.pre_ln ? 3.0 : 4.0) * T_ * H * es_d());
   mk::embed_fwd(dt_, ids_, w(c_->i_tok), w(c_->i_pos), f_.pre_ln ? nullptr : w(c_->i_eg),
@@ -382,7 +391,7 @@ void Step::layer_forward(int l, LayerActs& A) {
   linear(a, H, p.wqkv, p.bqkv, A.qkv, 3 * H, 3 * H);
   {
     Timed t(this, MIMOSE_K_ATTN_FWD, 4.0 * T_ * L_ * H * (f_.causal ? 0.5 : 1.0));
-    if (!dry_) mk::attention_fwd(dt_, A.qkv, A.ctx, A.lse, B_, L_, nh, d, f_.causal, st_);
+    if (!dry_) mk::attention_fwd(dt_, A.qkv, A.ctx, A.lse, lens_, B_, L_, nh, d, f_.causal, st_);
   }
   linear(A.ctx, H, p.wo, p.bo, A.s1, H, H, A.x, nullptr, 0, wide_);
   if (f_.pre_ln) {
@@ -432,7 +441,7 @@ void Step::layer_backward(int l, LayerActs& A) {
   float* delta = (float*)ar.alloc((uint64_t)B_ * nh * L_ * 4);
   {
     Timed t(this, MIMOSE_K_ATTN_BWD, 8.0 * T_ * L_ * H * (f_.causal ? 0.5 : 1.0));
-    if (!dry_) mk::attention_bwd(dt_, A.qkv, A.ctx, dctx, A.lse, delta, dqkv, B_, L_, nh, d, f_.causal, st_);
+    if (!dry_) mk::attention_bwd(dt_, A.qkv, A.ctx, dctx, A.lse, delta, dqkv, lens_, B_, L_, nh, d, f_.causal, st_);
   }
   const void* a = f_.pre_ln ? A.n1 : A.x;
   wgrad(dqkv, 3 * H, 3 * H, a, H, p.wqkv, p.bqkv);
@@ -537,7 +546,10 @@ void Step::run(const int32_t* tokens, const int32_t* labels, float* loss_out) {
   ar.reset_high();
   if (!dry_) {
     n_valid_ = 0;
-    for (int t = 0; t < T_; ++t) n_valid_ += labels[t] >= 0;
+    for (int b = 0; b < B_; ++b) {
+      const int n = lens_host ? lens_host[b] : L_;
+      for (int p = 0; p < n; ++p) n_valid_ += labels[(size_t)b * L_ + p] >= 0;
+    }
   }
   const uint64_t base = ar.top();
   float* loss_dev = (float*)ar.alloc(4);
@@ -604,8 +616,8 @@ void flops(const mimose_model_cfg& f, int B, int L, int n_re, double* useful, do
   *re = T * layer * n_re;
 }
 
-int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, int32_t B, int32_t L, bool dry,
-            float* loss, uint64_t* peak, uint64_t* plan_id) {
+int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, const int32_t* lengths, int32_t B, int32_t L,
+            bool dry, float* loss, uint64_t* peak, uint64_t* plan_id) {
   const auto& f = c->cfg;
   if (B < 1 || L < 1 || L > f.max_seq) return fail(c, MIMOSE_ERR_INVALID_ARG, "B >= 1 and 1 <= L <= max_seq required");
   if ((int64_t)B * L > (int64_t)1 << 28) return fail(c, MIMOSE_ERR_INVALID_ARG, "B*L too large");
@@ -617,6 +629,9 @@ int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, int32_t
       if (tokens[t] < 0 || tokens[t] >= f.vocab) return fail(c, MIMOSE_ERR_INVALID_ARG, "token id out of range");
       if (labels[t] < -1 || labels[t] >= f.vocab) return fail(c, MIMOSE_ERR_INVALID_ARG, "label out of range");
     }
+    if (lengths)
+      for (int b = 0; b < B; ++b)
+        if (lengths[b] < 1 || lengths[b] > L) return fail(c, MIMOSE_ERR_INVALID_ARG, "sample length outside [1, L]");
   }
   const int64_t x = (int64_t)B * L;
   const uint64_t all = f.n_layers >= 64 ? ~(uint64_t)0 : (((uint64_t)1 << f.n_layers) - 1);
@@ -653,6 +668,7 @@ int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, int32_t
   // ---- run
   c->dry = dry;
   Step s(c, B, L, plan, collect);
+  s.lens_host = dry ? nullptr : lengths;
   float lv = 0.f;
   try {
     s.run(tokens, labels, &lv);
@@ -803,12 +819,19 @@ int mimose_load_param(mimose_ctx* c, int32_t i, const float* host, uint64_t n) {
 int mimose_train_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, int32_t B, int32_t L,
                       float* loss, uint64_t* peak, uint64_t* plan_id) {
   if (!c) return MIMOSE_ERR_INVALID_ARG;
-  return do_step(c, tokens, labels, B, L, false, loss, peak, plan_id);
+  return do_step(c, tokens, labels, nullptr, B, L, false, loss, peak, plan_id);
+}
+
+int mimose_train_step_padded(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, const int32_t* lengths,
+                             int32_t B, int32_t L, float* loss, uint64_t* peak, uint64_t* plan_id) {
+  if (!c) return MIMOSE_ERR_INVALID_ARG;
+  if (!lengths) return fail(c, MIMOSE_ERR_INVALID_ARG, "lengths must be given");
+  return do_step(c, tokens, labels, lengths, B, L, false, loss, peak, plan_id);
 }
 
 int mimose_dry_step(mimose_ctx* c, int32_t B, int32_t L, uint64_t* peak, uint64_t* plan_id) {
   if (!c) return MIMOSE_ERR_INVALID_ARG;
-  return do_step(c, nullptr, nullptr, B, L, true, nullptr, peak, plan_id);
+  return do_step(c, nullptr, nullptr, nullptr, B, L, true, nullptr, peak, plan_id);
 }
 
 int mimose_get_grad(mimose_ctx* c, int32_t i, float* host, uint64_t n) {

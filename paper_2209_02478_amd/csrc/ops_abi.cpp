@@ -55,19 +55,19 @@ int mimose_op_gelu_bwd(int32_t dtype, void* d, const void* pre, int64_t n, int32
   return done();
 }
 
-int mimose_op_attention_fwd(int32_t dtype, const void* qkv, void* ctx, float* lse, int32_t B, int32_t L,
-                            int32_t nh, int32_t d, int32_t causal, void* stream) {
+int mimose_op_attention_fwd(int32_t dtype, const void* qkv, void* ctx, float* lse, const int32_t* lengths, int32_t B,
+                            int32_t L, int32_t nh, int32_t d, int32_t causal, void* stream) {
   if (bad_dtype(dtype) || !qkv || !ctx || !lse || B < 0 || L < 0 || nh < 1 || bad_head(d)) return MIMOSE_ERR_INVALID_ARG;
-  mk::attention_fwd(dtype, qkv, ctx, lse, B, L, nh, d, causal, (hipStream_t)stream);
+  mk::attention_fwd(dtype, qkv, ctx, lse, lengths, B, L, nh, d, causal, (hipStream_t)stream);
   return done();
 }
 
 int mimose_op_attention_bwd(int32_t dtype, const void* qkv, const void* ctx, const void* dctx, const float* lse,
-                            float* delta, void* dqkv, int32_t B, int32_t L, int32_t nh, int32_t d, int32_t causal,
-                            void* stream) {
+                            float* delta, void* dqkv, const int32_t* lengths, int32_t B, int32_t L, int32_t nh,
+                            int32_t d, int32_t causal, void* stream) {
   if (bad_dtype(dtype) || !qkv || !ctx || !dctx || !lse || !delta || !dqkv || B < 0 || L < 0 || nh < 1 || bad_head(d))
     return MIMOSE_ERR_INVALID_ARG;
-  mk::attention_bwd(dtype, qkv, ctx, dctx, lse, delta, dqkv, B, L, nh, d, causal, (hipStream_t)stream);
+  mk::attention_bwd(dtype, qkv, ctx, dctx, lse, delta, dqkv, lengths, B, L, nh, d, causal, (hipStream_t)stream);
   return done();
 }
 

@@ -177,5 +177,23 @@ def make_batch(s: ModelShape, B: int, L: int, seed: int) -> Tuple[np.ndarray, np
     return tokens, labels
 
 
+def make_padded_batch(s: ModelShape, lengths, seed: int) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """tokens[B, L], labels[B, L], lengths[B] (int32) of a batch whose samples have their own
+    lengths and are padded to the longest, L = max(lengths).
+
+    Padding positions hold token id 0 and label -1.  Causal shapes: the last real token of a
+    sample has no successor and carries no label.
+    """
+    lengths = np.asarray(lengths, dtype=np.int32)
+    B, L = len(lengths), int(lengths.max())
+    tokens, labels = make_batch(s, B, L, seed)
+    for b, n in enumerate(lengths):
+        tokens[b, n:] = 0
+        labels[b, n:] = -1
+        if s.causal:
+            labels[b, n - 1] = -1
+    return tokens, labels, lengths
+
+
 def step_seed(workload_seed: int, step: int) -> int:
     return (workload_seed * 1000003 + step * 7919 + 17) & 0x7FFFFFFFFFFFFFFF

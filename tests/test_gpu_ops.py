@@ -212,23 +212,26 @@ def test_gelu_bwd(dtype, form):
 
 
 # ---------------------------------------------------------------- attention
-def attention_case(dtype, B, L, nh, d, causal, seed):
+def attention_case(dtype, B, L, nh, d, causal, seed, lengths=None):
     rng = np.random.default_rng(seed)
+    lens_dev = None if lengths is None else torch.tensor(lengths, dtype=torch.int32, device=DEV)
     H = nh * d
     qkv = rng.standard_normal((B * L, 3 * H)).astype(np.float32)
     dctx = rng.standard_normal((B * L, H)).astype(np.float32)
     qq = quant(qkv, dtype)
     q, k, v = (om.split_heads(qq[:, i * H:(i + 1) * H], B, L, nh) for i in range(3))
-    o, p = om.attention_fwd(q, k, v, causal)
+    o, p = om.attention_fwd(q, k, v, causal, lengths=lengths)
     ctx_ref = om.merge_heads(o)
     s = (q @ k.transpose(0, 1, 3, 2)) / np.sqrt(d)
     if causal:
         s = np.where(np.triu(np.ones((L, L), bool), 1), -np.inf, s)
+    if lengths is not None:                                  # padded keys carry no weight
+        s = np.where(np.arange(L)[None, None, None, :] >= np.asarray(lengths)[:, None, None, None], -np.inf, s)
     lse_ref = np.log(np.exp(s - s.max(-1, keepdims=True)).sum(-1)) + s.max(-1)
     dqkv_dev = dev(qkv, dtype)
     ctx = torch.zeros((B * L, H), dtype=dqkv_dev.dtype, device=DEV)
     lse = torch.zeros(B * nh * L, dtype=torch.float32, device=DEV)
-    mi.mimose_op_attention_fwd(dtype, dqkv_dev, ctx, lse, B, L, nh, d, causal)
+    mi.mimose_op_attention_fwd(dtype, dqkv_dev, ctx, lse, B, L, nh, d, causal, lengths=lens_dev)
     sync()
     if dtype == 0:
         close(host(ctx), ctx_ref, dtype, k=3.0)
@@ -246,9 +249,12 @@ def attention_case(dtype, B, L, nh, d, causal, seed):
     ddctx = dev(dctx, dtype)
     delta = torch.zeros(B * nh * L, dtype=torch.float32, device=DEV)
     out = torch.zeros_like(dqkv_dev)
-    mi.mimose_op_attention_bwd(dtype, dqkv_dev, ctx, ddctx, lse, delta, out, B, L, nh, d, causal)
+    mi.mimose_op_attention_bwd(dtype, dqkv_dev, ctx, ddctx, lse, delta, out, B, L, nh, d, causal, lengths=lens_dev)
     sync()
     got = host(out)
+    if lengths is not None:                                  # dK, dV of padded keys: exact zeros
+        pad = (np.arange(L)[None, :] >= np.asarray(lengths)[:, None]).reshape(-1)
+        assert not got[pad, H:].any()
     floor = 1e-2 * np.linalg.norm(ref)                      # dQ and dK vanish identically when L = 1
     for i, name in enumerate("qkv"):
         part = ref[:, i * H:(i + 1) * H]
@@ -262,6 +268,16 @@ def attention_case(dtype, B, L, nh, d, causal, seed):
 @pytest.mark.parametrize("B,L,nh,d", [(2, 70, 2, 32), (1, 200, 3, 64), (3, 1, 2, 64), (2, 17, 1, 32), (1, 129, 2, 64), (2, 333, 2, 64)])
 def test_attention(dtype, causal, B, L, nh, d):
     attention_case(dtype, B, L, nh, d, causal, seed=B * 100 + L)
+
+
+# samples padded to the batch's longest: a sample of one token, padding that starts inside a key
+# tile, whole key blocks of padding, no padding at all
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("causal", [0, 1])
+@pytest.mark.parametrize("L,nh,d,lengths", [(70, 2, 32, [70, 1, 33]), (200, 3, 64, [200, 64, 65]),
+                                            (333, 2, 64, [5, 333, 128, 129]), (17, 1, 64, [17, 16])])
+def test_attention_padded(dtype, causal, L, nh, d, lengths):
+    attention_case(dtype, len(lengths), L, nh, d, causal, seed=L + 7, lengths=lengths)
 
 
 # ---------------------------------------------------------------- softmax cross-entropy

@@ -13,17 +13,17 @@ pytestmark = pytest.mark.gpu
 MiB = 1 << 20
 
 
-def oracle_step(shape, params, tokens, labels, dtype=np.float64):
+def oracle_step(shape, params, tokens, labels, dtype=np.float64, lengths=None):
     cfg = om.Cfg.from_shape(synthdata.shape_dict(shape))
     if shape.dtype == "bf16":
         params = {k: om.round_to_bf16(v) for k, v in params.items()}
-    return om.train_step(cfg, params, tokens, labels, dtype=dtype)
+    return om.train_step(cfg, params, tokens, labels, dtype=dtype, lengths=lengths)
 
 
-def check_against_oracle(shape, m, params, tokens, labels, loss_tol, grad_tol, oracle_dtype=np.float64):
-    loss, peak, plan = m.train_step(tokens, labels)
+def check_against_oracle(shape, m, params, tokens, labels, loss_tol, grad_tol, oracle_dtype=np.float64, lengths=None):
+    loss, peak, plan = m.train_step(tokens, labels, lengths=lengths)
     G = m.grads()
-    ref_loss, RG = oracle_step(shape, params, tokens, labels, oracle_dtype)
+    ref_loss, RG = oracle_step(shape, params, tokens, labels, oracle_dtype, lengths)
     assert abs(loss - ref_loss) <= loss_tol * abs(ref_loss), (loss, ref_loss)
     worst = ("", 0.0)
     for k, ref in RG.items():
@@ -151,6 +151,59 @@ def test_degenerate_batches(name):
     with pytest.raises(mi.MimoseError) as e:
         m.train_step(*synthdata.make_batch(shape, 1, shape.max_seq + 1, 46))      # longer than the position table
     assert e.value.code == mi.MIMOSE_ERR_INVALID_ARG
+    m.close()
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_padded_batches(name):
+    """Samples of their own lengths padded to the longest (Section 3.1): parity with the oracle,
+    the same bits under every plan, nothing depends on what the padding holds, memory and plan
+    are those of the unpadded call at the same B and L, and lengths == L is the unpadded step."""
+    shape = SMALL[name]
+    fp32 = shape.dtype == "fp32"
+    n = shape.n_layers
+    params = synthdata.make_params(shape, 51, perturb=True)
+    m = mi.Mimose(synthdata.shape_dict(shape), 0, arena_bytes=256 * MiB)
+    m.load_params(params)
+    m.force_plan(0)
+    for lengths in ([33, 2, 17, 32], [7, 7, 1], [shape.max_seq, 3]):
+        tokens, labels, lens = synthdata.make_padded_batch(shape, lengths, 60 + len(lengths))
+        if not shape.causal:
+            labels[0, 0] = -1
+        loss0, peak0, _, _ = check_against_oracle(shape, m, params, tokens, labels, 1e-4 if fp32 else 1e-2,
+                                                  1e-3 if fp32 else 2e-2, lengths=lens)
+        G0 = m.grads()
+        m.force_plan((1 << n) - 1)
+        loss1, peak1, plan1 = m.train_step(tokens, labels, lengths=lens)
+        assert loss1 == loss0 and plan1 == (1 << n) - 1 and peak1 < peak0
+        G1 = m.grads()
+        m.force_plan(0)
+        # other ids and labels in the padding: the same bits, except that the padding ids' own
+        # embedding rows are no longer touched (they got exact zeros before)
+        t2, l2 = tokens.copy(), labels.copy()
+        for b, k in enumerate(lens):
+            t2[b, k:] = (7 * b + 3) % shape.vocab
+            l2[b, k:] = 5
+        loss2, peak2, _ = m.train_step(t2, l2, lengths=lens)
+        G2 = m.grads()
+        assert loss2 == loss0 and peak2 == peak0
+        for k in G0:
+            assert np.array_equal(G0[k], G1[k]), k
+            assert np.array_equal(G0[k], G2[k]), k
+        _, peak3, _ = m.train_step(tokens, labels)                   # unpadded call, same B and L
+        assert peak3 == peak0
+    tokens, labels = synthdata.make_batch(shape, 3, 20, 70)
+    la, _, _ = m.train_step(tokens, labels)
+    Ga = m.grads()
+    lb, _, _ = m.train_step(tokens, labels, lengths=np.full(3, 20))
+    Gb = m.grads()
+    assert la == lb
+    for k in Ga:
+        assert np.array_equal(Ga[k], Gb[k]), k
+    for bad in ([0, 20, 20], [21, 20, 20]):
+        with pytest.raises(mi.MimoseError) as e:
+            m.train_step(tokens, labels, lengths=np.array(bad))
+        assert e.value.code == mi.MIMOSE_ERR_INVALID_ARG
     m.close()
 
 
