@@ -52,6 +52,8 @@ def main():
                          "none ignores the budget)")
     ap.add_argument("--no-update", action="store_true",
                     help="leave the parameter update (AdamW) out of the iteration: forward, loss and backward only")
+    ap.add_argument("--cost-aware", action="store_true",
+                    help="use the forward times collected in the sheltered steps inside Algorithm 1's buckets")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 256 MiB element-wise copy kernels (reference for scaling FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -85,7 +87,7 @@ def main():
     if args.plan_mode == "none":                      # the no-checkpoint limit needs the whole peak
         m = mi.Mimose(d, 0, arena_bytes=peak0 + (1 << 20))
     else:
-        m = mi.Mimose(d, budget)
+        m = mi.Mimose(d, budget, cost_aware=int(args.cost_aware))
     m.set_plan_mode(args.plan_mode)
     m.load_params(synthdata.make_params(shape, wl.seed))
     if update:
@@ -165,11 +167,13 @@ def main():
         "value": round(K * B / dt, 2), "unit": "samples/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
         "ms_per_step": round(1e3 * dt / K, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": shape.dtype, "data": "synthetic",
-        "config": {"workload": f"{wl.name}: {N} layers, hidden {shape.hidden}, {shape.n_heads} heads, ffn {shape.ffn}, "
+        "config": {"workload": f"{wl.name}: {N} layers, hidden {shape.hidden}, {shape.n_heads} heads, ffn "
+                               f"{'/'.join(map(str, shape.ffn_by_layer)) if shape.ffn_by_layer else shape.ffn}, "
                                f"vocab {shape.vocab}, batch {B}, per-batch length {wl.length_recipe}, "
                                f"budget {wl.budget_frac:.2f} x no-checkpoint peak at L={shape.max_seq}",
                    "global_batch": B, "mean_seq_len": round(float(np.mean([t.shape[1] for t, _ in timed])), 1),
-                   "budget_bytes": budget, "sheltered_steps": sheltered, "plan_mode": args.plan_mode},
+                   "budget_bytes": budget, "sheltered_steps": sheltered, "plan_mode": args.plan_mode,
+                   "cost_aware": bool(args.cost_aware)},
         "tokens_per_s": round(sum(t.size for t, _ in timed) / dt, 1),
         "useful_tflops": round(useful / dt / 1e12, 2), "recompute_tflops": round(recompute / dt / 1e12, 2),
         "mfma_frac_useful": round(useful / dt / 1e12 / PEAK_BF16_TFLOPS, 4),

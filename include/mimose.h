@@ -55,6 +55,15 @@ typedef struct {
   int32_t size_quantum;        /* [1]   plan-cache key granularity, Section 5                */
   uint64_t reserve_bytes;      /* kept free below the budget (Section 6.4 keeps 0.5-1 GB)    */
   uint64_t guard_bytes;        /* added to every predicted component; 0 selects 4096         */
+  /* stacks whose layers differ (the stages of Section 4.4): width of layer l's feed-forward
+   * block; 0 = ffn.  Entries from n_layers on are ignored. */
+  int32_t ffn_by_layer[64];
+  /* 1: inside the bucket Algorithm 1 selects, take the earliest layer whose estimated forward
+   * time (collected in the sheltered phase, Section 4.1) is within bucket_tol_permille of the
+   * bucket's cheapest remaining layer, instead of simply the earliest.  Equal times, or no
+   * collected times (host-only contexts that were fed none), give Algorithm 1. */
+  int32_t cost_aware;
+  int32_t reserved_;           /* keep zero */
 } mimose_model_cfg;
 
 typedef struct {
@@ -75,6 +84,7 @@ typedef struct {
 #define MIMOSE_Q_EMBED 3         /* e: bytes of the embedding stage held all step           */
 #define MIMOSE_Q_HEAD 4          /* g: transient bytes of head forward + backward           */
 #define MIMOSE_Q_FIXED 5         /* F: parameters, gradients, persistent scratch            */
+#define MIMOSE_Q_LAYER_TIME 6    /* t_l: forward time of layer l in ns (Section 4.1)        */
 
 /*
  * Create a context (Section 4.1: the planner wraps the training iteration).
@@ -209,6 +219,10 @@ int mimose_profile_read(mimose_ctx* ctx, int32_t kernel_class, uint64_t* launche
  * bytes kept (a_l), kept when checkpointed (b_l) and the backward transient (w_l). */
 int mimose_get_step_memory(mimose_ctx* ctx, uint64_t* fixed, uint64_t* embed, uint64_t* head,
                            uint64_t* kept, uint64_t* boundary, uint64_t* bwd);
+
+/* Forward time of each layer in the last sheltered (collecting) step, in ns, as fed to the
+ * estimator (Section 4.1).  ns: host array of n_layers.  NOT_READY before the first such step. */
+int mimose_get_layer_times(mimose_ctx* ctx, uint64_t* ns);
 
 int mimose_get_stats(mimose_ctx* ctx, mimose_stats* out);
 const char* mimose_last_error(mimose_ctx* ctx); /* ctx may be NULL: last init error */

@@ -49,12 +49,13 @@ class Cfg:
     gelu_tanh: int = 0
     head: int = 1
     ln_eps: float = 1e-5
+    ffn_by_layer: tuple = ()      # feed-forward width of each layer when they differ (empty: ffn)
 
     @staticmethod
     def from_shape(d: dict) -> "Cfg":
         keys = ("n_layers", "hidden", "n_heads", "ffn", "vocab", "max_seq",
                 "causal", "pre_ln", "gelu_tanh", "head", "ln_eps")
-        return Cfg(**{k: d[k] for k in keys})
+        return Cfg(**{k: d[k] for k in keys}, ffn_by_layer=tuple(d.get("ffn_by_layer", ()) or ()))
 
 
 # --------------------------------------------------------------------------
@@ -336,12 +337,16 @@ def train_step(cfg: Cfg, params: Dict[str, np.ndarray], tokens: np.ndarray,
     return loss, G
 
 
-def flops_per_step(cfg: Cfg, B: int, L: int, n_recomputed: int = 0) -> Tuple[float, float]:
-    """(useful, recompute) floating-point operations of one step, 2mnk per product."""
+def flops_per_step(cfg: Cfg, B: int, L: int, n_recomputed: int = 0, plan: int = None) -> Tuple[float, float]:
+    """(useful, recompute) floating-point operations of one step, 2mnk per product.
+    The recomputed layers are the first n_recomputed, or those whose bit is set in plan."""
     T = B * L
-    H, F, V = cfg.hidden, cfg.ffn, cfg.vocab
+    H, V = cfg.hidden, cfg.vocab
+    if plan is None:
+        plan = (1 << n_recomputed) - 1
     attn = 4.0 * L * H * (0.5 if cfg.causal else 1.0)
-    layer = 8.0 * H * H + 4.0 * H * F + attn
+    widths = [cfg.ffn_by_layer[l] if cfg.ffn_by_layer else cfg.ffn for l in range(cfg.n_layers)]
+    layers = [8.0 * H * H + 4.0 * H * F + attn for F in widths]
     head = 2.0 * H * V + (2.0 * H * H if cfg.head else 0.0)
-    useful = 3.0 * T * (cfg.n_layers * layer + head)
-    return useful, float(T) * layer * n_recomputed
+    useful = 3.0 * T * (sum(layers) + head)
+    return useful, float(T) * sum(f for l, f in enumerate(layers) if (plan >> l) & 1)

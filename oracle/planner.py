@@ -20,7 +20,10 @@ paper's order:
     bucket whose largest member is nearest above the excess supplies its
     earliest layer, or, when no single layer covers the excess, the earliest
     layer of the largest bucket is taken;
-  * plan cache (Section 5).
+  * plan cache (Section 5);
+  * optional use of the collected forward times (Section 4.1 has the collector
+    record each layer's forward time and the scheduler work from memory and
+    time; Algorithm 1 itself never reads the time): see "cost-aware" below.
 
 Readings where the paper is silent:
   - the per-layer quantity the algorithm ranks and subtracts is the droppable
@@ -34,7 +37,12 @@ Readings where the paper is silent:
     discussion of the per-encoder peak figure);
   - predictions are rounded to the nearest 256 bytes plus a fixed guard and all
     comparisons are integer;
-  - ties in the descending sort are broken by forward position.
+  - ties in the descending sort are broken by forward position;
+  - cost-aware selection: the bucket is chosen exactly as Algorithm 1 chooses
+    it, by memory; inside that bucket, whose members free about the same
+    amount, the layer taken is the earliest of those whose estimated forward
+    time is within the bucket tolerance (10 %) of the bucket's cheapest
+    remaining layer.  With equal times this is Algorithm 1.
 
 Peak model of one step under plan C (LIFO activation stack):
     kept_l(C) = sum_{j<l, j not in C} a_j + sum_{j<l, j in C} b_j
@@ -50,7 +58,7 @@ from typing import Dict, List, Optional, Sequence, Tuple
 
 import numpy as np
 
-Q_A, Q_B, Q_W, Q_E, Q_G, Q_F = 0, 1, 2, 3, 4, 5
+Q_A, Q_B, Q_W, Q_E, Q_G, Q_F, Q_T = 0, 1, 2, 3, 4, 5, 6
 GRANULE = 256
 
 
@@ -62,6 +70,7 @@ class Components:
     a: List[int]
     b: List[int]
     w: List[int]
+    t: Optional[List[int]] = None      # forward time of each layer (ns, >= 1) when collected
 
     @property
     def n(self) -> int:
@@ -123,8 +132,10 @@ def make_buckets(est: Sequence[int], tol_permille: int = 100) -> List[List[int]]
 
 
 def greedy_select(est: Sequence[int], buckets: List[List[int]], excess: int,
-                  chosen: List[int]) -> int:
-    """Selection loop of Algorithm 1.  Mutates buckets / chosen; returns the new excess."""
+                  chosen: List[int], times: Optional[Sequence[int]] = None,
+                  tol_permille: int = 100) -> int:
+    """Selection loop of Algorithm 1.  Mutates buckets / chosen; returns the new excess.
+    times: cost-aware choice inside the selected bucket."""
     while excess > 0:
         live = [b for b in buckets if b]
         if not live:
@@ -134,7 +145,12 @@ def greedy_select(est: Sequence[int], buckets: List[List[int]], excess: int,
             pick_from = min(cands, key=lambda b: max(est[l] for l in b))
         else:
             pick_from = live[0]
-        l = pick_from.pop(0)
+        if times is None:
+            l = pick_from[0]
+        else:
+            cheapest = min(times[j] for j in pick_from)
+            l = next(j for j in pick_from if 1000 * times[j] <= (1000 + tol_permille) * cheapest)
+        pick_from.remove(l)
         chosen.append(l)
         excess -= est[l]
     return excess
@@ -148,15 +164,17 @@ class PlanResult:
     feasible: bool
 
 
-def plan_from_components(c: Components, budget_eff: int, tol_permille: int = 100) -> PlanResult:
+def plan_from_components(c: Components, budget_eff: int, tol_permille: int = 100,
+                         cost_aware: bool = False) -> PlanResult:
     if budget_eff <= 0:                                 # unlimited
         return PlanResult(0, [], simulate_peak(c, 0), True)
     s = [max(c.a[l] - c.b[l], 0) for l in range(c.n)]
     buckets = make_buckets(s, tol_permille)
     chosen: List[int] = []
     excess = simulate_peak(c, 0) - budget_eff
+    times = c.t if cost_aware else None
     while True:
-        greedy_select(s, buckets, excess, chosen)
+        greedy_select(s, buckets, excess, chosen, times, tol_permille)
         plan = 0
         for l in chosen:
             plan |= 1 << l
@@ -189,7 +207,8 @@ class Planner:
 
     def __init__(self, n_layers: int, budget: int, sheltered_steps: int = 10,
                  tol_permille: int = 100, order: int = 2, quantum: int = 1,
-                 reserve: int = 0, guard: int = 1024):
+                 reserve: int = 0, guard: int = 1024, cost_aware: bool = False):
+        self.cost_aware = cost_aware
         self.n = n_layers
         self.budget = int(budget)
         self.sheltered_steps = sheltered_steps
@@ -212,7 +231,7 @@ class Planner:
         if quantity == Q_F:
             self.fixed = max(self.fixed, int(nbytes))
             return
-        key = (quantity, layer if quantity in (Q_A, Q_B, Q_W) else -1)
+        key = (quantity, layer if quantity in (Q_A, Q_B, Q_W, Q_T) else -1)
         self.samples.setdefault(key, []).append((int(x), int(nbytes)))
 
     def end_sheltered_step(self, x: int) -> None:
@@ -233,11 +252,14 @@ class Planner:
         assert self.models is not None
         def q(kind, layer=-1):
             return to_bytes(eval_poly(self.models[(kind, layer)], x), self.guard)
+        t = None
+        if all((Q_T, l) in self.models for l in range(self.n)):     # times: all layers or none
+            t = [max(int(np.floor(eval_poly(self.models[(Q_T, l)], x) + 0.5)), 1) for l in range(self.n)]
         return Components(
             F=self.fixed, e=q(Q_E), g=q(Q_G),
             a=[q(Q_A, l) for l in range(self.n)],
             b=[q(Q_B, l) for l in range(self.n)],
-            w=[q(Q_W, l) for l in range(self.n)])
+            w=[q(Q_W, l) for l in range(self.n)], t=t)
 
     # scheduler + cache
     def key_of(self, x: int) -> int:
@@ -256,7 +278,7 @@ class Planner:
         self.misses += 1
         comp = self.predict(key)
         eff = self.budget - self.reserve if self.budget > 0 else 0
-        res = plan_from_components(comp, eff, self.tol)
+        res = plan_from_components(comp, eff, self.tol, self.cost_aware)
         self.cache[key] = res
         return res
 

@@ -18,7 +18,7 @@ MIMOSE_ERR_HIP = -4
 MIMOSE_ERR_NOT_READY = -5
 ERR_NAMES = {0: "OK", -1: "INVALID_ARG", -2: "OOM_BUDGET", -3: "BUDGET_INFEASIBLE", -4: "HIP", -5: "NOT_READY"}
 
-Q_LAYER_KEPT, Q_LAYER_BOUNDARY, Q_LAYER_BWD, Q_EMBED, Q_HEAD, Q_FIXED = range(6)
+Q_LAYER_KEPT, Q_LAYER_BOUNDARY, Q_LAYER_BWD, Q_EMBED, Q_HEAD, Q_FIXED, Q_LAYER_TIME = range(7)
 
 
 class mimose_model_cfg(C.Structure):
@@ -27,7 +27,8 @@ class mimose_model_cfg(C.Structure):
                  "dtype", "causal", "pre_ln", "gelu_tanh", "head")] + \
                [("ln_eps", C.c_float)] + \
                [(n, C.c_int32) for n in ("sheltered_steps", "bucket_tol_permille", "poly_order", "size_quantum")] + \
-               [("reserve_bytes", C.c_uint64), ("guard_bytes", C.c_uint64)]
+               [("reserve_bytes", C.c_uint64), ("guard_bytes", C.c_uint64)] + \
+               [("ffn_by_layer", C.c_int32 * 64), ("cost_aware", C.c_int32), ("reserved_", C.c_int32)]
 
 
 class mimose_stats(C.Structure):
@@ -77,6 +78,7 @@ SIGNATURES = {
     "mimose_planner_query": (C.c_int, [_vp, _i32, _i32, C.POINTER(_u64), C.POINTER(_u64)]),
     "mimose_profile_enable": (C.c_int, [_vp, _i32]),
     "mimose_profile_read": (C.c_int, [_vp, _i32, C.POINTER(_u64), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "mimose_get_layer_times": (C.c_int, [_vp, _vp]),
     "mimose_get_step_memory": (C.c_int, [_vp, C.POINTER(_u64), C.POINTER(_u64), C.POINTER(_u64), _vp, _vp, _vp]),
     "mimose_get_stats": (C.c_int, [_vp, C.POINTER(mimose_stats)]),
     "mimose_last_error": (C.c_char_p, [_vp]),
@@ -137,6 +139,8 @@ def make_cfg(shape: dict, **planner) -> mimose_model_cfg:
     dt = shape.get("dtype", 0)
     c.dtype = {"fp32": 0, "bf16": 1}.get(dt, dt)
     c.ln_eps = float(shape.get("ln_eps", 1e-5))
+    for l, w in enumerate(shape.get("ffn_by_layer", ()) or ()):
+        c.ffn_by_layer[l] = int(w)
     for k, v in planner.items():
         setattr(c, k, v)
     return c
@@ -268,6 +272,12 @@ def mimose_get_step_memory(ctx, n_layers: int) -> dict:
                                                  b.ctypes.data, w.ctypes.data), ctx)
     return dict(F=F.value, e=e.value, g=g.value, a=[int(v) for v in a], b=[int(v) for v in b],
                 w=[int(v) for v in w])
+
+
+def mimose_get_layer_times(ctx, n_layers: int) -> list:
+    t = np.zeros(n_layers, dtype=np.uint64)
+    _check(load_library().mimose_get_layer_times(ctx, t.ctypes.data), ctx)
+    return [int(v) for v in t]
 
 
 def mimose_get_stats(ctx) -> dict:
@@ -413,6 +423,9 @@ class Mimose:
 
     def step_memory(self) -> dict:
         return mimose_get_step_memory(self.ctx, self.cfg.n_layers)
+
+    def layer_times(self) -> list:
+        return mimose_get_layer_times(self.ctx, self.cfg.n_layers)
 
     def close(self):
         if self.ctx is not None:

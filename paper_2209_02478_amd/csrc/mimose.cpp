@@ -92,6 +92,7 @@ struct mimose_ctx {
   // needs the same incoming gradient (fork / join with events; default priority)
   hipStream_t side = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  std::vector<hipEvent_t> ev_layer;   // begin / end of each layer's forward in a collecting step
   Arena arena;
   uint64_t fixed_top = 0;
   std::vector<Param> params;
@@ -120,7 +121,7 @@ struct mimose_ctx {
   std::vector<int32_t> sort_count;       // reused scratch of the per-step counting sort
   // memory components measured in the last completed step
   uint64_t last_e = 0, last_g = 0;
-  std::vector<uint64_t> last_a, last_b, last_w;
+  std::vector<uint64_t> last_a, last_b, last_w, last_t;
   // optional per-kernel-class timing with events on the work stream
   bool prof_on = false;
   struct ProfPending { int cls; double work; hipEvent_t a, b; };
@@ -165,14 +166,18 @@ int add_param(mimose_ctx* c, const std::string& name, std::initializer_list<int6
   return (int)c->params.size() - 1;
 }
 
+// width of layer l's feed-forward block
+inline int ffn_of(const mimose_model_cfg& f, int l) { return f.ffn_by_layer[l] > 0 ? f.ffn_by_layer[l] : f.ffn; }
+
 void build_params(mimose_ctx* c) {
   const auto& f = c->cfg;
-  const int64_t H = f.hidden, F = f.ffn, V = f.vocab;
+  const int64_t H = f.hidden, V = f.vocab;
   c->i_tok = add_param(c, "tok_emb", {V, H});
   c->i_pos = add_param(c, "pos_emb", {f.max_seq, H});
   if (!f.pre_ln) { c->i_eg = add_param(c, "emb_ln_g", {H}); c->i_eb = add_param(c, "emb_ln_b", {H}); }
   for (int l = 0; l < f.n_layers; ++l) {
     const std::string p = "layer" + std::to_string(l) + ".";
+    const int64_t F = ffn_of(f, l);
     LayerIdx x;
     x.wqkv = add_param(c, p + "wqkv", {3 * H, H}); x.bqkv = add_param(c, p + "bqkv", {3 * H});
     x.wo = add_param(c, p + "wo", {H, H});         x.bo = add_param(c, p + "bo", {H});
@@ -363,8 +368,7 @@ void Step::embed_stage(const int32_t* tokens, const int32_t* labels) {
 }
 
 void Step::alloc_layer(int l, LayerActs& A) {
-  (void)l;
-  const int64_t TH = (int64_t)T_ * f_.hidden, TF = (int64_t)T_ * f_.ffn;
+  const int64_t TH = (int64_t)T_ * f_.hidden, TF = (int64_t)T_ * ffn_of(f_, l);
   if (!A.has_out) {                   // first pass: the boundary tensor goes first
     A.mark = c_->arena.top();
     A.out = talloc(TH);
@@ -384,7 +388,7 @@ void Step::alloc_layer(int l, LayerActs& A) {
 
 void Step::layer_forward(int l, LayerActs& A) {
   const LayerIdx& p = c_->lidx[l];
-  const int H = f_.hidden, F = f_.ffn, nh = f_.n_heads, d = H / nh;
+  const int H = f_.hidden, F = ffn_of(f_, l), nh = f_.n_heads, d = H / nh;
   const int gelu = f_.gelu_tanh ? mk::GELU_TANH : mk::GELU_ERF;
   const void* a = A.x;
   if (f_.pre_ln) { ln_fwd(A.x, p.ln1g, p.ln1b, A.n1); a = A.n1; }
@@ -409,7 +413,7 @@ void Step::layer_forward(int l, LayerActs& A) {
 // Gradient of the layer output arrives in gA_; the gradient of its input leaves in gA_.
 void Step::layer_backward(int l, LayerActs& A) {
   const LayerIdx& p = c_->lidx[l];
-  const int H = f_.hidden, F = f_.ffn, nh = f_.n_heads, d = H / nh;
+  const int H = f_.hidden, F = ffn_of(f_, l), nh = f_.n_heads, d = H / nh;
   const int64_t TH = (int64_t)T_ * H, TF = (int64_t)T_ * F;
   Arena& ar = c_->arena;
   reserve_workspace({{H, F}, {F, H}, {H, H}, {3 * H, H}});
@@ -562,7 +566,10 @@ void Step::run(const int32_t* tokens, const int32_t* labels, float* loss_out) {
     LayerActs& A = c_->acts[l];
     A.x = x;
     alloc_layer(l, A);
+    const bool timed = collect_ && !dry_ && (int)c_->ev_layer.size() == 2 * N;
+    if (timed) HIPCHK(c_, hipEventRecord(c_->ev_layer[2 * l], st_));
     layer_forward(l, A);
+    if (timed) HIPCHK(c_, hipEventRecord(c_->ev_layer[2 * l + 1], st_));
     a_bytes[l] = ar.top() - A.mark;
     b_bytes[l] = A.after_out - A.mark;
     if ((plan_ >> l) & 1) { ar.pop_to(A.after_out); A.dropped = true; }
@@ -607,13 +614,18 @@ void Step::run(const int32_t* tokens, const int32_t* labels, float* loss_out) {
   }
 }
 
-void flops(const mimose_model_cfg& f, int B, int L, int n_re, double* useful, double* re) {
-  const double T = (double)B * L, H = f.hidden, F = f.ffn, V = f.vocab;
+void flops(const mimose_model_cfg& f, int B, int L, uint64_t plan, double* useful, double* re) {
+  const double T = (double)B * L, H = f.hidden, V = f.vocab;
   const double attn = 4.0 * L * H * (f.causal ? 0.5 : 1.0);
-  const double layer = 8.0 * H * H + 4.0 * H * F + attn;
   const double head = 2.0 * H * V + (f.head ? 2.0 * H * H : 0.0);
-  *useful = 3.0 * T * (f.n_layers * layer + head);
-  *re = T * layer * n_re;
+  double layers = 0.0;
+  *re = 0.0;
+  for (int l = 0; l < f.n_layers; ++l) {
+    const double layer = 8.0 * H * H + 4.0 * H * ffn_of(f, l) + attn;
+    layers += layer;
+    if ((plan >> l) & 1) *re += T * layer;
+  }
+  *useful = 3.0 * T * (layers + head);
 }
 
 int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, const int32_t* lengths, int32_t B, int32_t L,
@@ -700,13 +712,21 @@ int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, const i
     pl.feed(x, MIMOSE_Q_EMBED, -1, s.e_bytes);
     pl.feed(x, MIMOSE_Q_HEAD, -1, s.g_bytes);
     pl.feed(x, MIMOSE_Q_FIXED, -1, c->fixed_top);
+    if (!dry && (int)c->ev_layer.size() == 2 * f.n_layers)      // forward time of each layer, Section 4.1
+      for (int l = 0; l < f.n_layers; ++l) {
+        float ms = 0.f;
+        c->last_t.resize(f.n_layers, 0);
+        if (hipEventElapsedTime(&ms, c->ev_layer[2 * l], c->ev_layer[2 * l + 1]) == hipSuccess)
+          c->last_t[l] = (uint64_t)std::llround((double)ms * 1e6);
+        pl.feed(x, MIMOSE_Q_LAYER_TIME, l, c->last_t[l]);
+      }
     pl.end_step(x);
   }
   // ---- bookkeeping
   auto& S = c->stats;
   const int n_re = __builtin_popcountll(plan);
   double uf, rf;
-  flops(f, B, L, n_re, &uf, &rf);
+  flops(f, B, L, plan, &uf, &rf);
   S.steps++;
   S.sheltered_steps = c->planner->sheltered_steps_seen();
   S.cache_hits = c->planner->hits; S.cache_misses = c->planner->misses;
@@ -741,6 +761,9 @@ int mimose_init(const mimose_model_cfg* cfg, uint64_t mem_budget_bytes, void* ar
   if (f.hidden > mk::kMaxRowWidth) return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "hidden larger than 1024 is not supported");
   if (f.dtype != 0 && f.dtype != 1) return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "dtype must be 0 (fp32) or 1 (bf16)");
   if (f.dtype == 1 && (f.hidden % 8 || f.ffn % 8)) return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "bf16 needs hidden and ffn multiples of 8");
+  for (int l = 0; l < f.n_layers; ++l)
+    if (f.ffn_by_layer[l] < 0 || (f.dtype == 1 && f.ffn_by_layer[l] % 8))
+      return fail(nullptr, MIMOSE_ERR_INVALID_ARG, "ffn_by_layer: entries must be >= 0 (multiples of 8 for bf16)");
   if (f.ln_eps <= 0.f) f.ln_eps = 1e-5f;
   if (f.sheltered_steps <= 0) f.sheltered_steps = 10;
   if (f.bucket_tol_permille <= 0) f.bucket_tol_permille = 100;
@@ -770,8 +793,12 @@ int mimose_init(const mimose_model_cfg* cfg, uint64_t mem_budget_bytes, void* ar
   c->stats.fixed_bytes = c->fixed_top;
   c->stats.budget_bytes = mem_budget_bytes;
   c->planner.reset(new mimose::Planner(f.n_layers, mem_budget_bytes, f.sheltered_steps, f.bucket_tol_permille,
-                                       f.poly_order, f.size_quantum, f.reserve_bytes, f.guard_bytes));
+                                       f.poly_order, f.size_quantum, f.reserve_bytes, f.guard_bytes,
+                                       f.cost_aware != 0));
   if (c->has_device) {
+    c->ev_layer.resize(2 * (size_t)f.n_layers, nullptr);
+    for (auto& e : c->ev_layer)
+      if (hipEventCreate(&e) != hipSuccess) return fail(nullptr, MIMOSE_ERR_HIP, "hipEventCreate failed");
     if (hipHostMalloc((void**)&c->loss_host, 256, hipHostMallocDefault) != hipSuccess)
       return fail(nullptr, MIMOSE_ERR_HIP, "hipHostMalloc failed");
     if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess ||
@@ -953,8 +980,9 @@ int mimose_set_plan_mode(mimose_ctx* c, int32_t mode) {
 }
 
 int mimose_planner_feed(mimose_ctx* c, int32_t B, int32_t L, int32_t quantity, int32_t layer, uint64_t bytes) {
-  if (!c || B < 1 || L < 1 || quantity < 0 || quantity > 5) return fail(c, MIMOSE_ERR_INVALID_ARG, "bad sample");
-  if (quantity <= 2 && (layer < 0 || layer >= c->cfg.n_layers)) return fail(c, MIMOSE_ERR_INVALID_ARG, "layer out of range");
+  if (!c || B < 1 || L < 1 || quantity < 0 || quantity > MIMOSE_Q_LAYER_TIME) return fail(c, MIMOSE_ERR_INVALID_ARG, "bad sample");
+  if ((quantity <= 2 || quantity == MIMOSE_Q_LAYER_TIME) && (layer < 0 || layer >= c->cfg.n_layers))
+    return fail(c, MIMOSE_ERR_INVALID_ARG, "layer out of range");
   c->planner->feed((int64_t)B * L, quantity, layer, bytes);
   return MIMOSE_OK;
 }
@@ -1007,6 +1035,13 @@ int mimose_get_step_memory(mimose_ctx* c, uint64_t* fixed, uint64_t* embed, uint
   return MIMOSE_OK;
 }
 
+int mimose_get_layer_times(mimose_ctx* c, uint64_t* ns) {
+  if (!c || !ns) return MIMOSE_ERR_INVALID_ARG;
+  if (c->last_t.size() != (size_t)c->cfg.n_layers) return fail(c, MIMOSE_ERR_NOT_READY, "no collecting step has completed yet");
+  for (int l = 0; l < c->cfg.n_layers; ++l) ns[l] = c->last_t[l];
+  return MIMOSE_OK;
+}
+
 int mimose_get_stats(mimose_ctx* c, mimose_stats* out) {
   if (!c || !out) return MIMOSE_ERR_INVALID_ARG;
   c->stats.cache_hits = c->planner->hits;
@@ -1024,6 +1059,7 @@ void mimose_destroy(mimose_ctx* c) {
     (void)hipStreamSynchronize(c->stream);
     if (c->side) (void)hipStreamSynchronize(c->side);
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->ev_layer) if (e) (void)hipEventDestroy(e);
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
     if (c->side) (void)hipStreamDestroy(c->side);

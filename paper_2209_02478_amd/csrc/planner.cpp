@@ -19,15 +19,25 @@ int64_t simulate_peak(const Components& c, uint64_t plan) {
 namespace {
 
 struct Bucket {
-  std::vector<int> layers;      // forward order
-  size_t next = 0;              // layers[next..] are still available
-  bool empty() const { return next >= layers.size(); }
+  std::vector<int> layers;      // forward order; a layer leaves when it is chosen
+  bool empty() const { return layers.empty(); }
 };
 
 int64_t bucket_max(const Bucket& b, const std::vector<int64_t>& s) {
   int64_t m = -1;
-  for (size_t i = b.next; i < b.layers.size(); ++i) m = std::max(m, s[b.layers[i]]);
+  for (int l : b.layers) m = std::max(m, s[l]);
   return m;
+}
+
+// index into b.layers of the layer to take: the earliest, or with times the earliest among those
+// within the tolerance of the cheapest
+size_t take_from(const Bucket& b, const std::vector<int64_t>* t, int tol_permille) {
+  if (!t) return 0;
+  int64_t tmin = (*t)[b.layers[0]];
+  for (int l : b.layers) tmin = std::min(tmin, (*t)[l]);
+  for (size_t i = 0; i < b.layers.size(); ++i)
+    if (1000 * (*t)[b.layers[i]] <= (int64_t)(1000 + tol_permille) * tmin) return i;
+  return 0;
 }
 
 std::vector<Bucket> build_buckets(const std::vector<int64_t>& s, int tol_permille) {
@@ -50,7 +60,7 @@ std::vector<Bucket> build_buckets(const std::vector<int64_t>& s, int tol_permill
 
 // selection loop of Algorithm 1
 void select(const std::vector<int64_t>& s, std::vector<Bucket>& buckets, int64_t excess, uint64_t* plan,
-            int* n_chosen) {
+            int* n_chosen, const std::vector<int64_t>* t, int tol_permille) {
   while (excess > 0) {
     Bucket* first_live = nullptr;
     Bucket* best = nullptr;
@@ -63,7 +73,9 @@ void select(const std::vector<int64_t>& s, std::vector<Bucket>& buckets, int64_t
     }
     if (!first_live) return;
     Bucket* from = best ? best : first_live;
-    const int l = from->layers[from->next++];
+    const size_t i = take_from(*from, t, tol_permille);
+    const int l = from->layers[i];
+    from->layers.erase(from->layers.begin() + (ptrdiff_t)i);
     *plan |= (uint64_t)1 << l;
     ++*n_chosen;
     excess -= s[l];
@@ -72,7 +84,7 @@ void select(const std::vector<int64_t>& s, std::vector<Bucket>& buckets, int64_t
 
 }  // namespace
 
-PlanOut schedule(const Components& c, int64_t budget_eff, int tol_permille) {
+PlanOut schedule(const Components& c, int64_t budget_eff, int tol_permille, bool cost_aware) {
   PlanOut out;
   const int n = (int)c.a.size();
   if (budget_eff <= 0) {
@@ -84,8 +96,9 @@ PlanOut schedule(const Components& c, int64_t budget_eff, int tol_permille) {
   std::vector<Bucket> buckets = build_buckets(s, tol_permille);
   int chosen = 0;
   int64_t excess = simulate_peak(c, 0) - budget_eff;
+  const std::vector<int64_t>* t = cost_aware && (int)c.t.size() == n ? &c.t : nullptr;
   for (;;) {
-    select(s, buckets, excess, &out.plan, &chosen);
+    select(s, buckets, excess, &out.plan, &chosen, t, tol_permille);
     out.predicted_peak = simulate_peak(c, out.plan);
     if (out.predicted_peak <= budget_eff) { out.feasible = true; return out; }
     if (chosen == n) { out.feasible = false; return out; }
@@ -154,13 +167,13 @@ double PolyFit::eval(double x) const {
 }
 
 Planner::Planner(int n_layers, uint64_t budget, int sheltered_steps, int tol_permille, int order, int quantum,
-                 uint64_t reserve, uint64_t guard)
-    : n_(n_layers), budget_((int64_t)budget), sheltered_steps_(sheltered_steps), tol_(tol_permille),
+                 uint64_t reserve, uint64_t guard, bool cost_aware)
+    : cost_aware_(cost_aware), n_(n_layers), budget_((int64_t)budget), sheltered_steps_(sheltered_steps), tol_(tol_permille),
       order_(order), quantum_(quantum < 1 ? 1 : quantum), reserve_((int64_t)reserve), guard_((int64_t)guard) {}
 
 void Planner::feed(int64_t x, int quantity, int layer, uint64_t bytes) {
   if (quantity == 5) { fixed_ = std::max(fixed_, (int64_t)bytes); return; }
-  const int key_layer = quantity <= 2 ? layer : -1;
+  const int key_layer = (quantity <= 2 || quantity == 6) ? layer : -1;
   series_[{quantity, key_layer}].add((double)x, (double)bytes);
   fitted_ = false;
 }
@@ -181,8 +194,16 @@ bool Planner::fit_all() {
     for (int q = 0; q < 3; ++q)
       if (!series_.count({q, l})) return false;
   if (!series_.count({3, -1}) || !series_.count({4, -1})) return false;
-  for (auto& kv : series_)
-    if (!kv.second.fit(order_)) return false;
+  have_times_ = true;                       // forward times are optional: all layers or none
+  for (int l = 0; l < n_; ++l)
+    if (!series_.count({6, l})) have_times_ = false;
+  for (auto& kv : series_) {
+    if (kv.first.first == 6 && !have_times_) continue;
+    if (!kv.second.fit(order_)) {
+      if (kv.first.first != 6) return false;
+      have_times_ = false;
+    }
+  }
   fitted_ = true;
   cache_.clear();
   return true;
@@ -204,6 +225,11 @@ Components Planner::predict(int64_t x) {
     c.b[l] = to_bytes(series_[{1, l}].eval((double)x), guard_);
     c.w[l] = to_bytes(series_[{2, l}].eval((double)x), guard_);
   }
+  if (have_times_) {
+    c.t.resize(n_);
+    for (int l = 0; l < n_; ++l)
+      c.t[l] = std::max<int64_t>((int64_t)std::floor(series_[{6, l}].eval((double)x) + 0.5), 1);
+  }
   return c;
 }
 
@@ -221,7 +247,7 @@ int Planner::query(int64_t x, PlanOut* out, bool* hit) {
   if (hit) *hit = false;
   const Components c = predict(key);
   const int64_t eff = budget_ > 0 ? budget_ - reserve_ : 0;
-  *out = schedule(c, eff, tol_);
+  *out = schedule(c, eff, tol_, cost_aware_);
   cache_[key] = *out;
   return out->feasible ? 0 : -2;
 }

@@ -13,6 +13,7 @@ namespace mimose {
 struct Components {          // predicted or measured bytes of one step at one input size
   int64_t F = 0, e = 0, g = 0;
   std::vector<int64_t> a, b, w;
+  std::vector<int64_t> t;    // forward time of each layer in ns (>= 1); empty when not collected
 };
 
 // Peak of a step under `plan` (bit l = layer l dropped) with a LIFO activation stack.
@@ -26,7 +27,11 @@ struct PlanOut {
 
 // Algorithm 1 on the droppable bytes a_l - b_l, continued while the simulated peak of the
 // chosen set still exceeds the budget.  budget_eff <= 0 means unlimited.
-PlanOut schedule(const Components& c, int64_t budget_eff, int tol_permille);
+// cost_aware (and c.t given): the bucket is chosen as Algorithm 1 does, by memory; inside it the
+// layer taken is not simply the earliest but the earliest among those whose forward time is
+// within the bucket tolerance of the bucket's cheapest remaining layer (Section 4.1: the
+// scheduler works from the estimated memory and the computation time).
+PlanOut schedule(const Components& c, int64_t budget_eff, int tol_permille, bool cost_aware = false);
 
 // Least-squares polynomial through (x, y) samples; x is scaled by 1/max(x) and the system is
 // solved by Householder QR.
@@ -45,7 +50,7 @@ class PolyFit {
 class Planner {
  public:
   Planner(int n_layers, uint64_t budget, int sheltered_steps, int tol_permille, int order,
-          int quantum, uint64_t reserve, uint64_t guard);
+          int quantum, uint64_t reserve, uint64_t guard, bool cost_aware = false);
   void feed(int64_t x, int quantity, int layer, uint64_t bytes);
   void end_step(int64_t x);
   bool sheltered() const;
@@ -58,6 +63,7 @@ class Planner {
   uint64_t sheltered_steps_seen() const { return steps_seen_; }
  private:
   bool fit_all();
+  bool cost_aware_ = false, have_times_ = false;
   int n_;
   int64_t budget_;
   int sheltered_steps_, tol_, order_, quantum_;

@@ -38,6 +38,10 @@ class ModelShape:
     gelu_tanh: int = 0         # 1: tanh approximation of GELU
     head: int = 1              # 1: MLM head (dense+GELU+LN, tied decoder + bias); 0: tied LM head only
     ln_eps: float = 1e-5
+    ffn_by_layer: Tuple[int, ...] = ()   # stacks whose layers differ: feed-forward width per layer (empty: ffn)
+
+    def ffn_of(self, l: int) -> int:
+        return self.ffn_by_layer[l] if self.ffn_by_layer else self.ffn
 
 
 @dataclass(frozen=True)
@@ -68,6 +72,16 @@ WORKLOADS: Dict[str, Workload] = {
     "bert_large_stress": Workload(
         "bert_large_stress", ModelShape(24, 1024, 16, 4096, 30522, 512, "bf16"),
         256, ("bimodal", 32, 96, 384, 512, 8), 500, 0.30, MASTER_SEED + 4),
+    # stacks whose layers differ (the stages of Section 4.4): three stages with feed-forward
+    # widths stepping down, so that the layers fall into three buckets of Algorithm 1; the mean
+    # width, and with it the work per token, is that of bert_base
+    "tiny_stages": Workload(
+        "tiny_stages", ModelShape(4, 64, 2, 256, 1000, 64, "fp32", ffn_by_layer=(512, 512, 128, 128)),
+        4, ("uniform_int", 16, 64, 1), 24, 0.70, MASTER_SEED + 5),
+    "bert_stages": Workload(
+        "bert_stages", ModelShape(12, 768, 12, 3072, 30522, 512, "bf16",
+                                  ffn_by_layer=(4096,) * 4 + (3072,) * 4 + (2048,) * 4),
+        32, ("lognormal", 200.0, 0.5, 64, 512, 8), 200, 0.60, MASTER_SEED + 6),
 }
 
 
@@ -81,7 +95,7 @@ def param_shapes(s: ModelShape) -> List[Tuple[str, Tuple[int, ...], str]]:
     Linear weights are stored [out_features, in_features]; the fused QKV weight
     stacks the query, key and value projections along the output axis.
     """
-    H, F, V = s.hidden, s.ffn, s.vocab
+    H, V = s.hidden, s.vocab
     out: List[Tuple[str, Tuple[int, ...], str]] = [
         ("tok_emb", (V, H), "normal"),
         ("pos_emb", (s.max_seq, H), "normal"),
@@ -90,6 +104,7 @@ def param_shapes(s: ModelShape) -> List[Tuple[str, Tuple[int, ...], str]]:
         out += [("emb_ln_g", (H,), "ones"), ("emb_ln_b", (H,), "zeros")]
     for l in range(s.n_layers):
         p = f"layer{l}."
+        F = s.ffn_of(l)
         out += [
             (p + "wqkv", (3 * H, H), "normal"), (p + "bqkv", (3 * H,), "zeros"),
             (p + "wo", (H, H), "normal"), (p + "bo", (H,), "zeros"),

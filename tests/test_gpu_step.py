@@ -40,6 +40,9 @@ SMALL = {
     "fp32_preln_head": synthdata.ModelShape(2, 128, 2, 256, 200, 40, "fp32", pre_ln=1, head=1),
     "bf16_postln": synthdata.ModelShape(3, 128, 2, 512, 1000, 96, "bf16"),
     "bf16_preln_causal": synthdata.ModelShape(2, 256, 4, 512, 777, 80, "bf16", causal=1, pre_ln=1, gelu_tanh=1, head=0),
+    # layers of different feed-forward widths
+    "fp32_stages": synthdata.ModelShape(3, 64, 2, 256, 500, 48, "fp32", ffn_by_layer=(320, 100, 36)),
+    "bf16_stages": synthdata.ModelShape(3, 128, 2, 512, 1000, 96, "bf16", pre_ln=1, ffn_by_layer=(768, 264, 128)),
 }
 
 
@@ -59,7 +62,7 @@ def test_step_parity_small_models(name, B, L):
     m.close()
 
 
-@pytest.mark.parametrize("name", ["fp32_postln", "bf16_postln", "bf16_preln_causal"])
+@pytest.mark.parametrize("name", ["fp32_postln", "bf16_postln", "bf16_preln_causal", "fp32_stages", "bf16_stages"])
 def test_checkpointed_gradients_bit_identical(name):
     shape = SMALL[name]
     n = shape.n_layers
@@ -83,10 +86,12 @@ def test_checkpointed_gradients_bit_identical(name):
     m.close()
 
 
-def test_tiny_workload_every_step():
-    """The small fp32 configuration end to end: sheltered then responsive steps under the
-    budget, every step checked against the oracle and the oracle planner."""
-    wl = synthdata.WORKLOADS["tiny"]
+@pytest.mark.parametrize("name,cost_aware", [("tiny", 0), ("tiny_stages", 0), ("tiny_stages", 1)])
+def test_tiny_workload_every_step(name, cost_aware):
+    """The small fp32 configurations end to end: sheltered then responsive steps under the
+    budget, every step checked against the oracle and the oracle planner (with the measured
+    forward times of the sheltered steps when the selection is cost-aware)."""
+    wl = synthdata.WORKLOADS[name]
     shape, B, n = wl.shape, wl.batch, wl.shape.n_layers
     d = synthdata.shape_dict(shape)
     cal = mi.Mimose(d, 0, device=None)
@@ -95,9 +100,9 @@ def test_tiny_workload_every_step():
     cal.close()
     budget = int(wl.budget_frac * peak0)
     params = synthdata.make_params(shape, wl.seed)
-    m = mi.Mimose(d, budget)
+    m = mi.Mimose(d, budget, cost_aware=cost_aware)
     m.load_params(params)
-    ref = op.Planner(n, budget, guard=4096)
+    ref = op.Planner(n, budget, guard=4096, cost_aware=bool(cost_aware))
     lens = synthdata.seq_lengths(wl.length_recipe, wl.steps, wl.seed)
     plans = []
     for i, L in enumerate(lens):
@@ -114,6 +119,10 @@ def test_tiny_workload_every_step():
             for l in range(n):
                 ref.feed(x, op.Q_A, l, c.a[l]); ref.feed(x, op.Q_B, l, c.b[l]); ref.feed(x, op.Q_W, l, c.w[l])
             ref.feed(x, op.Q_E, -1, c.e); ref.feed(x, op.Q_G, -1, c.g); ref.feed(x, op.Q_F, -1, c.F)
+            times = m.layer_times()
+            assert all(t > 0 for t in times)
+            for l in range(n):
+                ref.feed(x, op.Q_T, l, times[l])
             ref.end_sheltered_step(x)
         else:
             assert plan == ref.query(x).plan

@@ -78,8 +78,9 @@ def random_tables(rng, n, steps, B):
     return lens, co, poly
 
 
+@pytest.mark.parametrize("cost_aware", [0, 1])
 @pytest.mark.parametrize("seed", range(6))
-def test_planner_matches_oracle_on_same_samples(seed):
+def test_planner_matches_oracle_on_same_samples(seed, cost_aware):
     rng = np.random.default_rng(seed)
     n = int(rng.integers(2, 25))
     B = int(rng.integers(1, 33))
@@ -98,7 +99,8 @@ def test_planner_matches_oracle_on_same_samples(seed):
     quantum = int(rng.choice([1, 1, 64]))
     m = mi.Mimose(shape, 0, device=None)                      # context only carries the planner here
     m.close()
-    cfg = mi.make_cfg(shape, size_quantum=quantum, guard_bytes=512)
+    cfg = mi.make_cfg(shape, size_quantum=quantum, guard_bytes=512, cost_aware=cost_aware)
+    ns = [(int(rng.integers(0, 5000)), int(rng.choice([40, 41, 80, 200]))) for _ in range(n)]   # forward time: c0 + c1 x
     ctx = mi.mimose_init(cfg, budget + 10 ** 9, None, 0, None)
     mi.mimose_destroy(ctx)
     # the library planner under test: budget is the context's budget
@@ -106,7 +108,7 @@ def test_planner_matches_oracle_on_same_samples(seed):
         ctx = mi.mimose_init(cfg, budget, None, 0, None)
     except mi.MimoseError:
         pytest.skip("fixed bytes of this random model exceed the random budget")
-    ref = op.Planner(n, budget, quantum=quantum, guard=512)
+    ref = op.Planner(n, budget, quantum=quantum, guard=512, cost_aware=bool(cost_aware))
     for L in lens[:12]:
         x = B * L
         c = comp(x)
@@ -114,6 +116,9 @@ def test_planner_matches_oracle_on_same_samples(seed):
             for q, v in ((op.Q_A, c.a[l]), (op.Q_B, c.b[l]), (op.Q_W, c.w[l])):
                 mi.mimose_planner_feed(ctx, B, L, q, l, v)
                 ref.feed(x, q, l, v)
+            if cost_aware:
+                mi.mimose_planner_feed(ctx, B, L, mi.Q_LAYER_TIME, l, ns[l][0] + ns[l][1] * x)
+                ref.feed(x, op.Q_T, l, ns[l][0] + ns[l][1] * x)
         for q, v in ((op.Q_E, c.e), (op.Q_G, c.g), (op.Q_F, fixed)):
             mi.mimose_planner_feed(ctx, B, L, q, -1, v)
             ref.feed(x, q, -1, v)
@@ -152,7 +157,8 @@ def components_of(m):
     return op.Components(F=d["F"], e=d["e"], g=d["g"], a=d["a"], b=d["b"], w=d["w"])
 
 
-@pytest.mark.parametrize("name,B,L", [("tiny", 4, 64), ("tiny", 4, 17), ("bert_base", 32, 200), ("gpt2_medium", 16, 333)])
+@pytest.mark.parametrize("name,B,L", [("tiny", 4, 64), ("tiny", 4, 17), ("bert_base", 32, 200), ("gpt2_medium", 16, 333),
+                                      ("tiny_stages", 4, 40), ("bert_stages", 32, 200)])
 def test_measured_peak_equals_simulated_peak_for_every_plan(name, B, L):
     wl, m = host_ctx(name)
     n = wl.shape.n_layers
@@ -196,7 +202,8 @@ def budget_for(name):
     return wl, int(wl.budget_frac * peak), peak, floor
 
 
-@pytest.mark.parametrize("name", ["tiny", "bert_base", "bert_large", "gpt2_medium", "bert_large_stress"])
+@pytest.mark.parametrize("name", ["tiny", "bert_base", "bert_large", "gpt2_medium", "bert_large_stress",
+                                  "tiny_stages", "bert_stages"])
 def test_whole_workload_stays_under_budget_and_matches_oracle_planner(name):
     wl, budget, peak0, floor = budget_for(name)
     assert floor <= budget < peak0, "the configured budget must bind and be feasible"
@@ -229,11 +236,72 @@ def test_whole_workload_stays_under_budget_and_matches_oracle_planner(name):
     st = m.stats()
     assert st["cache_hits"] == ref.hits and st["cache_misses"] == ref.misses
     assert st["steps"] == steps
+    if wl.shape.ffn_by_layer:                                 # stages of different widths: several buckets at work
+        c = ref.predict(wl.batch * wl.shape.max_seq)
+        assert len(op.make_buckets([a - b for a, b in zip(c.a, c.b)])) == len(set(wl.shape.ffn_by_layer))
     # the longest batch needs recomputation, short ones do not
     m2_plan = m.dry_step(wl.batch, wl.shape.max_seq)[1]
     assert m2_plan != 0
     assert m.dry_step(wl.batch, min(lens))[1] in n_plans | {0}
     m.close()
+
+
+def test_stages_of_different_widths_change_parameters_memory_and_flops():
+    wl, m = host_ctx("tiny_stages")
+    want = [(n, s) for n, s, _ in synthdata.param_shapes(wl.shape)]
+    assert [(n, m.shapes[n]) for n in m.names] == want
+    assert m.shapes["layer0.w1"] == (512, 64) and m.shapes["layer3.w2"] == (64, 128)
+    m.force_plan(0b0101)
+    m.dry_step(4, 32)
+    c = components_of(m)
+    es = 4
+    assert c.a[0] == c.a[1] > c.a[2] == c.a[3]
+    assert c.a[0] - c.a[2] == 2 * 4 * 32 * (512 - 128) * es   # pre-activation and activation of the wider block
+    from oracle import model as om
+    useful, re = om.flops_per_step(om.Cfg.from_shape(synthdata.shape_dict(wl.shape)), 4, 32, plan=0b0101)
+    st = m.stats()
+    assert st["useful_flops_last"] == useful and st["recompute_flops_last"] == re
+    m.close()
+    with pytest.raises(mi.MimoseError):
+        mi.Mimose({**synthdata.shape_dict(wl.shape), "ffn_by_layer": (512, -1, 128, 128)}, 0, device=None)
+
+
+def test_cost_aware_planner_matches_oracle_and_prefers_cheap_layers():
+    """Forward times fed next to the memory samples of dry sheltered steps (a host-only context
+    collects none itself): the cost-aware library planner must agree with the cost-aware oracle
+    on every responsive step, and differ from Algorithm 1 where the first layer of a bucket is
+    the expensive one."""
+    wl, budget, peak0, floor = budget_for("tiny_stages")
+    n = wl.shape.n_layers
+    m = mi.Mimose(synthdata.shape_dict(wl.shape), budget, device=None, cost_aware=1)
+    plain = mi.Mimose(synthdata.shape_dict(wl.shape), budget, device=None)
+    ref = op.Planner(n, budget, guard=4096, cost_aware=True)
+    ns_per_token = [900, 500, 400, 200]                       # layer 0 costs far more than its bucket mate
+    lens = synthdata.seq_lengths(wl.length_recipe, 60, wl.seed)
+    differs = 0
+    for i, L in enumerate(lens):
+        x = wl.batch * L
+        if ref.sheltered():
+            for l in range(n):
+                t = 1000 + ns_per_token[l] * x
+                mi.mimose_planner_feed(m.ctx, wl.batch, L, mi.Q_LAYER_TIME, l, t)
+                ref.feed(x, op.Q_T, l, t)
+            peak, plan = m.dry_step(wl.batch, L)
+            plain.dry_step(wl.batch, L)
+            c = components_of(m)
+            for l in range(n):
+                ref.feed(x, op.Q_A, l, c.a[l]); ref.feed(x, op.Q_B, l, c.b[l]); ref.feed(x, op.Q_W, l, c.w[l])
+            ref.feed(x, op.Q_E, -1, c.e); ref.feed(x, op.Q_G, -1, c.g); ref.feed(x, op.Q_F, -1, c.F)
+            ref.end_sheltered_step(x)
+            continue
+        peak, plan = m.dry_step(wl.batch, L)
+        want = ref.query(x)
+        assert plan == want.plan and peak <= budget, (i, L, bin(plan), bin(want.plan))
+        _, plan0 = plain.dry_step(wl.batch, L)
+        if plan & 0b11 == 0b10 and plan0 & 0b11 == 0b01:                 # layer 1 in place of layer 0
+            differs += 1
+    assert differs > 0
+    m.close(); plain.close()
 
 
 def test_budget_below_all_checkpointed_floor_is_an_error_and_context_survives():

@@ -78,6 +78,73 @@ def test_algorithm1_hand_traces(est, excess, want):
     assert chosen == want
 
 
+# ---------------------------------------------------------------- cost-aware selection
+def read_cost_traces():
+    out = []
+    with open(os.path.join(GOLDEN, "cost_aware_traces.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            est, times, excess, sel = [p.strip() for p in line.split("|")]
+            out.append(([int(v) for v in est.split(",")], [int(v) for v in times.split(",")], int(excess),
+                        [int(v) for v in sel.split(",")] if sel else []))
+    return out
+
+
+@pytest.mark.parametrize("est,times,excess,want", read_cost_traces())
+def test_cost_aware_hand_traces(est, times, excess, want):
+    chosen = []
+    op.greedy_select(est, op.make_buckets(est, 100), excess, chosen, times, 100)
+    assert chosen == want
+
+
+def test_cost_aware_equal_layers_takes_the_cheapest():
+    """Equal layers, a peak that does not depend on which of them is dropped (no backward
+    transient, the head on top of everything): any feasible plan drops at least
+    k = ceil(excess / s) layers, so the k cheapest are the optimum, which brute force confirms."""
+    rng = np.random.default_rng(5)
+    n, a, b = 8, 1000, 60
+    for trial in range(20):
+        times = [int(v) for v in rng.permutation(n) * 50 + 100]           # distinct, more than 10 % apart
+        c = op.Components(F=1000, e=500, g=5000, a=[a] * n, b=[b] * n, w=[0] * n, t=times)
+        p0 = op.simulate_peak(c, 0)
+        k = int(rng.integers(1, n))
+        M = p0 - (k * (a - b) - 7)
+        res = op.plan_from_components(c, M, cost_aware=True)
+        cheapest = sorted(range(n), key=lambda l: times[l])[:k]
+        assert res.feasible and res.plan == sum(1 << l for l in cheapest)
+        peaks = op.brute_force_peaks(c)
+        cost = lambda m: sum(times[l] for l in range(n) if (m >> l) & 1)
+        assert cost(res.plan) == min(cost(int(m)) for m in np.nonzero(peaks <= M)[0])
+        plain = op.plan_from_components(c, M)                              # Algorithm 1: the first k
+        assert plain.plan == (1 << k) - 1 and cost(plain.plan) >= cost(res.plan)
+
+
+def test_cost_aware_equal_times_is_algorithm1_and_stays_feasible():
+    rng = np.random.default_rng(13)
+    for trial in range(200):
+        n = int(rng.integers(1, 11))
+        b = [int(v) for v in rng.integers(10, 200, n)]
+        a = [bb + int(v) for bb, v in zip(b, rng.choice([600, 640, 1500, 3000], n))]
+        w = [int(v) for v in rng.integers(0, 1500, n)]
+        g = int(rng.integers(0, 4000))
+        same = op.Components(F=100, e=50, g=g, a=a, b=b, w=w, t=[777] * n)
+        rand = op.Components(F=100, e=50, g=g, a=a, b=b, w=w, t=[int(v) for v in rng.integers(1, 1000, n)])
+        peaks = op.brute_force_peaks(same)
+        lo, hi = int(peaks.min()), int(peaks.max())
+        for M in (lo - 1, lo, (lo + hi) // 2, hi - 1, hi):
+            plain = op.plan_from_components(same, M)
+            eq = op.plan_from_components(same, M, cost_aware=True)
+            assert (eq.plan, eq.order, eq.predicted_peak) == (plain.plan, plain.order, plain.predicted_peak)
+            res = op.plan_from_components(rand, M, cost_aware=True)
+            assert res.feasible == bool((peaks <= M).any())
+            if res.feasible:
+                assert peaks[res.plan] <= M
+            none = op.plan_from_components(op.Components(F=100, e=50, g=g, a=a, b=b, w=w), M, cost_aware=True)
+            assert none.plan == plain.plan                                # no times collected: Algorithm 1
+
+
 def test_bucket_construction():
     assert op.make_buckets([50, 100, 48, 95, 20, 47]) == [[1, 3], [0, 2, 5], [4]]
     assert op.make_buckets([80, 80, 40, 40, 20, 20, 10, 10]) == [[0, 1], [2, 3], [4, 5], [6, 7]]
