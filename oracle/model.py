@@ -35,6 +35,8 @@ from typing import Dict, List, Optional, Tuple
 import numpy as np
 from scipy.special import erf as _erf
 
+from . import philox
+
 
 @dataclass
 class Cfg:
@@ -56,6 +58,18 @@ class Cfg:
         keys = ("n_layers", "hidden", "n_heads", "ffn", "vocab", "max_seq",
                 "causal", "pre_ln", "gelu_tanh", "head", "ln_eps")
         return Cfg(**{k: d[k] for k in keys}, ffn_by_layer=tuple(d.get("ffn_by_layer", ()) or ()))
+
+
+@dataclass
+class Dropout:
+    """Dropout as the fine-tuning tasks of Section 6.1 use it: p_hidden on the embedding output, on
+    the attention block's output projection and on the feed-forward block's output (each before
+    its residual sum), p_attn on the attention probabilities.  Masks come from a counter-based
+    generator keyed by (seed, step), see oracle/philox.py."""
+    p_hidden: float = 0.0
+    p_attn: float = 0.0
+    seed: int = 0
+    step: int = 0
 
 
 # --------------------------------------------------------------------------
@@ -131,8 +145,11 @@ def merge_heads(x):
     return x.transpose(0, 2, 1, 3).reshape(B * L, h * d)
 
 
-def attention_fwd(q, k, v, causal, lengths=None):
+def attention_fwd(q, k, v, causal, lengths=None, keep=None):
     """q, k, v: [B,h,L,d].  Returns o and the probability matrix.
+
+    keep (optional, [B,h,L,L]): dropout multipliers of the probabilities (0 or 1/(1-p)); the
+    output is (p * keep) v, the returned probabilities are the undropped ones.
 
     lengths (optional, [B]): sample b has lengths[b] real tokens, the rest of its row is padding
     (the batch is padded to its longest sample, Section 2.1); padded keys get no weight."""
@@ -148,13 +165,16 @@ def attention_fwd(q, k, v, causal, lengths=None):
     s = s - s.max(axis=-1, keepdims=True)
     e = np.exp(s)
     p = e / e.sum(axis=-1, keepdims=True)
-    return p @ v, p
+    return (p if keep is None else p * keep) @ v, p
 
 
-def attention_bwd(do, q, k, v, p):
+def attention_bwd(do, q, k, v, p, keep=None):
     d = q.shape[-1]
-    dv = p.transpose(0, 1, 3, 2) @ do
+    pd = p if keep is None else p * keep
+    dv = pd.transpose(0, 1, 3, 2) @ do
     dp = do @ v.transpose(0, 1, 3, 2)
+    if keep is not None:
+        dp = dp * keep
     ds = p * (dp - (dp * p).sum(axis=-1, keepdims=True))
     ds = ds / np.sqrt(float(d))
     dq = ds @ k
@@ -181,10 +201,22 @@ def cross_entropy(logits, labels):
 # --------------------------------------------------------------------------
 # One transformer block.
 # --------------------------------------------------------------------------
-def layer_forward(cfg: Cfg, P: Dict[str, np.ndarray], l: int, h, B: int, L: int, lengths=None):
+def layer_forward(cfg: Cfg, P: Dict[str, np.ndarray], l: int, h, B: int, L: int, lengths=None, dropout=None):
     pre = f"layer{l}."
     H, nh = cfg.hidden, cfg.n_heads
     S = {"h": h}
+    # dropout multipliers of this layer's three sites; a rebuilt layer gets the same ones because
+    # they depend on (seed, step, site, element number) only
+    S["keep_p"] = S["keep_o"] = S["keep_f"] = None
+    if dropout is not None and dropout.p_attn > 0:
+        S["keep_p"] = philox.keep_scale(philox.attn_index(B, nh, L), dropout.p_attn, dropout.seed,
+                                        philox.site_attn_prob(l), dropout.step, h.dtype.type)
+    if dropout is not None and dropout.p_hidden > 0:
+        idx = philox.hidden_index(B * L, H)
+        S["keep_o"] = philox.keep_scale(idx, dropout.p_hidden, dropout.seed, philox.site_attn_out(l),
+                                        dropout.step, h.dtype.type)
+        S["keep_f"] = philox.keep_scale(idx, dropout.p_hidden, dropout.seed, philox.site_ffn_out(l),
+                                        dropout.step, h.dtype.type)
     a = h
     if cfg.pre_ln:
         a, S["ln1"] = layernorm_fwd(h, P[pre + "ln1_g"], P[pre + "ln1_b"], cfg.ln_eps)
@@ -193,11 +225,12 @@ def layer_forward(cfg: Cfg, P: Dict[str, np.ndarray], l: int, h, B: int, L: int,
     q = split_heads(qkv[:, :H], B, L, nh)
     k = split_heads(qkv[:, H:2 * H], B, L, nh)
     v = split_heads(qkv[:, 2 * H:], B, L, nh)
-    o, p = attention_fwd(q, k, v, cfg.causal, lengths)
+    o, p = attention_fwd(q, k, v, cfg.causal, lengths, S["keep_p"])
     S.update(q=q, k=k, v=v, p=p)
     ctx = merge_heads(o)
     S["ctx"] = ctx
-    s1 = h + linear_fwd(ctx, P[pre + "wo"], P[pre + "bo"])
+    proj = linear_fwd(ctx, P[pre + "wo"], P[pre + "bo"])
+    s1 = h + (proj if S["keep_o"] is None else proj * S["keep_o"])
     if cfg.pre_ln:
         u = s1
         f_in, S["ln2"] = layernorm_fwd(u, P[pre + "ln2_g"], P[pre + "ln2_b"], cfg.ln_eps)
@@ -208,7 +241,8 @@ def layer_forward(cfg: Cfg, P: Dict[str, np.ndarray], l: int, h, B: int, L: int,
     pa = linear_fwd(f_in, P[pre + "w1"], P[pre + "b1"])
     g = gelu_fwd(pa, cfg.gelu_tanh)
     S.update(pa=pa, g=g)
-    s2 = u + linear_fwd(g, P[pre + "w2"], P[pre + "b2"])
+    ffn = linear_fwd(g, P[pre + "w2"], P[pre + "b2"])
+    s2 = u + (ffn if S["keep_f"] is None else ffn * S["keep_f"])
     if cfg.pre_ln:
         out = s2
     else:
@@ -223,7 +257,8 @@ def layer_backward(cfg: Cfg, P, l: int, S, dout, G: Dict[str, np.ndarray]):
         ds2 = dout
     else:
         ds2, G[pre + "ln2_g"], G[pre + "ln2_b"] = layernorm_bwd(dout, S["ln2"], P[pre + "ln2_g"])
-    dg, G[pre + "w2"], G[pre + "b2"] = linear_bwd(ds2, S["g"], P[pre + "w2"])
+    dffn = ds2 if S["keep_f"] is None else ds2 * S["keep_f"]
+    dg, G[pre + "w2"], G[pre + "b2"] = linear_bwd(dffn, S["g"], P[pre + "w2"])
     dpa = dg * gelu_grad(S["pa"], cfg.gelu_tanh)
     dfin, G[pre + "w1"], G[pre + "b1"] = linear_bwd(dpa, S["f_in"], P[pre + "w1"])
     if cfg.pre_ln:
@@ -232,10 +267,11 @@ def layer_backward(cfg: Cfg, P, l: int, S, dout, G: Dict[str, np.ndarray]):
     else:
         du = ds2 + dfin
         ds1, G[pre + "ln1_g"], G[pre + "ln1_b"] = layernorm_bwd(du, S["ln1"], P[pre + "ln1_g"])
-    dctx, G[pre + "wo"], G[pre + "bo"] = linear_bwd(ds1, S["ctx"], P[pre + "wo"])
+    dproj = ds1 if S["keep_o"] is None else ds1 * S["keep_o"]
+    dctx, G[pre + "wo"], G[pre + "bo"] = linear_bwd(dproj, S["ctx"], P[pre + "wo"])
     B, nh, L, d = S["q"].shape
     do = split_heads(dctx, B, L, nh)
-    dq, dk, dv = attention_bwd(do, S["q"], S["k"], S["v"], S["p"])
+    dq, dk, dv = attention_bwd(do, S["q"], S["k"], S["v"], S["p"], S["keep_p"])
     dqkv = np.concatenate([merge_heads(dq), merge_heads(dk), merge_heads(dv)], axis=1)
     da, G[pre + "wqkv"], G[pre + "bqkv"] = linear_bwd(dqkv, S["a"], P[pre + "wqkv"])
     if cfg.pre_ln:
@@ -249,13 +285,14 @@ def layer_backward(cfg: Cfg, P, l: int, S, dout, G: Dict[str, np.ndarray]):
 # --------------------------------------------------------------------------
 def train_step(cfg: Cfg, params: Dict[str, np.ndarray], tokens: np.ndarray,
                labels: np.ndarray, plan: int = 0, dtype=np.float64,
-               return_logits: bool = False, lengths=None):
+               return_logits: bool = False, lengths=None, dropout: "Dropout" = None):
     """Loss and gradients for one mini-batch.
 
     plan: bitmask, bit l set = layer l drops its activations after its forward
     (only its input survives) and rebuilds them at the start of its backward.
     lengths (optional, [B]): real tokens per sample of a batch padded to L; padded keys are
     masked in every attention and padded positions carry no label.
+    dropout (optional): see Dropout; None or zero probabilities leave every value as it is.
     """
     P = {k: np.asarray(v, dtype=dtype) for k, v in params.items()}
     B, L = tokens.shape
@@ -275,13 +312,18 @@ def train_step(cfg: Cfg, params: Dict[str, np.ndarray], tokens: np.ndarray,
         emb_saved = None
     else:
         h, emb_saved = layernorm_fwd(emb, P["emb_ln_g"], P["emb_ln_b"], cfg.ln_eps)
+    keep_e = None
+    if dropout is not None and dropout.p_hidden > 0:
+        keep_e = philox.keep_scale(philox.hidden_index(T, H), dropout.p_hidden, dropout.seed,
+                                   philox.SITE_EMBED, dropout.step, h.dtype.type)
+        h = h * keep_e
 
     # layer stack, keeping or dropping activations
     inputs: List[np.ndarray] = []
     saved: List[Optional[dict]] = []
     for l in range(cfg.n_layers):
         inputs.append(h)
-        h, S = layer_forward(cfg, P, l, h, B, L, lengths)
+        h, S = layer_forward(cfg, P, l, h, B, L, lengths, dropout)
         saved.append(None if (plan >> l) & 1 else S)
 
     # head and loss
@@ -316,11 +358,13 @@ def train_step(cfg: Cfg, params: Dict[str, np.ndarray], tokens: np.ndarray,
     for l in reversed(range(cfg.n_layers)):
         S = saved[l]
         if S is None:
-            _, S = layer_forward(cfg, P, l, inputs[l], B, L, lengths)
+            _, S = layer_forward(cfg, P, l, inputs[l], B, L, lengths, dropout)
         dh = layer_backward(cfg, P, l, S, dh, G)
         saved[l] = None
 
     # embedding backward
+    if keep_e is not None:
+        dh = dh * keep_e
     if cfg.pre_ln:
         demb = dh
     else:
