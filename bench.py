@@ -54,6 +54,9 @@ def main():
                     help="leave the parameter update (AdamW) out of the iteration: forward, loss and backward only")
     ap.add_argument("--cost-aware", action="store_true",
                     help="use the forward times collected in the sheltered steps inside Algorithm 1's buckets")
+    ap.add_argument("--dropout", type=float, default=0.0,
+                    help="dropout probability of the hidden sites (embedding output, attention and feed-forward "
+                         "block outputs), masks from the counter-based generator; 0 = off, the measured default")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 256 MiB element-wise copy kernels (reference for scaling FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -92,6 +95,8 @@ def main():
     m.load_params(synthdata.make_params(shape, wl.seed))
     if update:
         m.optimizer_init(**adamw)
+    if args.dropout > 0:
+        m.set_dropout(args.dropout, 0.0, wl.seed, 0)
 
     def iteration(t, l):
         r = m.train_step(t, l)
@@ -173,7 +178,7 @@ def main():
                                f"budget {wl.budget_frac:.2f} x no-checkpoint peak at L={shape.max_seq}",
                    "global_batch": B, "mean_seq_len": round(float(np.mean([t.shape[1] for t, _ in timed])), 1),
                    "budget_bytes": budget, "sheltered_steps": sheltered, "plan_mode": args.plan_mode,
-                   "cost_aware": bool(args.cost_aware)},
+                   "cost_aware": bool(args.cost_aware), "dropout": args.dropout},
         "tokens_per_s": round(sum(t.size for t, _ in timed) / dt, 1),
         "useful_tflops": round(useful / dt / 1e12, 2), "recompute_tflops": round(recompute / dt / 1e12, 2),
         "mfma_frac_useful": round(useful / dt / 1e12 / PEAK_BF16_TFLOPS, 4),

@@ -141,6 +141,23 @@ int mimose_train_step_padded(mimose_ctx* ctx, const int32_t* tokens_host, const 
                              const int32_t* lengths_host, int32_t B, int32_t L, float* loss,
                              uint64_t* peak_bytes, uint64_t* plan_id);
 
+/*
+ * Dropout, as the fine-tuning tasks of Section 6.1 train with it.  p_hidden acts on the
+ * embedding output, on the attention block's output projection and on the feed-forward block's
+ * output (each before its residual sum); kept elements are scaled by 1/(1-p).  The masks come
+ * from a counter-based generator (Philox4x32, ten rounds): element i of the tensor at site s in
+ * iteration t is kept when word i%4 of the block with counter (i/4 low, i/4 high, s, t) and key
+ * (seed low, seed high) is >= round(p * 2^32).  Sites: 0 the embedding output; layer l:
+ * 4(l+1)+1 the attention output projection, 4(l+1)+2 the feed-forward output.  A layer that is
+ * checkpointed and run again before its backward therefore meets the masks of its first run
+ * (Section 2.2: recomputation must reproduce the dropped tensors), and nothing is stored.
+ * first_step numbers the next iteration; every completed mimose_train_step adds one.
+ * p_attn (dropout of the attention probabilities, site 4(l+1)) must be 0: not available.
+ * Zero probabilities (the initial state) switch dropout off.  Errors: INVALID_ARG.
+ */
+int mimose_set_dropout(mimose_ctx* ctx, float p_hidden, float p_attn, uint64_t seed,
+                       uint64_t first_step);
+
 /* Same planning, allocation and bookkeeping as mimose_train_step but no device work:
  * reports the peak the step would reach.  Works on host-only contexts. */
 int mimose_dry_step(mimose_ctx* ctx, int32_t B, int32_t L, uint64_t* peak_bytes, uint64_t* plan_id);
@@ -278,6 +295,12 @@ int mimose_op_attention_bwd(int32_t dtype, const void* qkv, const void* ctx, con
                             const float* lse, float* delta, void* dqkv, const int32_t* lengths,
                             int32_t B, int32_t L, int32_t n_heads, int32_t head_dim,
                             int32_t causal, void* stream);
+/* dst[n] = (resid ? resid[n] : 0) + mask * src[n] / (1-p) with the mask mimose_set_dropout
+ * describes for (seed, site, step).  dst, src: storage type, or fp32 when io_f32; resid: storage
+ * type or NULL; dst may be src. */
+int mimose_op_dropout(int32_t dtype, void* dst, const void* src, int32_t io_f32, const void* resid,
+                      int64_t n, float p, uint64_t seed, uint32_t site, uint32_t step,
+                      void* stream);
 /* logits [T, ld] (first V columns valid) -> in place d loss / d logits (columns >= V zeroed);
  * row_loss fp32[T]; loss: device fp32 scalar = sum(row_loss)/n_valid. */
 int mimose_op_softmax_xent(int32_t dtype, void* logits, int64_t ld, const int32_t* labels,

@@ -66,6 +66,8 @@ SIGNATURES = {
     "mimose_train_step": (C.c_int, [_vp, _vp, _vp, _i32, _i32, C.POINTER(_f32), C.POINTER(_u64), C.POINTER(_u64)]),
     "mimose_train_step_padded": (C.c_int, [_vp, _vp, _vp, _vp, _i32, _i32, C.POINTER(_f32), C.POINTER(_u64),
                                            C.POINTER(_u64)]),
+    "mimose_set_dropout": (C.c_int, [_vp, _f32, _f32, _u64, _u64]),
+    "mimose_op_dropout": (C.c_int, [_i32, _vp, _vp, _i32, _vp, _i64, _f32, _u64, C.c_uint32, C.c_uint32, _vp]),
     "mimose_dry_step": (C.c_int, [_vp, _i32, _i32, C.POINTER(_u64), C.POINTER(_u64)]),
     "mimose_get_grad": (C.c_int, [_vp, _i32, _vp, _u64]),
     "mimose_get_param": (C.c_int, [_vp, _i32, _vp, _u64]),
@@ -339,6 +341,15 @@ def mimose_op_attention_bwd(dtype, qkv, ctx_in, dctx, lse, delta, dqkv, B, L, n_
                                                   _ptr(stream)))
 
 
+def mimose_op_dropout(dtype, dst, src, io_f32, resid, n, p, seed, site, step, stream=None):
+    _check(load_library().mimose_op_dropout(dtype, _ptr(dst), _ptr(src), int(io_f32), _ptr(resid), n, p, seed, site, step,
+                                            _ptr(stream)))
+
+
+def mimose_set_dropout(ctx, p_hidden: float, p_attn: float, seed: int, first_step: int = 0):
+    _check(load_library().mimose_set_dropout(ctx, p_hidden, p_attn, seed, first_step), ctx)
+
+
 def mimose_op_softmax_xent(dtype, logits, ld, labels, row_loss, loss, T, V, n_valid, stream=None):
     _check(load_library().mimose_op_softmax_xent(dtype, _ptr(logits), ld, _ptr(labels), _ptr(row_loss), _ptr(loss),
                                                  T, V, n_valid, _ptr(stream)))
@@ -394,6 +405,9 @@ class Mimose:
         if lengths is not None:
             return mimose_train_step_padded(self.ctx, tokens, labels, lengths)
         return mimose_train_step(self.ctx, tokens, labels)
+
+    def set_dropout(self, p_hidden, p_attn=0.0, seed=0, first_step=0):
+        mimose_set_dropout(self.ctx, p_hidden, p_attn, seed, first_step)
 
     def dry_step(self, B, L):
         return mimose_dry_step(self.ctx, B, L)

@@ -13,6 +13,15 @@ constexpr int kMaxRowWidth = 1024;  // widest row the row-wise kernels accept (h
 
 inline size_t elt_size(int dtype) { return dtype == BF16 ? 2 : 4; }
 
+// Dropout mask descriptor, passed by value to kernels.  thr == 0: dropout off.
+struct DropDesc {
+  uint32_t thr = 0;      // an element is kept when its 32-bit word >= thr (thr = round(p * 2^32))
+  float scale = 1.f;     // 1 / (1 - p), applied to kept elements
+  uint32_t k0 = 0, k1 = 0;  // seed, low and high half
+  uint32_t site = 0;     // which tensor of the model (embedding, layer l's projections ...)
+  uint32_t step = 0;     // iteration number
+};
+
 struct GemmArgs {
   const void* A; int64_t lda; bool a_kmajor;
   const void* B; int64_t ldb; bool b_kmajor;
@@ -76,6 +85,11 @@ struct AdamChunk { int32_t tensor; int32_t pad; int64_t start; };
 struct AdamHyper { float lr, beta1, beta2, eps, weight_decay, inv_c1, inv_c2; };   // inv_c = 1 / (1 - beta^t)
 void adamw_update(int lowp_dtype, const AdamTensor* tensors, const AdamChunk* chunks, int n_chunks, AdamHyper h,
                   hipStream_t st);
+// dst[n] = (resid ? resid[n] : 0) + mask * d.scale * src[n] with the mask of d (element i: word i % 4
+// of block i / 4).  dst and src have the storage type, or fp32 when io_f32; resid has the storage
+// type; dst may be src.
+void dropout_apply(int dtype, void* dst, const void* src, bool io_f32, const void* resid, int64_t n, const DropDesc& d,
+                   hipStream_t st);
 // dst fp32 = src (storage dtype)
 void convert_to_f32(int dtype, const void* src, float* dst, int64_t n, hipStream_t st);
 

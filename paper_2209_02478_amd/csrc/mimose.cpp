@@ -102,6 +102,9 @@ struct mimose_ctx {
   std::unique_ptr<mimose::Planner> planner;
   int64_t forced_plan = -1;
   int plan_mode = MIMOSE_PLAN_INPUT_AWARE;
+  // dropout: probability of the hidden sites, seed, number of the next iteration
+  float p_hidden = 0.f;
+  uint64_t drop_seed = 0, drop_step = 0;
   // parameter update (Section 2.1: the iteration ends with it; its state is part of the
   // input-independent memory of Section 3.1)
   bool opt_on = false;
@@ -260,6 +263,23 @@ class Step {
     a.gelu_out = act; a.gelu = gelu;
     gemm(a);
   }
+  // Dropout sites: 0 the embedding output; layer l: 4(l+1)+1 the attention block's output
+  // projection, 4(l+1)+2 the feed-forward block's output (4(l+1) is kept for the attention
+  // probabilities).
+  bool drop_on() const { return c_->p_hidden > 0.f; }
+  mk::DropDesc drop_desc(uint32_t site) const {
+    mk::DropDesc d;
+    const double p = (double)c_->p_hidden;
+    d.thr = (uint32_t)std::min(std::floor(p * 4294967296.0 + 0.5), 4294967295.0);
+    d.scale = (float)(1.0 / (1.0 - p));
+    d.k0 = (uint32_t)c_->drop_seed; d.k1 = (uint32_t)(c_->drop_seed >> 32);
+    d.site = site; d.step = (uint32_t)c_->drop_step;
+    return d;
+  }
+  // io (storage type, or fp32 when io_f32) = resid + dropout(src); src may be io
+  void dropout(void* dst, const void* src, bool io_f32, const void* resid, uint32_t site) {
+    if (!dry_) mk::dropout_apply(dt_, dst, src, io_f32, resid, (int64_t)T_ * f_.hidden, drop_desc(site), st_);
+  }
   // dX[T,in] = dY[T,out] W[out,in] (+ resid)
   void dgrad(const void* dY, int64_t ldy, int out, int wi, void* dX, int in, const void* resid = nullptr,
              bool out_f32 = false) {
@@ -365,6 +385,7 @@ void Step::embed_stage(const int32_t* tokens, const int32_t* labels) {
   Timed t(this, MIMOSE_K_EMBED_FWD, (f_.pre_ln ? 3.0 : 4.0) * T_ * H * es_d());
   mk::embed_fwd(dt_, ids_, w(c_->i_tok), w(c_->i_pos), f_.pre_ln ? nullptr : w(c_->i_eg),
                 f_.pre_ln ? nullptr : w(c_->i_eb), emb_sum_, h0_, B_, L_, H, f_.ln_eps, !f_.pre_ln, st_);
+  if (drop_on()) dropout(h0_, h0_, false, nullptr, 0);
 }
 
 void Step::alloc_layer(int l, LayerActs& A) {
@@ -397,15 +418,22 @@ void Step::layer_forward(int l, LayerActs& A) {
     Timed t(this, MIMOSE_K_ATTN_FWD, 4.0 * T_ * L_ * H * (f_.causal ? 0.5 : 1.0));
     if (!dry_) mk::attention_fwd(dt_, A.qkv, A.ctx, A.lse, lens_, B_, L_, nh, d, f_.causal, st_);
   }
-  linear(A.ctx, H, p.wo, p.bo, A.s1, H, H, A.x, nullptr, 0, wide_);
+  // with dropout the product lands in the sum's buffer and an element-wise pass makes
+  // sum = residual + dropout(product) in place; without it the residual rides in the epilogue
+  const bool drop = drop_on();
+  const uint32_t site_o = 4 * (uint32_t)(l + 1) + 1, site_f = site_o + 1;
+  linear(A.ctx, H, p.wo, p.bo, A.s1, H, H, drop ? nullptr : A.x, nullptr, 0, wide_);
+  if (drop) dropout(A.s1, A.s1, wide_, A.x, site_o);
   if (f_.pre_ln) {
     ln_fwd(A.s1, p.ln2g, p.ln2b, A.u);
     linear(A.u, H, p.w1, p.b1, A.pre, F, F, nullptr, A.act, gelu);
-    linear(A.act, F, p.w2, p.b2, A.out, H, H, A.s1);
+    linear(A.act, F, p.w2, p.b2, A.out, H, H, drop ? nullptr : A.s1);
+    if (drop) dropout(A.out, A.out, false, A.s1, site_f);
   } else {
     ln_fwd(A.s1, p.ln1g, p.ln1b, A.u, wide_);
     linear(A.u, H, p.w1, p.b1, A.pre, F, F, nullptr, A.act, gelu);
-    linear(A.act, F, p.w2, p.b2, A.s2, H, H, A.u, nullptr, 0, wide_);
+    linear(A.act, F, p.w2, p.b2, A.s2, H, H, drop ? nullptr : A.u, nullptr, 0, wide_);
+    if (drop) dropout(A.s2, A.s2, wide_, A.u, site_f);
     ln_fwd(A.s2, p.ln2g, p.ln2b, A.out, wide_);
   }
 }
@@ -421,9 +449,14 @@ void Step::layer_backward(int l, LayerActs& A) {
   // post-LN: oA = d s2 (LayerNorm 2 backward of the incoming gradient); pre-LN: the incoming
   // gradient is d s2 itself (oA aliases gA)
   if (!f_.pre_ln) ln_bwd(gA_, A.s2, p.ln2g, p.ln2b, oA_, nullptr, wide_, wide_);
-  wgrad(oA_, H, H, A.act, F, p.w2, p.b2);
+  // with dropout the branch sees the masked gradient (a copy: the residual path keeps the whole one)
+  const bool drop = drop_on();
+  const uint32_t site_o = 4 * (uint32_t)(l + 1) + 1, site_f = site_o + 1;
+  const void* dffn = oA_;
+  if (drop) { void* m = talloc(TH); dropout(m, oA_, false, nullptr, site_f); dffn = m; }
+  wgrad(dffn, H, H, A.act, F, p.w2, p.b2);
   void* dact = talloc(TF);
-  dgrad(oA_, H, H, p.w2, dact, F);
+  dgrad(dffn, H, H, p.w2, dact, F);
   {
     Timed t(this, MIMOSE_K_GELU_BWD, 3.0 * TF * es_d());
     if (!dry_) mk::gelu_bwd(dt_, dact, A.pre, TF, f_.gelu_tanh, st_);        // dact = d pre
@@ -438,9 +471,11 @@ void Step::layer_backward(int l, LayerActs& A) {
     dgrad(dact, F, F, p.w1, gB_, H, oA_, wide_);                              // gB = d u = d s2 + FFN path
     ln_bwd(gB_, A.s1, p.ln1g, p.ln1b, oB_, nullptr, wide_, wide_);            // oB = d s1
   }
-  wgrad(oB_, H, H, A.ctx, H, p.wo, p.bo);
+  const void* dproj = oB_;
+  if (drop) { void* m = talloc(TH); dropout(m, oB_, false, nullptr, site_o); dproj = m; }
+  wgrad(dproj, H, H, A.ctx, H, p.wo, p.bo);
   void* dctx = talloc(TH);
-  dgrad(oB_, H, H, p.wo, dctx, H);
+  dgrad(dproj, H, H, p.wo, dctx, H);
   void* dqkv = talloc(3 * TH);
   float* delta = (float*)ar.alloc((uint64_t)B_ * nh * L_ * 4);
   {
@@ -537,6 +572,7 @@ void Step::embed_sort(const int32_t* tokens) {
 
 void Step::embed_backward() {
   const int H = f_.hidden;
+  if (drop_on()) dropout(gA_, gA_, wide_, nullptr, 0);
   if (!f_.pre_ln) ln_bwd(gA_, emb_sum_, c_->i_eg, c_->i_eb, oA_, nullptr, wide_, false);
   if (!dry_)
     mk::embed_bwd(dt_, oA_, ids_, order_, seg_, n_seg_, g(c_->i_tok), g(c_->i_pos), B_, L_, H, f_.max_seq, st_);
@@ -728,6 +764,7 @@ int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, const i
   double uf, rf;
   flops(f, B, L, plan, &uf, &rf);
   S.steps++;
+  if (!dry) c->drop_step++;                 // the next iteration draws other masks
   S.sheltered_steps = c->planner->sheltered_steps_seen();
   S.cache_hits = c->planner->hits; S.cache_misses = c->planner->misses;
   S.cache_entries = c->planner->cache_entries();
@@ -854,6 +891,17 @@ int mimose_train_step_padded(mimose_ctx* c, const int32_t* tokens, const int32_t
   if (!c) return MIMOSE_ERR_INVALID_ARG;
   if (!lengths) return fail(c, MIMOSE_ERR_INVALID_ARG, "lengths must be given");
   return do_step(c, tokens, labels, lengths, B, L, false, loss, peak, plan_id);
+}
+
+int mimose_set_dropout(mimose_ctx* c, float p_hidden, float p_attn, uint64_t seed, uint64_t first_step) {
+  if (!c) return MIMOSE_ERR_INVALID_ARG;
+  if (!(p_hidden >= 0.f) || !(p_hidden < 1.f) || !(p_attn >= 0.f) || !(p_attn < 1.f))
+    return fail(c, MIMOSE_ERR_INVALID_ARG, "dropout probabilities must lie in [0, 1)");
+  if (p_attn > 0.f) return fail(c, MIMOSE_ERR_INVALID_ARG, "dropout of the attention probabilities is not available");
+  c->p_hidden = p_hidden;
+  c->drop_seed = seed;
+  c->drop_step = first_step;
+  return MIMOSE_OK;
 }
 
 int mimose_dry_step(mimose_ctx* c, int32_t B, int32_t L, uint64_t* peak, uint64_t* plan_id) {

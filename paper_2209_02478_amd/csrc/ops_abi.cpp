@@ -71,6 +71,18 @@ int mimose_op_attention_bwd(int32_t dtype, const void* qkv, const void* ctx, con
   return done();
 }
 
+int mimose_op_dropout(int32_t dtype, void* dst, const void* src, int32_t io_f32, const void* resid, int64_t n, float p,
+                      uint64_t seed, uint32_t site, uint32_t step, void* stream) {
+  if (bad_dtype(dtype) || !dst || !src || n < 0 || !(p >= 0.f) || !(p < 1.f)) return MIMOSE_ERR_INVALID_ARG;
+  mk::DropDesc d;
+  d.thr = (uint32_t)std::min(std::floor((double)p * 4294967296.0 + 0.5), 4294967295.0);
+  d.scale = (float)(1.0 / (1.0 - (double)p));
+  d.k0 = (uint32_t)seed; d.k1 = (uint32_t)(seed >> 32);
+  d.site = site; d.step = step;
+  mk::dropout_apply(dtype, dst, src, io_f32 != 0, resid, n, d, (hipStream_t)stream);
+  return done();
+}
+
 int mimose_op_softmax_xent(int32_t dtype, void* logits, int64_t ld, const int32_t* labels, float* row_loss,
                            float* loss, int32_t T, int32_t V, int32_t n_valid, void* stream) {
   if (bad_dtype(dtype) || !logits || !labels || !row_loss || !loss || T < 0 || V < 1 || ld < V) return MIMOSE_ERR_INVALID_ARG;

@@ -9,6 +9,7 @@
 #include <initializer_list>
 
 #include "kernels.h"
+#include "philox.h"
 
 namespace mk {
 
@@ -571,6 +572,24 @@ __global__ __launch_bounds__(256) void widen_kernel(const T* __restrict__ src, f
   if (i < n) dst[i] = ld<T>(src + i);
 }
 
+// dst[i] = (resid ? resid[i] : 0) + keep(i) * scale * src[i]; element i reads word i % 4 of block
+// i / 4.  Four elements per thread; dst may be src.
+template <typename TIO, typename TR>
+__global__ __launch_bounds__(256) void dropout_kernel(TIO* __restrict__ dst, const TIO* src, const TR* __restrict__ resid,
+                                                      int64_t n, DropDesc d) {
+  const int64_t blk = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t i0 = 4 * blk;
+  if (i0 >= n) return;
+  const uint4 w4 = drop_words(d, (uint64_t)blk);
+  const uint32_t w[4] = {w4.x, w4.y, w4.z, w4.w};
+  const int cnt = (int)min((int64_t)4, n - i0);
+  for (int e = 0; e < cnt; ++e) {
+    float v = w[e] >= d.thr ? ld<TIO>(src + i0 + e) * d.scale : 0.f;
+    if (resid) v += ld<TR>(resid + i0 + e);
+    st<TIO>(dst + i0 + e, v);
+  }
+}
+
 // One block per chunk of kAdamChunk elements of one tensor; element-wise, fp32 arithmetic:
 //   m = b1 m + (1-b1) g;  v = b2 v + (1-b2) g^2
 //   p = p - lr * ( (m / c1) / (sqrt(v / c2) + eps) + wd p )      (decoupled weight decay)
@@ -767,6 +786,21 @@ void convert_to_f32(int dtype, const void* src, float* dst, int64_t n, hipStream
   dim3 grid((unsigned)((n + 255) / 256));
   if (dtype == BF16) hipLaunchKernelGGL(widen_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)src, dst, n);
   else hipLaunchKernelGGL(widen_kernel<float>, grid, dim3(256), 0, st, (const float*)src, dst, n);
+}
+
+void dropout_apply(int dtype, void* dst, const void* src, bool io_f32, const void* resid, int64_t n, const DropDesc& d,
+                   hipStream_t st) {
+  if (n <= 0) return;
+  dim3 grid((unsigned)(((n + 3) / 4 + 255) / 256));
+  if (dtype == BF16 && !io_f32)
+    hipLaunchKernelGGL((dropout_kernel<bf16_t, bf16_t>), grid, dim3(256), 0, st, (bf16_t*)dst, (const bf16_t*)src,
+                       (const bf16_t*)resid, n, d);
+  else if (dtype == BF16)
+    hipLaunchKernelGGL((dropout_kernel<float, bf16_t>), grid, dim3(256), 0, st, (float*)dst, (const float*)src,
+                       (const bf16_t*)resid, n, d);
+  else
+    hipLaunchKernelGGL((dropout_kernel<float, float>), grid, dim3(256), 0, st, (float*)dst, (const float*)src,
+                       (const float*)resid, n, d);
 }
 
 void adamw_update(int lowp_dtype, const AdamTensor* tensors, const AdamChunk* chunks, int n_chunks, AdamHyper h,

@@ -342,3 +342,35 @@ def test_embedding_fwd_bwd(dtype, has_ln):
     ref_pos = np.zeros((max_seq, H)); np.add.at(ref_pos, p, quant(d, dtype))
     close(host(gtok), ref_tok, 0, k=20.0)
     close(host(gpos), ref_pos, 0, k=20.0)
+
+
+# ---------------------------------------------------------------- dropout (counter-based masks)
+@pytest.mark.parametrize("dtype,io_f32", [(0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("n", [4096 + 3, 5, 1 << 18])
+@pytest.mark.parametrize("with_resid", [0, 1])
+def test_dropout_op(dtype, io_f32, n, with_resid):
+    """The kept set must be the oracle's bit for bit (an integer comparison of generator words);
+    the values are one multiplication and one addition in fp32."""
+    from oracle import philox as ph
+    rng = np.random.default_rng(n + dtype)
+    p = float(np.float32(0.3))
+    seed, site, step = 0x9E3779B97F4A7C15, 4 * 7 + 1, 123456
+    src = rng.standard_normal(n).astype(np.float32)
+    resid = rng.standard_normal(n).astype(np.float32)
+    io_dtype = 0 if io_f32 else dtype
+    d_src = dev(src, io_dtype)
+    d_res = dev(resid, dtype) if with_resid else None
+    out = torch.full_like(d_src, 9.0)
+    mi.mimose_op_dropout(dtype, out, d_src, io_f32, d_res, n, p, seed, site, step)
+    inplace = d_src.clone()
+    mi.mimose_op_dropout(dtype, inplace, inplace, io_f32, d_res, n, p, seed, site, step)
+    sync()
+    keep = ph.keep_scale(np.arange(n, dtype=np.uint64), p, seed, site, step)
+    base = quant(resid, dtype).astype(np.float64) if with_resid else np.zeros(n)
+    ref = base + keep * quant(src, io_dtype)
+    got = host(out)
+    if not with_resid:
+        assert np.array_equal(got != 0, (keep != 0) & (quant(src, io_dtype) != 0))      # the same elements survive
+    close(got, ref, io_dtype, k=1.5)
+    assert np.array_equal(host(inplace), got)
+    assert 0.25 < (keep == 0).mean() < 0.35 or n < 100

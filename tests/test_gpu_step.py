@@ -20,6 +20,13 @@ def oracle_step(shape, params, tokens, labels, dtype=np.float64, lengths=None):
     return om.train_step(cfg, params, tokens, labels, dtype=dtype, lengths=lengths)
 
 
+def oracle_step_dropout(shape, params, tokens, labels, dropout, lengths=None):
+    cfg = om.Cfg.from_shape(synthdata.shape_dict(shape))
+    if shape.dtype == "bf16":
+        params = {k: om.round_to_bf16(v) for k, v in params.items()}
+    return om.train_step(cfg, params, tokens, labels, lengths=lengths, dropout=dropout)
+
+
 def check_against_oracle(shape, m, params, tokens, labels, loss_tol, grad_tol, oracle_dtype=np.float64, lengths=None):
     loss, peak, plan = m.train_step(tokens, labels, lengths=lengths)
     G = m.grads()
@@ -213,6 +220,70 @@ def test_padded_batches(name):
         with pytest.raises(mi.MimoseError) as e:
             m.train_step(tokens, labels, lengths=np.array(bad))
         assert e.value.code == mi.MIMOSE_ERR_INVALID_ARG
+    m.close()
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_dropout_parity_and_replay(name):
+    """Dropout with counter-based masks: parity with the oracle given (p, seed, iteration), the
+    same bits whether a layer's forward ran once or was rebuilt, other masks in the next
+    iteration, and the plain step again once it is switched off."""
+    shape = SMALL[name]
+    fp32 = shape.dtype == "fp32"
+    n = shape.n_layers
+    p = float(np.float32(0.15))
+    seed = 0xC0FFEE1234567
+    params = synthdata.make_params(shape, 81, perturb=True)
+    tokens, labels = synthdata.make_batch(shape, 4, 33, 82)
+    m = mi.Mimose(synthdata.shape_dict(shape), 0, arena_bytes=256 * MiB)
+    m.load_params(params)
+    m.force_plan(0)
+    plain_loss, plain_peak, _ = m.train_step(tokens, labels)
+    plain_G = m.grads()
+
+    def run(step, plan):
+        m.set_dropout(p, 0.0, seed, step)
+        m.force_plan(plan)
+        loss, peak, _ = m.train_step(tokens, labels)
+        return loss, peak, m.grads()
+
+    loss0, peak0, G0 = run(5, 0)
+    ref_loss, RG = oracle_step_dropout(shape, params, tokens, labels, om.Dropout(p, 0.0, seed, 5))
+    assert abs(loss0 - ref_loss) <= (1e-4 if fp32 else 1e-2) * abs(ref_loss)
+    for k, ref in RG.items():
+        assert rel_l2(G0[k], ref) <= (1e-3 if fp32 else 2e-2), k
+    assert loss0 != plain_loss and peak0 >= plain_peak           # masked gradient copies live in the backward
+    for plan in range(1, 1 << n):
+        loss, _, G = run(5, plan)
+        assert loss == loss0
+        for k in G0:
+            assert np.array_equal(G0[k], G[k]), (plan, k)
+    # the library counts iterations itself: the step after 5 is 6
+    m.set_dropout(p, 0.0, seed, 5)
+    m.force_plan(0)
+    m.train_step(tokens, labels)
+    loss6, _, _ = m.train_step(tokens, labels)
+    ref6, _ = oracle_step_dropout(shape, params, tokens, labels, om.Dropout(p, 0.0, seed, 6))
+    assert loss6 != loss0 and abs(loss6 - ref6) <= (1e-4 if fp32 else 1e-2) * abs(ref6)
+    # padded batch and dropout together
+    tk, lb, lens = synthdata.make_padded_batch(shape, [20, 7, 13], 83)
+    m.set_dropout(p, 0.0, seed, 9)
+    lossp, _, _ = m.train_step(tk, lb, lengths=lens)
+    refp, RGp = oracle_step_dropout(shape, params, tk, lb, om.Dropout(p, 0.0, seed, 9), lens)
+    assert abs(lossp - refp) <= (1e-4 if fp32 else 1e-2) * abs(refp)
+    Gp = m.grads()
+    for k, ref in RGp.items():
+        assert rel_l2(Gp[k], ref) <= (1e-3 if fp32 else 2e-2), k
+    # off again: the plain step, bit for bit
+    m.set_dropout(0.0, 0.0, 0, 0)
+    loss, peak, _ = m.train_step(tokens, labels)
+    assert loss == plain_loss and peak == plain_peak
+    for k, g in m.grads().items():
+        assert np.array_equal(g, plain_G[k]), k
+    with pytest.raises(mi.MimoseError):
+        m.set_dropout(1.0, 0.0, 0, 0)
+    with pytest.raises(mi.MimoseError):
+        m.set_dropout(0.1, 0.1, 0, 0)                            # attention-probability dropout: not available
     m.close()
 
 

@@ -174,6 +174,25 @@ def test_measured_peak_equals_simulated_peak_for_every_plan(name, B, L):
     m.close()
 
 
+def test_dropout_memory_is_in_the_backward_transient():
+    """Masked copies of the two branch gradients live in a layer's backward; nothing is kept from
+    the forward (the masks are regenerated), so a_l, b_l stay and w_l grows by 2 T H elements."""
+    wl, m = host_ctx("tiny")
+    n = wl.shape.n_layers
+    m.force_plan(0b01)
+    peak0, _ = m.dry_step(4, 40)
+    c0 = components_of(m)
+    m.set_dropout(0.1, 0.0, 1, 0)
+    for plan in (0, 0b01, 0b10, 0b11):
+        m.force_plan(plan)
+        peak1, _ = m.dry_step(4, 40)
+        c1 = components_of(m)
+        assert peak1 == op.simulate_peak(c1, plan)
+        assert c1.a == c0.a and c1.b == c0.b and c1.e == c0.e and c1.g == c0.g
+        assert [w1 - w0 for w0, w1 in zip(c0.w, c1.w)] == [2 * 4 * 40 * wl.shape.hidden * 4] * n
+    m.close()
+
+
 def test_components_are_polynomial_in_input_size():
     """Section 4.3: activation bytes are (at most) quadratic in the input size; with fused
     attention nothing of size L x L is stored, so here they are affine in x up to allocation
