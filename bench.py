@@ -55,7 +55,7 @@ def main():
     ap.add_argument("--cost-aware", action="store_true",
                     help="use the forward times collected in the sheltered steps inside Algorithm 1's buckets")
     ap.add_argument("--dropout", type=float, default=0.0,
-                    help="dropout probability of the hidden sites (embedding output, attention and feed-forward "
+                    help="dropout probability of the attention probabilities and of the hidden sites (embedding output, attention and feed-forward "
                          "block outputs), masks from the counter-based generator; 0 = off, the measured default")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 256 MiB element-wise copy kernels (reference for scaling FETCH_SIZE / WRITE_SIZE)")
@@ -96,7 +96,7 @@ def main():
     if update:
         m.optimizer_init(**adamw)
     if args.dropout > 0:
-        m.set_dropout(args.dropout, 0.0, wl.seed, 0)
+        m.set_dropout(args.dropout, args.dropout, wl.seed, 0)
 
     def iteration(t, l):
         r = m.train_step(t, l)

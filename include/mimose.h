@@ -152,7 +152,10 @@ int mimose_train_step_padded(mimose_ctx* ctx, const int32_t* tokens_host, const 
  * checkpointed and run again before its backward therefore meets the masks of its first run
  * (Section 2.2: recomputation must reproduce the dropped tensors), and nothing is stored.
  * first_step numbers the next iteration; every completed mimose_train_step adds one.
- * p_attn (dropout of the attention probabilities, site 4(l+1)) must be 0: not available.
+ * p_attn acts on the attention probabilities of every layer (site 4(l+1); element number
+ * ((b*heads + head)*L + query) * 4*ceil(L/4) + key, so that four neighbouring keys of a query
+ * share a block): the softmax normaliser counts every probability, the dropped ones leave the
+ * product with V.
  * Zero probabilities (the initial state) switch dropout off.  Errors: INVALID_ARG.
  */
 int mimose_set_dropout(mimose_ctx* ctx, float p_hidden, float p_attn, uint64_t seed,
@@ -285,16 +288,19 @@ int mimose_op_gelu_bwd(int32_t dtype, void* d, const void* pre, int64_t n, int32
 /* qkv [B*L, 3*H] (q | k | v, heads contiguous inside each) -> ctx [B*L, H], lse fp32 [B, h, L].
  * head_dim must be 32 or 64.  lengths: NULL, or device int32 [B] with 1 <= lengths[b] <= L (not
  * checked: the caller guarantees it): keys of sample b from lengths[b] on are padding and get
- * no weight. */
+ * no weight.  p_drop > 0: dropout of the probabilities with the masks mimose_set_dropout
+ * describes for (seed, site, step). */
 int mimose_op_attention_fwd(int32_t dtype, const void* qkv, void* ctx, float* lse,
                             const int32_t* lengths, int32_t B, int32_t L, int32_t n_heads,
-                            int32_t head_dim, int32_t causal, void* stream);
-/* dqkv from qkv, ctx, dctx, lse; delta: fp32 scratch [B, h, L]; lengths as in the forward (dK, dV
- * of padded keys are written as zeros). */
+                            int32_t head_dim, int32_t causal, float p_drop, uint64_t seed,
+                            uint32_t site, uint32_t step, void* stream);
+/* dqkv from qkv, ctx, dctx, lse; delta: fp32 scratch [B, h, L]; lengths and dropout as in the
+ * forward (dK, dV of padded keys are written as zeros). */
 int mimose_op_attention_bwd(int32_t dtype, const void* qkv, const void* ctx, const void* dctx,
                             const float* lse, float* delta, void* dqkv, const int32_t* lengths,
                             int32_t B, int32_t L, int32_t n_heads, int32_t head_dim,
-                            int32_t causal, void* stream);
+                            int32_t causal, float p_drop, uint64_t seed, uint32_t site,
+                            uint32_t step, void* stream);
 /* dst[n] = (resid ? resid[n] : 0) + mask * src[n] / (1-p) with the mask mimose_set_dropout
  * describes for (seed, site, step).  dst, src: storage type, or fp32 when io_f32; resid: storage
  * type or NULL; dst may be src. */

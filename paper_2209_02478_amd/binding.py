@@ -93,8 +93,10 @@ SIGNATURES = {
                                           _vp]),
     "mimose_op_partial_rows": (_i32, [_i32]),
     "mimose_op_gelu_bwd": (C.c_int, [_i32, _vp, _vp, _i64, _i32, _vp]),
-    "mimose_op_attention_fwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp]),
-    "mimose_op_attention_bwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp]),
+    "mimose_op_attention_fwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _f32, _u64, C.c_uint32,
+                                          C.c_uint32, _vp]),
+    "mimose_op_attention_bwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _f32,
+                                          _u64, C.c_uint32, C.c_uint32, _vp]),
     "mimose_op_softmax_xent": (C.c_int, [_i32, _vp, _i64, _vp, _vp, _vp, _i32, _i32, _i32, _vp]),
     "mimose_op_embed_fwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _f32, _i32, _vp]),
     "mimose_op_embed_bwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32, _i32, _i32, _i32, _vp]),
@@ -329,16 +331,17 @@ def mimose_op_gelu_bwd(dtype, d, pre, n, tanh_form, stream=None):
     _check(load_library().mimose_op_gelu_bwd(dtype, _ptr(d), _ptr(pre), n, tanh_form, _ptr(stream)))
 
 
-def mimose_op_attention_fwd(dtype, qkv, ctx_out, lse, B, L, n_heads, head_dim, causal, stream=None, lengths=None):
+def mimose_op_attention_fwd(dtype, qkv, ctx_out, lse, B, L, n_heads, head_dim, causal, stream=None, lengths=None,
+                            p_drop=0.0, seed=0, site=0, step=0):
     _check(load_library().mimose_op_attention_fwd(dtype, _ptr(qkv), _ptr(ctx_out), _ptr(lse), _ptr(lengths), B, L,
-                                                  n_heads, head_dim, causal, _ptr(stream)))
+                                                  n_heads, head_dim, causal, p_drop, seed, site, step, _ptr(stream)))
 
 
 def mimose_op_attention_bwd(dtype, qkv, ctx_in, dctx, lse, delta, dqkv, B, L, n_heads, head_dim, causal, stream=None,
-                            lengths=None):
+                            lengths=None, p_drop=0.0, seed=0, site=0, step=0):
     _check(load_library().mimose_op_attention_bwd(dtype, _ptr(qkv), _ptr(ctx_in), _ptr(dctx), _ptr(lse), _ptr(delta),
-                                                  _ptr(dqkv), _ptr(lengths), B, L, n_heads, head_dim, causal,
-                                                  _ptr(stream)))
+                                                  _ptr(dqkv), _ptr(lengths), B, L, n_heads, head_dim, causal, p_drop,
+                                                  seed, site, step, _ptr(stream)))
 
 
 def mimose_op_dropout(dtype, dst, src, io_f32, resid, n, p, seed, site, step, stream=None):

@@ -13,6 +13,7 @@
 //             delta_i = dO_i O_i;  dQ = dS K / sqrt(d), dK = dS^T Q / sqrt(d), dV = P^T dO
 #include "device_common.h"
 #include "kernels.h"
+#include "philox.h"
 
 namespace mk {
 
@@ -48,15 +49,15 @@ constexpr int kRowsPerBlock = 16;   // 4 waves x 4 rows
 
 // bf16, head size 64: MFMA kernels
 void attention_fwd_mfma(const void* qkv, void* ctx, float* lse, const int32_t* lens, int B, int L, int nh, int causal,
-                        hipStream_t st);
+                        const DropDesc& drop, hipStream_t st);
 void attention_bwd_mfma(const void* qkv, const void* dctx, const float* lse, const float* delta, void* dqkv,
-                        const int32_t* lens, int B, int L, int nh, int causal, hipStream_t st);
+                        const int32_t* lens, int B, int L, int nh, int causal, const DropDesc& drop, hipStream_t st);
 
 // qkv row stride is 3*H; head hh of token t: q at t*3H + hh*D, k at +H, v at +2H.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void attn_fwd_kernel(const T* __restrict__ qkv, T* __restrict__ ctx,
                                                        float* __restrict__ lse, const int32_t* __restrict__ lens,
-                                                       int L, int nh, int causal) {
+                                                       int L, int nh, int causal, DropDesc drop) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int bh = blockIdx.y, b = bh / nh, hh = bh - b * nh;
   const int H = nh * D;
@@ -78,17 +79,18 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const T* __restrict__ qkv
       const float mnew = fmaxf(m, wave_max(s));
       const float p = j < jmax ? expf(s - mnew) : 0.f;
       const float alpha = expf(m - mnew);
-      l = l * alpha + wave_sum(p);
+      l = l * alpha + wave_sum(p);                  // the normaliser counts every probability
       o *= alpha;
+      const float pd = drop.thr && j < jmax && !attn_keep(drop, (int64_t)bh * L + i, (L + 3) >> 2, j) ? 0.f : p;
       const int cnt = min(64, jmax - j0);
       const T* vcol = base + (int64_t)j0 * ld3 + 2 * H + (lane < D ? lane : 0);
       for (int jj = 0; jj < cnt; ++jj) {
-        const float pj = __shfl(p, jj, 64);
+        const float pj = __shfl(pd, jj, 64);
         o = fmaf(pj, ld<T>(vcol + (int64_t)jj * ld3), o);
       }
       m = mnew;
     }
-    if (lane < D) st<T>(ctx + ((int64_t)b * L + i) * H + hh * D + lane, o / l);
+    if (lane < D) st<T>(ctx + ((int64_t)b * L + i) * H + hh * D + lane, o * (drop.scale / l));
     if (lane == 0) lse[(int64_t)bh * L + i] = m + logf(l);
   }
 }
@@ -112,7 +114,8 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const T* __restrict__ qkv, const T* __restrict__ dctx,
                                                           const float* __restrict__ lse,
                                                           const float* __restrict__ delta, T* __restrict__ dqkv,
-                                                          const int32_t* __restrict__ lens, int L, int nh, int causal) {
+                                                          const int32_t* __restrict__ lens, int L, int nh, int causal,
+                                                          DropDesc drop) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int bh = blockIdx.y, b = bh / nh, hh = bh - b * nh;
   const int H = nh * D;
@@ -135,7 +138,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const T* __restrict__ 
       if (j < jmax) {
         const float s = scale * dot_row<T, D>(base + (int64_t)j * ld3 + H, q);
         const float p = expf(s - lse_i);
-        const float dp = dot_row<T, D>(base + (int64_t)j * ld3 + 2 * H, go);
+        float dp = dot_row<T, D>(base + (int64_t)j * ld3 + 2 * H, go);
+        if (drop.thr) dp = attn_keep(drop, (int64_t)bh * L + i, (L + 3) >> 2, j) ? dp * drop.scale : 0.f;
         ds = p * (dp - delta_i);
       }
       const int cnt = min(64, jmax - j0);
@@ -150,7 +154,8 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const T* __restrict__ qkv, const T* __restrict__ dctx,
                                                            const float* __restrict__ lse,
                                                            const float* __restrict__ delta, T* __restrict__ dqkv,
-                                                           const int32_t* __restrict__ lens, int L, int nh, int causal) {
+                                                           const int32_t* __restrict__ lens, int L, int nh, int causal,
+                                                           DropDesc drop) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int bh = blockIdx.y, b = bh / nh, hh = bh - b * nh;
   const int H = nh * D;
@@ -173,8 +178,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const T* __restrict__
       if (i < L) {
         const float s = scale * dot_row<T, D>(base + (int64_t)i * ld3, k);
         p = expf(s - lse[(int64_t)bh * L + i]);
-        const float dp = dot_row<T, D>(gobase + (int64_t)i * H, v);
+        float dp = dot_row<T, D>(gobase + (int64_t)i * H, v);
+        float pd = p;                                   // what multiplied V in the forward
+        if (drop.thr) {
+          const bool keep = attn_keep(drop, (int64_t)bh * L + i, (L + 3) >> 2, j);
+          dp = keep ? dp * drop.scale : 0.f;
+          pd = keep ? p * drop.scale : 0.f;
+        }
         ds = p * (dp - delta[(int64_t)bh * L + i]);
+        p = pd;
       }
       const int cnt = min(64, L - i0);
       const int cl = lane < D ? lane : 0;
@@ -195,21 +207,22 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const T* __restrict__
 
 template <typename T, int D>
 static void fwd_t(const void* qkv, void* ctx, float* lse, const int32_t* lens, int B, int L, int nh, int causal,
-                  hipStream_t st) {
+                  const DropDesc& drop, hipStream_t st) {
   dim3 grid((L + kRowsPerBlock - 1) / kRowsPerBlock, B * nh);
-  hipLaunchKernelGGL((attn_fwd_kernel<T, D>), grid, dim3(256), 0, st, (const T*)qkv, (T*)ctx, lse, lens, L, nh, causal);
+  hipLaunchKernelGGL((attn_fwd_kernel<T, D>), grid, dim3(256), 0, st, (const T*)qkv, (T*)ctx, lse, lens, L, nh, causal,
+                     drop);
 }
 template <typename T, int D>
 static void bwd_t(const void* qkv, const void* ctx, const void* dctx, const float* lse, float* delta, void* dqkv,
-                  const int32_t* lens, int B, int L, int nh, int causal, hipStream_t st) {
+                  const int32_t* lens, int B, int L, int nh, int causal, const DropDesc& drop, hipStream_t st) {
   int64_t n = (int64_t)B * L * nh;
   hipLaunchKernelGGL((attn_delta_kernel<T, D>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
                      (const T*)ctx, (const T*)dctx, delta, B, L, nh);
   dim3 grid((L + kRowsPerBlock - 1) / kRowsPerBlock, B * nh);
   hipLaunchKernelGGL((attn_bwd_dq_kernel<T, D>), grid, dim3(256), 0, st, (const T*)qkv, (const T*)dctx, lse,
-                     delta, (T*)dqkv, lens, L, nh, causal);
+                     delta, (T*)dqkv, lens, L, nh, causal, drop);
   hipLaunchKernelGGL((attn_bwd_dkv_kernel<T, D>), grid, dim3(256), 0, st, (const T*)qkv, (const T*)dctx, lse,
-                     delta, (T*)dqkv, lens, L, nh, causal);
+                     delta, (T*)dqkv, lens, L, nh, causal, drop);
 }
 
 #define DISPATCH_TD(CALL_F32, CALL_BF16)                         \
@@ -220,28 +233,29 @@ static void bwd_t(const void* qkv, const void* ctx, const void* dctx, const floa
   }
 
 void attention_fwd(int dtype, const void* qkv, void* ctx, float* lse, const int32_t* lens, int B, int L, int nh, int d,
-                   int causal, hipStream_t st) {
+                   int causal, const DropDesc& drop, hipStream_t st) {
   if (B * L <= 0) return;
-  if (dtype == BF16 && d == 64) { attention_fwd_mfma(qkv, ctx, lse, lens, B, L, nh, causal, st); return; }
-#define F32_(DD) fwd_t<float, DD>(qkv, ctx, lse, lens, B, L, nh, causal, st)
-#define BF_(DD) fwd_t<bf16_t, DD>(qkv, ctx, lse, lens, B, L, nh, causal, st)
+  if (dtype == BF16 && d == 64) { attention_fwd_mfma(qkv, ctx, lse, lens, B, L, nh, causal, drop, st); return; }
+#define F32_(DD) fwd_t<float, DD>(qkv, ctx, lse, lens, B, L, nh, causal, drop, st)
+#define BF_(DD) fwd_t<bf16_t, DD>(qkv, ctx, lse, lens, B, L, nh, causal, drop, st)
   DISPATCH_TD(F32_, BF_)
 #undef F32_
 #undef BF_
 }
 
 void attention_bwd(int dtype, const void* qkv, const void* ctx, const void* dctx, const float* lse, float* delta,
-                   void* dqkv, const int32_t* lens, int B, int L, int nh, int d, int causal, hipStream_t st) {
+                   void* dqkv, const int32_t* lens, int B, int L, int nh, int d, int causal, const DropDesc& drop,
+                   hipStream_t st) {
   if (B * L <= 0) return;
   if (dtype == BF16 && d == 64) {
     int64_t n = (int64_t)B * L * nh;
     hipLaunchKernelGGL((attn_delta_kernel<bf16_t, 64>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
                        (const bf16_t*)ctx, (const bf16_t*)dctx, delta, B, L, nh);
-    attention_bwd_mfma(qkv, dctx, lse, delta, dqkv, lens, B, L, nh, causal, st);
+    attention_bwd_mfma(qkv, dctx, lse, delta, dqkv, lens, B, L, nh, causal, drop, st);
     return;
   }
-#define F32_(DD) bwd_t<float, DD>(qkv, ctx, dctx, lse, delta, dqkv, lens, B, L, nh, causal, st)
-#define BF_(DD) bwd_t<bf16_t, DD>(qkv, ctx, dctx, lse, delta, dqkv, lens, B, L, nh, causal, st)
+#define F32_(DD) bwd_t<float, DD>(qkv, ctx, dctx, lse, delta, dqkv, lens, B, L, nh, causal, drop, st)
+#define BF_(DD) bwd_t<bf16_t, DD>(qkv, ctx, dctx, lse, delta, dqkv, lens, B, L, nh, causal, drop, st)
   DISPATCH_TD(F32_, BF_)
 #undef F32_
 #undef BF_

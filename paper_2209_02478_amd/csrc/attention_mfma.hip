@@ -18,6 +18,7 @@
 // No atomics: dQ comes from a kernel that owns query rows, dK/dV from one that owns key rows.
 #include "device_common.h"
 #include "kernels.h"
+#include "philox.h"
 
 namespace mk {
 
@@ -118,10 +119,10 @@ __device__ __forceinline__ void store_rows(bf16_t* dst, const f32x16 (&acc)[2], 
 }  // namespace
 
 // ------------------------------------------------------------------ forward
-template <bool CAUSAL>
+template <bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx,
                                                      float* __restrict__ lse, const int32_t* __restrict__ lens,
-                                                     int L, int nh) {
+                                                     int L, int nh, DropDesc drop) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[TK][LDT];   // [key][d]
   __shared__ __attribute__((aligned(16))) bf16_t Vt[D][LDT];    // [d][key]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, ql = lane & 31, h = lane >> 5;
@@ -185,8 +186,21 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(const bf16_t* __restrict
         rs += p;
       }
     rs += __shfl_xor(rs, 32, 64);
-    l = l * alpha + rs;
+    l = l * alpha + rs;                               // the normaliser counts every probability
     m = mnew;
+    if (DROP) {                                       // dropped ones leave the P V product; the scale waits for the end
+      const int64_t row = (int64_t)bh * L + qc;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const uint4 w = attn_drop_words(drop, row, (L + 3) >> 2, k0 + 32 * kb + 8 * g + 4 * h);
+          if (w.x < drop.thr) s[kb][4 * g] = 0.f;
+          if (w.y < drop.thr) s[kb][4 * g + 1] = 0.f;
+          if (w.z < drop.thr) s[kb][4 * g + 2] = 0.f;
+          if (w.w < drop.thr) s[kb][4 * g + 3] = 0.f;
+        }
+    }
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
@@ -202,17 +216,17 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(const bf16_t* __restrict
       }
   }
   if (qi < L) {
-    store_rows(ctx + ((int64_t)b * L + qi) * H + hh * D, o, h, 1.f / l);
+    store_rows(ctx + ((int64_t)b * L + qi) * H + hh * D, o, h, (DROP ? drop.scale : 1.f) / l);
     if (h == 0) lse[(int64_t)bh * L + qi] = m * scale + __logf(l);
   }
 }
 
 // ------------------------------------------------------------------ dQ
-template <bool CAUSAL>
+template <bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
                                                         const float* __restrict__ lse, const float* __restrict__ delta,
                                                         bf16_t* __restrict__ dqkv, const int32_t* __restrict__ lens, int L,
-                                                        int nh) {
+                                                        int nh, DropDesc drop) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[TK][LDT];   // [key][d]
   __shared__ __attribute__((aligned(16))) bf16_t Kt[D][LDT];    // [d][key]
   __shared__ __attribute__((aligned(16))) bf16_t Vs[TK][LDT];   // [key][d]
@@ -257,6 +271,17 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(const bf16_t* __restr
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(&Ks[32 * kb + ql][16 * kk + 8 * h]), qf[kk], s, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_frag(&Vs[32 * kb + ql][16 * kk + 8 * h]), gf[kk], dp, 0, 0, 0);
       }
+      if (DROP) {                                     // d(P) of a dropped probability is zero, of a kept one scaled
+        const int64_t row = (int64_t)bh * L + qc;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const uint4 w = attn_drop_words(drop, row, (L + 3) >> 2, k0 + 32 * kb + 8 * g + 4 * h);
+          dp[4 * g] = w.x < drop.thr ? 0.f : dp[4 * g] * drop.scale;
+          dp[4 * g + 1] = w.y < drop.thr ? 0.f : dp[4 * g + 1] * drop.scale;
+          dp[4 * g + 2] = w.z < drop.thr ? 0.f : dp[4 * g + 2] * drop.scale;
+          dp[4 * g + 3] = w.w < drop.thr ? 0.f : dp[4 * g + 3] * drop.scale;
+        }
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = fast_exp2(fmaf(s[r], c2, nlse_q)) * (dp[r] - delta_q);
       if (CAUSAL || k0 + TK > Lk) {
@@ -279,11 +304,11 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(const bf16_t* __restr
 }
 
 // ------------------------------------------------------------------ dK, dV
-template <bool CAUSAL>
+template <bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(256, 2) void fa_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
                                                          const float* __restrict__ lse, const float* __restrict__ delta,
                                                          bf16_t* __restrict__ dqkv, const int32_t* __restrict__ lens, int L,
-                                                        int nh) {
+                                                        int nh, DropDesc drop) {
   __shared__ __attribute__((aligned(16))) bf16_t Qs[TK][LDT];   // [query][d]
   __shared__ __attribute__((aligned(16))) bf16_t Qt[D][LDT];    // [d][query]
   __shared__ __attribute__((aligned(16))) bf16_t Gs[TK][LDT];   // dO [query][d]
@@ -346,12 +371,35 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dkv_kernel(const bf16_t* __rest
         const int qq = 32 * qb + 8 * g + 4 * h;
         const float4 nl = *(const float4*)&lse_s[qq], dl = *(const float4*)&delta_s[qq];
         const float nls[4] = {nl.x, nl.y, nl.z, nl.w}, dls[4] = {dl.x, dl.y, dl.z, dl.w};
+        // Dropout: this lane holds one key and four queries; a generator block covers four keys
+        // of one query.  The four lanes of a quad (four neighbouring keys) each make the block of
+        // one of the four queries and pass its words round: in turn t a lane receives, from the
+        // lane t places on, the word of its own key for that lane's query.
+        bool keep[4] = {true, true, true, true};
+        if (DROP) {
+          const int c = lane & 3;
+          const int qmine = min(q0 + qq + c, L - 1);
+          const uint4 w = attn_drop_words(drop, (int64_t)bh * L + qmine, (L + 3) >> 2, ki & ~3);
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const uint32_t got = __shfl(pick_word(w, (c - t) & 3), (lane & ~3) | ((c + t) & 3), 64);
+            const bool k = got >= drop.thr;
+            const int e = (c + t) & 3;
+            keep[0] = e == 0 ? k : keep[0]; keep[1] = e == 1 ? k : keep[1];
+            keep[2] = e == 2 ? k : keep[2]; keep[3] = e == 3 ? k : keep[3];
+          }
+        }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = 4 * g + e;
           const float p = fast_exp2(fmaf(s[r], c2, nls[e]));
-          s[r] = p;
-          dp[r] = p * (dp[r] - dls[e]);
+          if (DROP) {
+            s[r] = keep[e] ? p * drop.scale : 0.f;                         // what multiplied V in the forward
+            dp[r] = p * ((keep[e] ? dp[r] * drop.scale : 0.f) - dls[e]);
+          } else {
+            s[r] = p;
+            dp[r] = p * (dp[r] - dls[e]);
+          }
         }
       }
       if (CAUSAL || q0 + TK > L) {
@@ -381,22 +429,25 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dkv_kernel(const bf16_t* __rest
 }
 
 void attention_fwd_mfma(const void* qkv, void* ctx, float* lse, const int32_t* lens, int B, int L, int nh, int causal,
-                        hipStream_t st) {
+                        const DropDesc& drop, hipStream_t st) {
   dim3 grid((L + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, B * nh);
-  if (causal) hipLaunchKernelGGL(fa_fwd_kernel<true>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (bf16_t*)ctx, lse, lens, L, nh);
-  else hipLaunchKernelGGL(fa_fwd_kernel<false>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (bf16_t*)ctx, lse, lens, L, nh);
+#define FWD_(C, D) hipLaunchKernelGGL((fa_fwd_kernel<C, D>), grid, dim3(256), 0, st, (const bf16_t*)qkv, (bf16_t*)ctx, lse, lens, L, nh, drop)
+  if (drop.thr) { if (causal) FWD_(true, true); else FWD_(false, true); }
+  else { if (causal) FWD_(true, false); else FWD_(false, false); }
+#undef FWD_
 }
 
 void attention_bwd_mfma(const void* qkv, const void* dctx, const float* lse, const float* delta, void* dqkv,
-                        const int32_t* lens, int B, int L, int nh, int causal, hipStream_t st) {
+                        const int32_t* lens, int B, int L, int nh, int causal, const DropDesc& drop, hipStream_t st) {
   dim3 grid((L + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, B * nh);
-  if (causal) {
-    hipLaunchKernelGGL(fa_bwd_dq_kernel<true>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, lens, L, nh);
-    hipLaunchKernelGGL(fa_bwd_dkv_kernel<true>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, lens, L, nh);
-  } else {
-    hipLaunchKernelGGL(fa_bwd_dq_kernel<false>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, lens, L, nh);
-    hipLaunchKernelGGL(fa_bwd_dkv_kernel<false>, grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, lens, L, nh);
-  }
+#define BWD_(C, D)                                                                                               \
+  hipLaunchKernelGGL((fa_bwd_dq_kernel<C, D>), grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, \
+                     delta, (bf16_t*)dqkv, lens, L, nh, drop);                                                    \
+  hipLaunchKernelGGL((fa_bwd_dkv_kernel<C, D>), grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, \
+                     delta, (bf16_t*)dqkv, lens, L, nh, drop)
+  if (drop.thr) { if (causal) { BWD_(true, true); } else { BWD_(false, true); } }
+  else { if (causal) { BWD_(true, false); } else { BWD_(false, false); } }
+#undef BWD_
 }
 
 }  // namespace mk

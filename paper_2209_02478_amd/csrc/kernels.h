@@ -56,12 +56,13 @@ void layernorm_bwd(int dtype, const void* dy, bool dy_f32, const void* x, bool x
 int partial_rows(int T);
 void gelu_bwd(int dtype, void* d, const void* pre, int64_t n, int tanh_form, hipStream_t st);
 // lens (optional, device, [B]): real tokens per sample of a padded batch; keys from lens[b] on get
-// no weight.  nullptr: every sample fills its row.
+// no weight.  nullptr: every sample fills its row.  drop: dropout of the probabilities (the
+// softmax normaliser counts all of them; ctx = (mask * scale * P) V).
 void attention_fwd(int dtype, const void* qkv, void* ctx, float* lse, const int32_t* lens, int B, int L, int nh, int d,
-                   int causal, hipStream_t st);
+                   int causal, const DropDesc& drop, hipStream_t st);
 void attention_bwd(int dtype, const void* qkv, const void* ctx, const void* dctx, const float* lse,
                    float* delta, void* dqkv, const int32_t* lens, int B, int L, int nh, int d, int causal,
-                   hipStream_t st);
+                   const DropDesc& drop, hipStream_t st);
 void softmax_xent(int dtype, void* logits, int64_t ld, const int32_t* labels, float* row_loss,
                   float* loss, int T, int V, int n_valid, hipStream_t st);
 void embed_fwd(int dtype, const int32_t* ids, const void* tok, const void* pos, const void* gamma,

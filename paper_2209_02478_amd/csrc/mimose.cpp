@@ -103,7 +103,7 @@ struct mimose_ctx {
   int64_t forced_plan = -1;
   int plan_mode = MIMOSE_PLAN_INPUT_AWARE;
   // dropout: probability of the hidden sites, seed, number of the next iteration
-  float p_hidden = 0.f;
+  float p_hidden = 0.f, p_attn = 0.f;
   uint64_t drop_seed = 0, drop_step = 0;
   // parameter update (Section 2.1: the iteration ends with it; its state is part of the
   // input-independent memory of Section 3.1)
@@ -267,9 +267,10 @@ class Step {
   // projection, 4(l+1)+2 the feed-forward block's output (4(l+1) is kept for the attention
   // probabilities).
   bool drop_on() const { return c_->p_hidden > 0.f; }
-  mk::DropDesc drop_desc(uint32_t site) const {
+  mk::DropDesc drop_desc(uint32_t site, bool attn = false) const {
     mk::DropDesc d;
-    const double p = (double)c_->p_hidden;
+    const double p = (double)(attn ? c_->p_attn : c_->p_hidden);
+    if (p <= 0.0) return d;
     d.thr = (uint32_t)std::min(std::floor(p * 4294967296.0 + 0.5), 4294967295.0);
     d.scale = (float)(1.0 / (1.0 - p));
     d.k0 = (uint32_t)c_->drop_seed; d.k1 = (uint32_t)(c_->drop_seed >> 32);
@@ -416,7 +417,8 @@ void Step::layer_forward(int l, LayerActs& A) {
   linear(a, H, p.wqkv, p.bqkv, A.qkv, 3 * H, 3 * H);
   {
     Timed t(this, MIMOSE_K_ATTN_FWD, 4.0 * T_ * L_ * H * (f_.causal ? 0.5 : 1.0));
-    if (!dry_) mk::attention_fwd(dt_, A.qkv, A.ctx, A.lse, lens_, B_, L_, nh, d, f_.causal, st_);
+    if (!dry_)
+      mk::attention_fwd(dt_, A.qkv, A.ctx, A.lse, lens_, B_, L_, nh, d, f_.causal, drop_desc(4 * (uint32_t)(l + 1), true), st_);
   }
   // with dropout the product lands in the sum's buffer and an element-wise pass makes
   // sum = residual + dropout(product) in place; without it the residual rides in the epilogue
@@ -480,7 +482,9 @@ void Step::layer_backward(int l, LayerActs& A) {
   float* delta = (float*)ar.alloc((uint64_t)B_ * nh * L_ * 4);
   {
     Timed t(this, MIMOSE_K_ATTN_BWD, 8.0 * T_ * L_ * H * (f_.causal ? 0.5 : 1.0));
-    if (!dry_) mk::attention_bwd(dt_, A.qkv, A.ctx, dctx, A.lse, delta, dqkv, lens_, B_, L_, nh, d, f_.causal, st_);
+    if (!dry_)
+      mk::attention_bwd(dt_, A.qkv, A.ctx, dctx, A.lse, delta, dqkv, lens_, B_, L_, nh, d, f_.causal,
+                        drop_desc(4 * (uint32_t)(l + 1), true), st_);
   }
   const void* a = f_.pre_ln ? A.n1 : A.x;
   wgrad(dqkv, 3 * H, 3 * H, a, H, p.wqkv, p.bqkv);
@@ -897,8 +901,8 @@ int mimose_set_dropout(mimose_ctx* c, float p_hidden, float p_attn, uint64_t see
   if (!c) return MIMOSE_ERR_INVALID_ARG;
   if (!(p_hidden >= 0.f) || !(p_hidden < 1.f) || !(p_attn >= 0.f) || !(p_attn < 1.f))
     return fail(c, MIMOSE_ERR_INVALID_ARG, "dropout probabilities must lie in [0, 1)");
-  if (p_attn > 0.f) return fail(c, MIMOSE_ERR_INVALID_ARG, "dropout of the attention probabilities is not available");
   c->p_hidden = p_hidden;
+  c->p_attn = p_attn;
   c->drop_seed = seed;
   c->drop_step = first_step;
   return MIMOSE_OK;

@@ -55,31 +55,43 @@ int mimose_op_gelu_bwd(int32_t dtype, void* d, const void* pre, int64_t n, int32
   return done();
 }
 
+static bool bad_p(float p) { return !(p >= 0.f) || !(p < 1.f); }
+static mk::DropDesc make_desc(float p, uint64_t seed, uint32_t site, uint32_t step) {
+  mk::DropDesc d;
+  if (p <= 0.f) return d;
+  d.thr = (uint32_t)std::min(std::floor((double)p * 4294967296.0 + 0.5), 4294967295.0);
+  d.scale = (float)(1.0 / (1.0 - (double)p));
+  d.k0 = (uint32_t)seed; d.k1 = (uint32_t)(seed >> 32);
+  d.site = site; d.step = step;
+  return d;
+}
+
 int mimose_op_attention_fwd(int32_t dtype, const void* qkv, void* ctx, float* lse, const int32_t* lengths, int32_t B,
-                            int32_t L, int32_t nh, int32_t d, int32_t causal, void* stream) {
-  if (bad_dtype(dtype) || !qkv || !ctx || !lse || B < 0 || L < 0 || nh < 1 || bad_head(d)) return MIMOSE_ERR_INVALID_ARG;
-  mk::attention_fwd(dtype, qkv, ctx, lse, lengths, B, L, nh, d, causal, (hipStream_t)stream);
+                            int32_t L, int32_t nh, int32_t d, int32_t causal, float p_drop, uint64_t seed,
+                            uint32_t site, uint32_t step, void* stream) {
+  if (bad_dtype(dtype) || !qkv || !ctx || !lse || B < 0 || L < 0 || nh < 1 || bad_head(d) || bad_p(p_drop))
+    return MIMOSE_ERR_INVALID_ARG;
+  mk::attention_fwd(dtype, qkv, ctx, lse, lengths, B, L, nh, d, causal, make_desc(p_drop, seed, site, step),
+                    (hipStream_t)stream);
   return done();
 }
 
 int mimose_op_attention_bwd(int32_t dtype, const void* qkv, const void* ctx, const void* dctx, const float* lse,
                             float* delta, void* dqkv, const int32_t* lengths, int32_t B, int32_t L, int32_t nh,
-                            int32_t d, int32_t causal, void* stream) {
-  if (bad_dtype(dtype) || !qkv || !ctx || !dctx || !lse || !delta || !dqkv || B < 0 || L < 0 || nh < 1 || bad_head(d))
+                            int32_t d, int32_t causal, float p_drop, uint64_t seed, uint32_t site, uint32_t step,
+                            void* stream) {
+  if (bad_dtype(dtype) || !qkv || !ctx || !dctx || !lse || !delta || !dqkv || B < 0 || L < 0 || nh < 1 || bad_head(d) ||
+      bad_p(p_drop))
     return MIMOSE_ERR_INVALID_ARG;
-  mk::attention_bwd(dtype, qkv, ctx, dctx, lse, delta, dqkv, lengths, B, L, nh, d, causal, (hipStream_t)stream);
+  mk::attention_bwd(dtype, qkv, ctx, dctx, lse, delta, dqkv, lengths, B, L, nh, d, causal,
+                    make_desc(p_drop, seed, site, step), (hipStream_t)stream);
   return done();
 }
 
 int mimose_op_dropout(int32_t dtype, void* dst, const void* src, int32_t io_f32, const void* resid, int64_t n, float p,
                       uint64_t seed, uint32_t site, uint32_t step, void* stream) {
-  if (bad_dtype(dtype) || !dst || !src || n < 0 || !(p >= 0.f) || !(p < 1.f)) return MIMOSE_ERR_INVALID_ARG;
-  mk::DropDesc d;
-  d.thr = (uint32_t)std::min(std::floor((double)p * 4294967296.0 + 0.5), 4294967295.0);
-  d.scale = (float)(1.0 / (1.0 - (double)p));
-  d.k0 = (uint32_t)seed; d.k1 = (uint32_t)(seed >> 32);
-  d.site = site; d.step = step;
-  mk::dropout_apply(dtype, dst, src, io_f32 != 0, resid, n, d, (hipStream_t)stream);
+  if (bad_dtype(dtype) || !dst || !src || n < 0 || bad_p(p)) return MIMOSE_ERR_INVALID_ARG;
+  mk::dropout_apply(dtype, dst, src, io_f32 != 0, resid, n, make_desc(p, seed, site, step), (hipStream_t)stream);
   return done();
 }
 

@@ -32,4 +32,17 @@ __device__ __forceinline__ uint4 drop_words(const DropDesc& d, uint64_t block) {
   return philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), d.site, d.step, d.k0, d.k1);
 }
 
+// Attention probabilities [B, nh, L, L]: every row of L keys is padded to a multiple of four, so
+// four neighbouring keys of one query share a block whatever L is:
+//   block = row * ceil(L / 4) + key / 4,  row = (b * nh + h) * L + query,  word = key % 4.
+__device__ __forceinline__ uint4 attn_drop_words(const DropDesc& d, int64_t row, int L4q, int key) {
+  return drop_words(d, (uint64_t)row * (uint64_t)L4q + (uint64_t)(key >> 2));
+}
+__device__ __forceinline__ uint32_t pick_word(const uint4& w, int i) {
+  return i == 0 ? w.x : i == 1 ? w.y : i == 2 ? w.z : w.w;
+}
+__device__ __forceinline__ bool attn_keep(const DropDesc& d, int64_t row, int L4q, int key) {
+  return pick_word(attn_drop_words(d, row, L4q, key), key & 3) >= d.thr;
+}
+
 }  // namespace mk

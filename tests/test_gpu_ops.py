@@ -212,15 +212,20 @@ def test_gelu_bwd(dtype, form):
 
 
 # ---------------------------------------------------------------- attention
-def attention_case(dtype, B, L, nh, d, causal, seed, lengths=None):
+def attention_case(dtype, B, L, nh, d, causal, seed, lengths=None, p_drop=0.0):
     rng = np.random.default_rng(seed)
+    keep, kw = None, {}
+    if p_drop:
+        from oracle import philox as ph
+        kw = dict(p_drop=float(np.float32(p_drop)), seed=0xABCDEF0123456789, site=4 * 3, step=77)
+        keep = ph.keep_scale(ph.attn_index(B, nh, L), kw["p_drop"], kw["seed"], kw["site"], kw["step"])
     lens_dev = None if lengths is None else torch.tensor(lengths, dtype=torch.int32, device=DEV)
     H = nh * d
     qkv = rng.standard_normal((B * L, 3 * H)).astype(np.float32)
     dctx = rng.standard_normal((B * L, H)).astype(np.float32)
     qq = quant(qkv, dtype)
     q, k, v = (om.split_heads(qq[:, i * H:(i + 1) * H], B, L, nh) for i in range(3))
-    o, p = om.attention_fwd(q, k, v, causal, lengths=lengths)
+    o, p = om.attention_fwd(q, k, v, causal, lengths=lengths, keep=keep)
     ctx_ref = om.merge_heads(o)
     s = (q @ k.transpose(0, 1, 3, 2)) / np.sqrt(d)
     if causal:
@@ -231,7 +236,7 @@ def attention_case(dtype, B, L, nh, d, causal, seed, lengths=None):
     dqkv_dev = dev(qkv, dtype)
     ctx = torch.zeros((B * L, H), dtype=dqkv_dev.dtype, device=DEV)
     lse = torch.zeros(B * nh * L, dtype=torch.float32, device=DEV)
-    mi.mimose_op_attention_fwd(dtype, dqkv_dev, ctx, lse, B, L, nh, d, causal, lengths=lens_dev)
+    mi.mimose_op_attention_fwd(dtype, dqkv_dev, ctx, lse, B, L, nh, d, causal, lengths=lens_dev, **kw)
     sync()
     if dtype == 0:
         close(host(ctx), ctx_ref, dtype, k=3.0)
@@ -244,12 +249,12 @@ def attention_case(dtype, B, L, nh, d, causal, seed, lengths=None):
     # backward consumes the stored (rounded) forward output, like the training step does
     ctx_q = host(ctx)
     do = om.split_heads(quant(dctx, dtype), B, L, nh)
-    dq, dk, dv = om.attention_bwd(do, q, k, v, p)
+    dq, dk, dv = om.attention_bwd(do, q, k, v, p, keep)
     ref = np.concatenate([om.merge_heads(dq), om.merge_heads(dk), om.merge_heads(dv)], axis=1)
     ddctx = dev(dctx, dtype)
     delta = torch.zeros(B * nh * L, dtype=torch.float32, device=DEV)
     out = torch.zeros_like(dqkv_dev)
-    mi.mimose_op_attention_bwd(dtype, dqkv_dev, ctx, ddctx, lse, delta, out, B, L, nh, d, causal, lengths=lens_dev)
+    mi.mimose_op_attention_bwd(dtype, dqkv_dev, ctx, ddctx, lse, delta, out, B, L, nh, d, causal, lengths=lens_dev, **kw)
     sync()
     got = host(out)
     if lengths is not None:                                  # dK, dV of padded keys: exact zeros
@@ -278,6 +283,16 @@ def test_attention(dtype, causal, B, L, nh, d):
                                             (333, 2, 64, [5, 333, 128, 129]), (17, 1, 64, [17, 16])])
 def test_attention_padded(dtype, causal, L, nh, d, lengths):
     attention_case(dtype, len(lengths), L, nh, d, causal, seed=L + 7, lengths=lengths)
+
+
+# dropout of the probabilities: the kept set is the oracle's (integer comparisons of generator
+# words), so the usual tolerances apply; lengths off the 4-key grid, several key tiles, padding
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("causal", [0, 1])
+@pytest.mark.parametrize("B,L,nh,d,lengths", [(2, 70, 2, 32, None), (1, 200, 3, 64, None), (2, 333, 2, 64, None),
+                                              (3, 5, 1, 64, None), (2, 130, 2, 64, [130, 61])])
+def test_attention_dropout(dtype, causal, B, L, nh, d, lengths):
+    attention_case(dtype, B, L, nh, d, causal, seed=L + 11, lengths=lengths, p_drop=0.2)
 
 
 # ---------------------------------------------------------------- softmax cross-entropy

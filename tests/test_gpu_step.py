@@ -231,7 +231,7 @@ def test_dropout_parity_and_replay(name):
     shape = SMALL[name]
     fp32 = shape.dtype == "fp32"
     n = shape.n_layers
-    p = float(np.float32(0.15))
+    p, pa = float(np.float32(0.15)), float(np.float32(0.1))
     seed = 0xC0FFEE1234567
     params = synthdata.make_params(shape, 81, perturb=True)
     tokens, labels = synthdata.make_batch(shape, 4, 33, 82)
@@ -242,13 +242,13 @@ def test_dropout_parity_and_replay(name):
     plain_G = m.grads()
 
     def run(step, plan):
-        m.set_dropout(p, 0.0, seed, step)
+        m.set_dropout(p, pa, seed, step)
         m.force_plan(plan)
         loss, peak, _ = m.train_step(tokens, labels)
         return loss, peak, m.grads()
 
     loss0, peak0, G0 = run(5, 0)
-    ref_loss, RG = oracle_step_dropout(shape, params, tokens, labels, om.Dropout(p, 0.0, seed, 5))
+    ref_loss, RG = oracle_step_dropout(shape, params, tokens, labels, om.Dropout(p, pa, seed, 5))
     assert abs(loss0 - ref_loss) <= (1e-4 if fp32 else 1e-2) * abs(ref_loss)
     for k, ref in RG.items():
         assert rel_l2(G0[k], ref) <= (1e-3 if fp32 else 2e-2), k
@@ -259,17 +259,17 @@ def test_dropout_parity_and_replay(name):
         for k in G0:
             assert np.array_equal(G0[k], G[k]), (plan, k)
     # the library counts iterations itself: the step after 5 is 6
-    m.set_dropout(p, 0.0, seed, 5)
+    m.set_dropout(p, pa, seed, 5)
     m.force_plan(0)
     m.train_step(tokens, labels)
     loss6, _, _ = m.train_step(tokens, labels)
-    ref6, _ = oracle_step_dropout(shape, params, tokens, labels, om.Dropout(p, 0.0, seed, 6))
+    ref6, _ = oracle_step_dropout(shape, params, tokens, labels, om.Dropout(p, pa, seed, 6))
     assert loss6 != loss0 and abs(loss6 - ref6) <= (1e-4 if fp32 else 1e-2) * abs(ref6)
     # padded batch and dropout together
     tk, lb, lens = synthdata.make_padded_batch(shape, [20, 7, 13], 83)
-    m.set_dropout(p, 0.0, seed, 9)
+    m.set_dropout(p, pa, seed, 9)
     lossp, _, _ = m.train_step(tk, lb, lengths=lens)
-    refp, RGp = oracle_step_dropout(shape, params, tk, lb, om.Dropout(p, 0.0, seed, 9), lens)
+    refp, RGp = oracle_step_dropout(shape, params, tk, lb, om.Dropout(p, pa, seed, 9), lens)
     assert abs(lossp - refp) <= (1e-4 if fp32 else 1e-2) * abs(refp)
     Gp = m.grads()
     for k, ref in RGp.items():
@@ -283,7 +283,7 @@ def test_dropout_parity_and_replay(name):
     with pytest.raises(mi.MimoseError):
         m.set_dropout(1.0, 0.0, 0, 0)
     with pytest.raises(mi.MimoseError):
-        m.set_dropout(0.1, 0.1, 0, 0)                            # attention-probability dropout: not available
+        m.set_dropout(0.1, -0.1, 0, 0)
     m.close()
 
 
