@@ -75,6 +75,9 @@ typedef struct {
   double useful_flops_total, recompute_flops_total;
   uint64_t peak_bytes_last, peak_bytes_max, predicted_peak_last;
   uint64_t fixed_bytes, budget_bytes;
+  /* estimator + scheduler time of the iterations that had to generate a plan (cache misses),
+   * for the overhead accounting of Section 6.4; min is 0 until the first miss */
+  uint64_t plan_gen_count, plan_gen_ns_total, plan_gen_ns_min, plan_gen_ns_max;
 } mimose_stats;
 
 /* quantities of the collector's sample table (Section 4.2), see mimose_planner_feed */

@@ -690,7 +690,7 @@ int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, const i
   // ---- plan (host only, on the critical path of every iteration)
   const auto t0 = std::chrono::steady_clock::now();
   uint64_t plan = 0;
-  bool collect = false;
+  bool collect = false, generated = false;
   int64_t predicted = 0;
   if (c->forced_plan >= 0) {
     plan = (uint64_t)c->forced_plan & all;
@@ -709,6 +709,7 @@ int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, const i
     const int rc = c->planner->query(xq, &po, &hit);
     if (rc == -1) return fail(c, MIMOSE_ERR_NOT_READY, "estimator could not be fitted");
     predicted = po.predicted_peak;
+    generated = !hit;
     if (rc == -2) {
       c->stats.predicted_peak_last = (uint64_t)predicted;
       return fail(c, MIMOSE_ERR_BUDGET_INFEASIBLE, "predicted peak exceeds the budget even with every layer checkpointed");
@@ -773,6 +774,12 @@ int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, const i
   S.cache_hits = c->planner->hits; S.cache_misses = c->planner->misses;
   S.cache_entries = c->planner->cache_entries();
   S.planner_ns_last = ns; S.planner_ns_total += ns;
+  if (generated) {                          // estimator + scheduler ran (Section 6.4's overhead accounting)
+    S.plan_gen_ns_min = S.plan_gen_count ? std::min(S.plan_gen_ns_min, ns) : ns;
+    S.plan_gen_ns_max = std::max(S.plan_gen_ns_max, ns);
+    S.plan_gen_ns_total += ns;
+    S.plan_gen_count++;
+  }
   S.recomputed_layers_last = n_re; S.recomputed_layers_total += n_re;
   S.useful_flops_last = uf; S.recompute_flops_last = rf;
   S.useful_flops_total += uf; S.recompute_flops_total += rf;

@@ -255,6 +255,7 @@ def test_whole_workload_stays_under_budget_and_matches_oracle_planner(name):
     st = m.stats()
     assert st["cache_hits"] == ref.hits and st["cache_misses"] == ref.misses
     assert st["steps"] == steps
+    assert st["plan_gen_count"] == ref.misses and st["plan_gen_ns_min"] <= st["plan_gen_ns_max"] <= st["plan_gen_ns_total"]
     if wl.shape.ffn_by_layer:                                 # stages of different widths: several buckets at work
         c = ref.predict(wl.batch * wl.shape.max_seq)
         assert len(op.make_buckets([a - b for a, b in zip(c.a, c.b)])) == len(set(wl.shape.ffn_by_layer))
