@@ -92,6 +92,9 @@ struct mimose_ctx {
   // needs the same incoming gradient (fork / join with events; default priority)
   hipStream_t side = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  // the last weight-gradient product of a layer is waited for one layer later: ev_early marks
+  // the side stream just before it, ev_late just after it
+  hipEvent_t ev_early = nullptr, ev_late = nullptr;
   std::vector<hipEvent_t> ev_layer;   // begin / end of each layer's forward in a collecting step
   Arena arena;
   uint64_t fixed_top = 0;
@@ -289,10 +292,10 @@ class Step {
     gemm(a);
   }
   // dW[out,in] = dY^T X, db[out] = column sums of dY
-  void wgrad(const void* dY, int64_t ldy, int out, const void* X, int in, int wi, int bi) {
+  void wgrad(const void* dY, int64_t ldy, int out, const void* X, int in, int wi, int bi, bool late = false) {
     mk::GemmArgs a{dY, ldy, false, X, in, false, g(wi), in, true, out, in, T_};
     a.a_rowsum = bi >= 0 ? g(bi) : nullptr;
-    with_workspace(a);
+    with_workspace(a, late);
   }
   // Weight-gradient products may cut their reduction in parts; the scratch for that is taken
   // once per layer backward / head (a size fixed by the weight shapes), so that every
@@ -306,15 +309,46 @@ class Step {
     ws_ = need ? c_->arena.alloc(need) : nullptr;
     ws_bytes_ = need;
   }
-  void with_workspace(mk::GemmArgs& a) {
-    a.workspace = ws_; a.workspace_bytes = ws_bytes_;
+  // late: the product reads and writes nothing that the layer's pop frees (its operand and its
+  // scratch live in the step-long slot), so the layer's end need not wait for it
+  void with_workspace(mk::GemmArgs& a, bool late = false) {
+    a.workspace = late ? late_ws_ : ws_;
+    a.workspace_bytes = late ? late_ws_bytes_ : ws_bytes_;
     if (dry_) return;
     // per-kernel timing brackets work on the main stream only, so it keeps everything there
     if (!c_->side || c_->prof_on) { gemm(a); return; }
     if (hipEventRecord(c_->ev_fork, st_) != hipSuccess || hipStreamWaitEvent(c_->side, c_->ev_fork, 0) != hipSuccess)
       throw StepError{MIMOSE_ERR_HIP, "fork to the weight-gradient stream failed"};
+    if (late && hipEventRecord(c_->ev_early, c_->side) != hipSuccess)
+      throw StepError{MIMOSE_ERR_HIP, "marking the weight-gradient stream failed"};
     if (!mk::gemm(dt_, a, c_->side)) throw StepError{MIMOSE_ERR_INVALID_ARG, "gemm: unsupported alignment"};
+    if (late) {
+      if (hipEventRecord(c_->ev_late, c_->side) != hipSuccess)
+        throw StepError{MIMOSE_ERR_HIP, "marking the weight-gradient stream failed"};
+      late_pending_ = early_marked_ = true;
+    }
     side_busy_ = true;
+  }
+  // Step-long slot for the gradient of the fused QKV projection and the scratch of its
+  // weight-gradient product (post-LN stacks; see layer_backward).
+  void* late_dqkv_ = nullptr;
+  void* late_ws_ = nullptr;
+  size_t late_ws_bytes_ = 0;
+  bool late_pending_ = false, early_marked_ = false;
+  bool late_ok() const { return !f_.pre_ln; }
+  // before the slot is written again: the product that still reads it must be done
+  void wait_late() {
+    if (!late_pending_) return;
+    if (hipStreamWaitEvent(st_, c_->ev_late, 0) != hipSuccess)
+      throw StepError{MIMOSE_ERR_HIP, "waiting for the weight-gradient stream failed"};
+    late_pending_ = false;
+  }
+  // the main stream waits for the weight-gradient products issued before the late one
+  void join_early() {
+    if (!early_marked_) { join(); return; }
+    if (hipStreamWaitEvent(st_, c_->ev_early, 0) != hipSuccess)
+      throw StepError{MIMOSE_ERR_HIP, "join of the weight-gradient stream failed"};
+    early_marked_ = false;
   }
   // the main stream waits for every weight-gradient product issued so far (before their inputs
   // or scratch are reused, and before anything reads the gradients)
@@ -323,7 +357,7 @@ class Step {
     if (!side_busy_) return;
     if (hipEventRecord(c_->ev_join, c_->side) != hipSuccess || hipStreamWaitEvent(st_, c_->ev_join, 0) != hipSuccess)
       throw StepError{MIMOSE_ERR_HIP, "join of the weight-gradient stream failed"};
-    side_busy_ = false;
+    side_busy_ = late_pending_ = early_marked_ = false;
   }
   void ln_fwd(const void* x, int gi, int bi, void* y, bool x_f32 = false) {
     Timed t(this, MIMOSE_K_LN_FWD, (x_f32 ? 6.0 : 2.0 * es_d()) * T_ * f_.hidden);
@@ -343,7 +377,7 @@ class Step {
   void embed_stage(const int32_t* tokens, const int32_t* labels);
   void embed_sort(const int32_t* tokens);
   void alloc_layer(int l, LayerActs& A);
-  void layer_forward(int l, LayerActs& A);
+  void layer_forward(int l, LayerActs& A, bool rebuild = false);
   void layer_backward(int l, LayerActs& A);
   void head(float* loss_dev);
   void embed_backward();
@@ -363,6 +397,11 @@ void Step::embed_stage(const int32_t* tokens, const int32_t* labels) {
   oB_ = wide_ ? talloc((int64_t)T_ * H) : gB_;
   if (!f_.pre_ln) emb_sum_ = talloc((int64_t)T_ * H);
   h0_ = talloc((int64_t)T_ * H);
+  if (late_ok()) {
+    late_dqkv_ = talloc(3 * (int64_t)T_ * H);
+    late_ws_bytes_ = dt_ == mk::BF16 ? mk::gemm_workspace_bytes(3 * H, H) : 0;
+    late_ws_ = late_ws_bytes_ ? c_->arena.alloc(late_ws_bytes_) : nullptr;
+  }
   if (dry_) return;
 
   // host side: stable sort of positions by token id, run boundaries of equal ids
@@ -408,7 +447,10 @@ void Step::alloc_layer(int l, LayerActs& A) {
   if (!f_.pre_ln) A.s2 = walloc(TH);  // post-LN: u + ffn (LN2 input, fp32 when wide)
 }
 
-void Step::layer_forward(int l, LayerActs& A) {
+// rebuild: the forward of a checkpointed layer run again before its backward.  Its output is
+// still in place (it is the layer's boundary tensor), so a post-LN layer leaves out the final
+// LayerNorm, which produces nothing else; later layers' pending products may still read it.
+void Step::layer_forward(int l, LayerActs& A, bool rebuild) {
   const LayerIdx& p = c_->lidx[l];
   const int H = f_.hidden, F = ffn_of(f_, l), nh = f_.n_heads, d = H / nh;
   const int gelu = f_.gelu_tanh ? mk::GELU_TANH : mk::GELU_ERF;
@@ -436,7 +478,7 @@ void Step::layer_forward(int l, LayerActs& A) {
     linear(A.u, H, p.w1, p.b1, A.pre, F, F, nullptr, A.act, gelu);
     linear(A.act, F, p.w2, p.b2, A.s2, H, H, drop ? nullptr : A.u, nullptr, 0, wide_);
     if (drop) dropout(A.s2, A.s2, wide_, A.u, site_f);
-    ln_fwd(A.s2, p.ln2g, p.ln2b, A.out, wide_);
+    if (!rebuild) ln_fwd(A.s2, p.ln2g, p.ln2b, A.out, wide_);
   }
 }
 
@@ -446,7 +488,8 @@ void Step::layer_backward(int l, LayerActs& A) {
   const int H = f_.hidden, F = ffn_of(f_, l), nh = f_.n_heads, d = H / nh;
   const int64_t TH = (int64_t)T_ * H, TF = (int64_t)T_ * F;
   Arena& ar = c_->arena;
-  reserve_workspace({{H, F}, {F, H}, {H, H}, {3 * H, H}});
+  if (late_ok()) reserve_workspace({{H, F}, {F, H}, {H, H}});
+  else reserve_workspace({{H, F}, {F, H}, {H, H}, {3 * H, H}});
   const uint64_t m0 = ar.top();
   // post-LN: oA = d s2 (LayerNorm 2 backward of the incoming gradient); pre-LN: the incoming
   // gradient is d s2 itself (oA aliases gA)
@@ -478,8 +521,14 @@ void Step::layer_backward(int l, LayerActs& A) {
   wgrad(dproj, H, H, A.ctx, H, p.wo, p.bo);
   void* dctx = talloc(TH);
   dgrad(dproj, H, H, p.wo, dctx, H);
-  void* dqkv = talloc(3 * TH);
+  // Post-LN: the QKV weight gradient is the last product of the layer, issued when the main
+  // stream has one product left; waiting for it at the layer's end idles the chip.  Its operands
+  // (this gradient, in a step-long slot, and the layer's input, which the pop does not free) and
+  // its scratch outlive the layer, so only the earlier products are waited for here and this one
+  // before the slot is written again, a layer later.
+  void* dqkv = late_ok() ? late_dqkv_ : talloc(3 * TH);
   float* delta = (float*)ar.alloc((uint64_t)B_ * nh * L_ * 4);
+  if (late_ok() && !dry_) wait_late();
   {
     Timed t(this, MIMOSE_K_ATTN_BWD, 8.0 * T_ * L_ * H * (f_.causal ? 0.5 : 1.0));
     if (!dry_)
@@ -487,7 +536,7 @@ void Step::layer_backward(int l, LayerActs& A) {
                         drop_desc(4 * (uint32_t)(l + 1), true), st_);
   }
   const void* a = f_.pre_ln ? A.n1 : A.x;
-  wgrad(dqkv, 3 * H, 3 * H, a, H, p.wqkv, p.bqkv);
+  wgrad(dqkv, 3 * H, 3 * H, a, H, p.wqkv, p.bqkv, late_ok());
   if (f_.pre_ln) {
     dgrad(dqkv, 3 * H, 3 * H, p.wqkv, gA_, H);                                // gA = d LN1(x)
     join();
@@ -495,7 +544,7 @@ void Step::layer_backward(int l, LayerActs& A) {
     ln_bwd(gA_, A.x, p.ln1g, p.ln1b, gA_, gB_);                               // gA = d x
   } else {
     dgrad(dqkv, 3 * H, 3 * H, p.wqkv, gA_, H, oB_, wide_);                    // gA = d x = d s1 + attention path
-    join();
+    if (dry_) {} else join_early();
     ar.pop_to(m0);
   }
 }
@@ -625,9 +674,9 @@ void Step::run(const int32_t* tokens, const int32_t* labels, float* loss_out) {
 
   for (int l = N - 1; l >= 0; --l) {
     LayerActs& A = c_->acts[l];
-    if (A.dropped) {                      // rebuild: same tensors, same launches
+    if (A.dropped) {                      // rebuild: same tensors, same values
       alloc_layer(l, A);
-      layer_forward(l, A);
+      layer_forward(l, A, true);
     }
     const uint64_t m = ar.top();
     ar.begin_section();
@@ -851,7 +900,9 @@ int mimose_init(const mimose_model_cfg* cfg, uint64_t mem_budget_bytes, void* ar
       return fail(nullptr, MIMOSE_ERR_HIP, "hipHostMalloc failed");
     if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess ||
         hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess)
+        hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_early, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_late, hipEventDisableTiming) != hipSuccess)
       return fail(nullptr, MIMOSE_ERR_HIP, "creating the weight-gradient stream failed");
     // gradients start at zero so that a read before the first step is defined
     mk::fill_zero(c->params.front().g, (int64_t)((char*)c->arena.alloc(0) - (char*)c->params.front().g), c->stream);
@@ -1121,6 +1172,8 @@ void mimose_destroy(mimose_ctx* c) {
     for (hipEvent_t e : c->ev_layer) if (e) (void)hipEventDestroy(e);
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+    if (c->ev_early) (void)hipEventDestroy(c->ev_early);
+    if (c->ev_late) (void)hipEventDestroy(c->ev_late);
     if (c->side) (void)hipStreamDestroy(c->side);
     if (c->stage) (void)hipHostFree(c->stage);
     if (c->loss_host) (void)hipHostFree(c->loss_host);
