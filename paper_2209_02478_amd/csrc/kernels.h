@@ -53,6 +53,10 @@ void layernorm_fwd(int dtype, const void* x, bool x_f32, const void* gamma, cons
 void layernorm_bwd(int dtype, const void* dy, bool dy_f32, const void* x, bool x_f32,
                    const void* gamma, void* dx, const void* add, float* dgamma, float* dbeta,
                    float* partial, int T, int H, float eps, hipStream_t st);
+// the two halves of layernorm_bwd: dx and the per-chunk partial sums; then dgamma, dbeta from them
+void layernorm_bwd_rows(int dtype, const void* dy, bool dy_f32, const void* x, bool x_f32, const void* gamma, void* dx,
+                        const void* add, float* partial, int T, int H, float eps, hipStream_t st);
+void layernorm_bwd_reduce(const float* partial, float* dgamma, float* dbeta, int T, int H, hipStream_t st);
 int partial_rows(int T);
 void gelu_bwd(int dtype, void* d, const void* pre, int64_t n, int tanh_form, hipStream_t st);
 // lens (optional, device, [B]): real tokens per sample of a padded batch; keys from lens[b] on get

@@ -317,8 +317,8 @@ class Step {
     if (dry_) return;
     // per-kernel timing brackets work on the main stream only, so it keeps everything there
     if (!c_->side || c_->prof_on) { gemm(a); return; }
-    if (hipEventRecord(c_->ev_fork, st_) != hipSuccess || hipStreamWaitEvent(c_->side, c_->ev_fork, 0) != hipSuccess)
-      throw StepError{MIMOSE_ERR_HIP, "fork to the weight-gradient stream failed"};
+    if (!forked_) fork();
+    forked_ = false;
     if (late && hipEventRecord(c_->ev_early, c_->side) != hipSuccess)
       throw StepError{MIMOSE_ERR_HIP, "marking the weight-gradient stream failed"};
     if (!mk::gemm(dt_, a, c_->side)) throw StepError{MIMOSE_ERR_INVALID_ARG, "gemm: unsupported alignment"};
@@ -372,6 +372,33 @@ class Step {
     if (!dry_)
       mk::layernorm_bwd(dt_, dy, dy_f32, x, x_f32, w(gi), dx, add, g(gi), g(bi), partial, T_, f_.hidden, f_.ln_eps, st_);
     c_->arena.pop_to(m);
+  }
+
+  // The same in two halves, for the layers' backward: the row pass on the main stream (its
+  // partial sums stay allocated until the layer's end), the small reduction to dgamma, dbeta on
+  // the weight-gradient stream after the next fork, off the chain of data gradients.
+  float* ln_bwd_rows(const void* dy, const void* x, int gi, void* dx, const void* add, bool dy_f32 = false,
+                     bool x_f32 = false) {
+    float* partial = (float*)c_->arena.alloc((uint64_t)mk::partial_rows(T_) * 2 * f_.hidden * 4);
+    const double bytes = (dy_f32 ? 4.0 : es_d()) + (x_f32 ? 4.0 : es_d()) + es_d() * (add ? 2.0 : 1.0);
+    Timed t(this, MIMOSE_K_LN_BWD, bytes * T_ * f_.hidden);
+    if (!dry_) mk::layernorm_bwd_rows(dt_, dy, dy_f32, x, x_f32, w(gi), dx, add, partial, T_, f_.hidden, f_.ln_eps, st_);
+    return partial;
+  }
+  void ln_bwd_reduce(const float* partial, int gi, int bi) {
+    if (dry_) return;
+    const bool aside = c_->side && !c_->prof_on;
+    mk::layernorm_bwd_reduce(partial, g(gi), g(bi), T_, f_.hidden, aside ? c_->side : st_);
+    if (aside) side_busy_ = true;
+  }
+  // One fork serves everything issued on the weight-gradient stream until the main stream
+  // launches again.
+  bool forked_ = false;
+  void fork() {
+    if (dry_ || !c_->side || c_->prof_on) return;
+    if (hipEventRecord(c_->ev_fork, st_) != hipSuccess || hipStreamWaitEvent(c_->side, c_->ev_fork, 0) != hipSuccess)
+      throw StepError{MIMOSE_ERR_HIP, "fork to the weight-gradient stream failed"};
+    forked_ = true;
   }
 
   void embed_stage(const int32_t* tokens, const int32_t* labels);
@@ -493,12 +520,14 @@ void Step::layer_backward(int l, LayerActs& A) {
   const uint64_t m0 = ar.top();
   // post-LN: oA = d s2 (LayerNorm 2 backward of the incoming gradient); pre-LN: the incoming
   // gradient is d s2 itself (oA aliases gA)
-  if (!f_.pre_ln) ln_bwd(gA_, A.s2, p.ln2g, p.ln2b, oA_, nullptr, wide_, wide_);
+  float* part2 = f_.pre_ln ? nullptr : ln_bwd_rows(gA_, A.s2, p.ln2g, oA_, nullptr, wide_, wide_);
   // with dropout the branch sees the masked gradient (a copy: the residual path keeps the whole one)
   const bool drop = drop_on();
   const uint32_t site_o = 4 * (uint32_t)(l + 1) + 1, site_f = site_o + 1;
   const void* dffn = oA_;
   if (drop) { void* m = talloc(TH); dropout(m, oA_, false, nullptr, site_f); dffn = m; }
+  fork();
+  if (part2) ln_bwd_reduce(part2, p.ln2g, p.ln2b);
   wgrad(dffn, H, H, A.act, F, p.w2, p.b2);
   void* dact = talloc(TF);
   dgrad(dffn, H, H, p.w2, dact, F);
@@ -509,15 +538,19 @@ void Step::layer_backward(int l, LayerActs& A) {
   wgrad(dact, F, F, A.u, H, p.w1, p.b1);
   // dact stays allocated until the end of the layer: the weight-gradient stream may still read
   // it, and waiting for that stream here would idle the chip for the length of the hand-over
+  float* part1;
   if (f_.pre_ln) {
     dgrad(dact, F, F, p.w1, gB_, H);                                          // gB = d LN2(u)
-    ln_bwd(gB_, A.s1, p.ln2g, p.ln2b, gB_, gA_);                              // gB = d u
+    part1 = ln_bwd_rows(gB_, A.s1, p.ln2g, gB_, gA_);                         // gB = d u
   } else {
     dgrad(dact, F, F, p.w1, gB_, H, oA_, wide_);                              // gB = d u = d s2 + FFN path
-    ln_bwd(gB_, A.s1, p.ln1g, p.ln1b, oB_, nullptr, wide_, wide_);            // oB = d s1
+    part1 = ln_bwd_rows(gB_, A.s1, p.ln1g, oB_, nullptr, wide_, wide_);       // oB = d s1
   }
   const void* dproj = oB_;
   if (drop) { void* m = talloc(TH); dropout(m, oB_, false, nullptr, site_o); dproj = m; }
+  fork();
+  if (f_.pre_ln) ln_bwd_reduce(part1, p.ln2g, p.ln2b);
+  else ln_bwd_reduce(part1, p.ln1g, p.ln1b);
   wgrad(dproj, H, H, A.ctx, H, p.wo, p.bo);
   void* dctx = talloc(TH);
   dgrad(dproj, H, H, p.wo, dctx, H);

@@ -705,18 +705,26 @@ static void ln_bwd_t(const void* dy, const void* x, const void* g, void* dx, con
   DISPATCH_NPL(H, M_);
 #undef M_
 }
-void layernorm_bwd(int dtype, const void* dy, bool dy_f32, const void* x, bool x_f32, const void* gamma, void* dx,
-                   const void* add, float* dgamma, float* dbeta, float* partial, int T_, int H, float eps,
-                   hipStream_t st) {
+void layernorm_bwd_rows(int dtype, const void* dy, bool dy_f32, const void* x, bool x_f32, const void* gamma, void* dx,
+                        const void* add, float* partial, int T_, int H, float eps, hipStream_t st) {
   if (T_ <= 0) return;
   if (dtype != BF16) ln_bwd_t<float, float, float>(dy, x, gamma, dx, add, partial, T_, H, eps, st);
   else if (dy_f32 && x_f32) ln_bwd_t<float, float, bf16_t>(dy, x, gamma, dx, add, partial, T_, H, eps, st);
   else if (dy_f32) ln_bwd_t<float, bf16_t, bf16_t>(dy, x, gamma, dx, add, partial, T_, H, eps, st);
   else if (x_f32) ln_bwd_t<bf16_t, float, bf16_t>(dy, x, gamma, dx, add, partial, T_, H, eps, st);
   else ln_bwd_t<bf16_t, bf16_t, bf16_t>(dy, x, gamma, dx, add, partial, T_, H, eps, st);
+}
+void layernorm_bwd_reduce(const float* partial, float* dgamma, float* dbeta, int T_, int H, hipStream_t st) {
+  if (T_ <= 0) return;
   int P = (T_ + kRowsPerChunk - 1) / kRowsPerChunk;
   hipLaunchKernelGGL(reduce_partials_kernel, dim3((2 * H + 15) / 16), dim3(256), 0, st, partial, P, 2 * H,
                      dgamma, dbeta, H);
+}
+void layernorm_bwd(int dtype, const void* dy, bool dy_f32, const void* x, bool x_f32, const void* gamma, void* dx,
+                   const void* add, float* dgamma, float* dbeta, float* partial, int T_, int H, float eps,
+                   hipStream_t st) {
+  layernorm_bwd_rows(dtype, dy, dy_f32, x, x_f32, gamma, dx, add, partial, T_, H, eps, st);
+  layernorm_bwd_reduce(partial, dgamma, dbeta, T_, H, st);
 }
 int partial_rows(int T_) { return (T_ + kRowsPerChunk - 1) / kRowsPerChunk; }
 
