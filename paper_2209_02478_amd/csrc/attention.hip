@@ -50,7 +50,7 @@ constexpr int kRowsPerBlock = 16;   // 4 waves x 4 rows
 // bf16, head size 64: MFMA kernels
 void attention_fwd_mfma(const void* qkv, void* ctx, float* lse, const int32_t* lens, int B, int L, int nh, int causal,
                         const DropDesc& drop, hipStream_t st);
-void attention_bwd_mfma(const void* qkv, const void* dctx, const float* lse, const float* delta, void* dqkv,
+void attention_bwd_mfma(const void* qkv, const void* ctx, const void* dctx, const float* lse, float* delta, void* dqkv,
                         const int32_t* lens, int B, int L, int nh, int causal, const DropDesc& drop, hipStream_t st);
 
 // qkv row stride is 3*H; head hh of token t: q at t*3H + hh*D, k at +H, v at +2H.
@@ -247,11 +247,8 @@ void attention_bwd(int dtype, const void* qkv, const void* ctx, const void* dctx
                    void* dqkv, const int32_t* lens, int B, int L, int nh, int d, int causal, const DropDesc& drop,
                    hipStream_t st) {
   if (B * L <= 0) return;
-  if (dtype == BF16 && d == 64) {
-    int64_t n = (int64_t)B * L * nh;
-    hipLaunchKernelGGL((attn_delta_kernel<bf16_t, 64>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                       (const bf16_t*)ctx, (const bf16_t*)dctx, delta, B, L, nh);
-    attention_bwd_mfma(qkv, dctx, lse, delta, dqkv, lens, B, L, nh, causal, drop, st);
+  if (dtype == BF16 && d == 64) {        // delta is made inside the dQ kernel
+    attention_bwd_mfma(qkv, ctx, dctx, lse, delta, dqkv, lens, B, L, nh, causal, drop, st);
     return;
   }
 #define F32_(DD) bwd_t<float, DD>(qkv, ctx, dctx, lse, delta, dqkv, lens, B, L, nh, causal, drop, st)

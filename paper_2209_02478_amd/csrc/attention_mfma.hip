@@ -223,8 +223,9 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(const bf16_t* __restrict
 
 // ------------------------------------------------------------------ dQ
 template <bool CAUSAL, bool DROP>
-__global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx,
-                                                        const float* __restrict__ lse, const float* __restrict__ delta,
+__global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ ctx,
+                                                        const bf16_t* __restrict__ dctx,
+                                                        const float* __restrict__ lse, float* __restrict__ delta,
                                                         bf16_t* __restrict__ dqkv, const int32_t* __restrict__ lens, int L,
                                                         int nh, DropDesc drop) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[TK][LDT];   // [key][d]
@@ -239,14 +240,22 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(const bf16_t* __restr
   const int qc = min(qi, L - 1);
   const float scale = 0.125f;
 
+  // delta = sum over the head's columns of dO * O for this query: each half of the wave holds 32
+  // of the 64 columns.  Written out for the dK/dV kernel, which runs after this one.
   bf16x8 qf[4], gf[4];
+  float delta_q = 0.f;
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
     qf[kk] = ld_frag(base + (int64_t)qc * ld3 + 16 * kk + 8 * h);
     gf[kk] = ld_frag(dctx + ((int64_t)b * L + qc) * H + hh * D + 16 * kk + 8 * h);
+    const bf16x8 of = ld_frag(ctx + ((int64_t)b * L + qc) * H + hh * D + 16 * kk + 8 * h);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) delta_q = fmaf((float)of[e], (float)gf[kk][e], delta_q);
   }
+  delta_q += __shfl_xor(delta_q, 32, 64);
+  if (h == 0 && qi < L) delta[(int64_t)bh * L + qi] = delta_q;
   const float c2 = scale * LOG2E;
-  const float nlse_q = -LOG2E * lse[(int64_t)bh * L + qc], delta_q = delta[(int64_t)bh * L + qc];
+  const float nlse_q = -LOG2E * lse[(int64_t)bh * L + qc];
   f32x16 dq[2];
   zero(dq[0]); zero(dq[1]);
   const int Lk = lens ? lens[b] : L;                  // keys from Lk on are padding (1 <= Lk <= L)
@@ -437,12 +446,12 @@ void attention_fwd_mfma(const void* qkv, void* ctx, float* lse, const int32_t* l
 #undef FWD_
 }
 
-void attention_bwd_mfma(const void* qkv, const void* dctx, const float* lse, const float* delta, void* dqkv,
+void attention_bwd_mfma(const void* qkv, const void* ctx, const void* dctx, const float* lse, float* delta, void* dqkv,
                         const int32_t* lens, int B, int L, int nh, int causal, const DropDesc& drop, hipStream_t st) {
   dim3 grid((L + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, B * nh);
 #define BWD_(C, D)                                                                                               \
-  hipLaunchKernelGGL((fa_bwd_dq_kernel<C, D>), grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, \
-                     delta, (bf16_t*)dqkv, lens, L, nh, drop);                                                    \
+  hipLaunchKernelGGL((fa_bwd_dq_kernel<C, D>), grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)ctx,  \
+                     (const bf16_t*)dctx, lse, delta, (bf16_t*)dqkv, lens, L, nh, drop);                          \
   hipLaunchKernelGGL((fa_bwd_dkv_kernel<C, D>), grid, dim3(256), 0, st, (const bf16_t*)qkv, (const bf16_t*)dctx, lse, \
                      delta, (bf16_t*)dqkv, lens, L, nh, drop)
   if (drop.thr) { if (causal) { BWD_(true, true); } else { BWD_(false, true); } }

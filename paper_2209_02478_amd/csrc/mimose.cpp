@@ -254,6 +254,7 @@ class Step {
 
   void gemm(const mk::GemmArgs& a) {
     if (dry_) return;
+    forked_ = false;                      // the main stream moves on: later side work needs a new fork
     Timed t(this, MIMOSE_K_GEMM, 2.0 * a.M * a.N * a.K);
     if (!mk::gemm(dt_, a, st_)) throw StepError{MIMOSE_ERR_INVALID_ARG, "gemm: unsupported alignment"};
   }
@@ -318,7 +319,6 @@ class Step {
     // per-kernel timing brackets work on the main stream only, so it keeps everything there
     if (!c_->side || c_->prof_on) { gemm(a); return; }
     if (!forked_) fork();
-    forked_ = false;
     if (late && hipEventRecord(c_->ev_early, c_->side) != hipSuccess)
       throw StepError{MIMOSE_ERR_HIP, "marking the weight-gradient stream failed"};
     if (!mk::gemm(dt_, a, c_->side)) throw StepError{MIMOSE_ERR_INVALID_ARG, "gemm: unsupported alignment"};
@@ -392,7 +392,7 @@ class Step {
     if (aside) side_busy_ = true;
   }
   // One fork serves everything issued on the weight-gradient stream until the main stream
-  // launches again.
+  // launches its next product (every group of side work here is followed by one).
   bool forked_ = false;
   void fork() {
     if (dry_ || !c_->side || c_->prof_on) return;
