@@ -405,6 +405,9 @@ class Step {
   void embed_sort(const int32_t* tokens);
   void alloc_layer(int l, LayerActs& A);
   void layer_forward(int l, LayerActs& A, bool rebuild = false);
+  void layer_forward_rows(int l, LayerActs& A, int b0, int nb, hipStream_t s);
+  bool split_forward() const;
+  void cross_sync();
   void layer_backward(int l, LayerActs& A);
   void head(float* loss_dev);
   void embed_backward();
@@ -472,6 +475,63 @@ void Step::alloc_layer(int l, LayerActs& A) {
   A.pre = talloc(TF);
   A.act = talloc(TF);
   if (!f_.pre_ln) A.s2 = walloc(TH);  // post-LN: u + ffn (LN2 input, fp32 when wide)
+}
+
+// The forward of samples [b0, b0 + nb) of the batch on stream s: the same kernels on a range of
+// rows.  Nothing in a layer's forward couples two samples, and every product uses the same tile
+// shape and reduction order wherever its rows sit, so the values are those of layer_forward
+// bit for bit.  Two such halves on two streams let one half's kernels fill the compute units
+// that the other's leave idle in their last round of tiles.
+void Step::layer_forward_rows(int l, LayerActs& A, int b0, int nb, hipStream_t s) {
+  const LayerIdx& p = c_->lidx[l];
+  const int H = f_.hidden, F = ffn_of(f_, l), nh = f_.n_heads, d = H / nh;
+  const int gelu = f_.gelu_tanh ? mk::GELU_TANH : mk::GELU_ERF;
+  const int64_t r0 = (int64_t)b0 * L_;
+  const int rows = nb * L_;
+  auto at = [&](const void* base, int64_t width, bool f32 = false) -> void* {
+    return (char*)const_cast<void*>(base) + r0 * width * (f32 ? 4 : (int64_t)es_);
+  };
+  auto lin = [&](const void* X, int in, int wi, int bi, void* Y, int out, const void* resid, void* act, int ge,
+                 bool out_f32) {
+    mk::GemmArgs a{X, in, true, w(wi), in, true, Y, out, out_f32, rows, out, in};
+    a.bias = w(bi);
+    a.resid = resid; a.ldr = out;
+    a.gelu_out = act; a.gelu = ge;
+    if (!mk::gemm(dt_, a, s)) throw StepError{MIMOSE_ERR_INVALID_ARG, "gemm: unsupported alignment"};
+  };
+  auto ln = [&](const void* x, int gi, int bi, void* y, bool x_f32) {
+    mk::layernorm_fwd(dt_, x, x_f32, w(gi), w(bi), y, rows, H, f_.ln_eps, s);
+  };
+  const void* x = at(A.x, H);
+  const void* a = x;
+  if (f_.pre_ln) { ln(x, p.ln1g, p.ln1b, at(A.n1, H), false); a = at(A.n1, H); }
+  lin(a, H, p.wqkv, p.bqkv, at(A.qkv, 3 * H), 3 * H, nullptr, nullptr, 0, false);
+  mk::attention_fwd(dt_, at(A.qkv, 3 * H), at(A.ctx, H), A.lse + (int64_t)b0 * nh * L_, lens_ ? lens_ + b0 : nullptr, nb, L_,
+                    nh, d, f_.causal, mk::DropDesc(), s);
+  lin(at(A.ctx, H), H, p.wo, p.bo, at(A.s1, H, wide_), H, x, nullptr, 0, wide_);
+  if (f_.pre_ln) {
+    ln(at(A.s1, H), p.ln2g, p.ln2b, at(A.u, H), false);
+    lin(at(A.u, H), H, p.w1, p.b1, at(A.pre, F), F, nullptr, at(A.act, F), gelu, false);
+    lin(at(A.act, F), F, p.w2, p.b2, at(A.out, H), H, at(A.s1, H), nullptr, 0, false);
+  } else {
+    ln(at(A.s1, H, wide_), p.ln1g, p.ln1b, at(A.u, H), wide_);
+    lin(at(A.u, H), H, p.w1, p.b1, at(A.pre, F), F, nullptr, at(A.act, F), gelu, false);
+    lin(at(A.act, F), F, p.w2, p.b2, at(A.s2, H, wide_), H, at(A.u, H), nullptr, 0, wide_);
+    ln(at(A.s2, H, wide_), p.ln2g, p.ln2b, at(A.out, H), wide_);
+  }
+}
+
+// Both halves on their own stream: only a real step, without dropout (whose masks count elements
+// from the tensor's start), without per-kernel or per-layer timing, with two samples at least.
+bool Step::split_forward() const {
+  return !dry_ && c_->side && !c_->prof_on && !collect_ && !drop_on() && c_->p_attn <= 0.f && B_ >= 2;
+}
+
+// each stream waits for what the other has been given so far
+void Step::cross_sync() {
+  if (hipEventRecord(c_->ev_fork, st_) != hipSuccess || hipStreamWaitEvent(c_->side, c_->ev_fork, 0) != hipSuccess ||
+      hipEventRecord(c_->ev_join, c_->side) != hipSuccess || hipStreamWaitEvent(st_, c_->ev_join, 0) != hipSuccess)
+    throw StepError{MIMOSE_ERR_HIP, "synchronising the two forward streams failed"};
 }
 
 // rebuild: the forward of a checkpointed layer run again before its backward.  Its output is
@@ -684,18 +744,38 @@ void Step::run(const int32_t* tokens, const int32_t* labels, float* loss_out) {
 
   c_->acts.assign(N, LayerActs());
   const void* x = h0_;
+  // the two halves of the batch run through the layers on two streams, meeting only where a
+  // dropped layer's memory is handed to the next layer and at the end
+  const bool split = split_forward() && N > 0;
+  const int nb0 = B_ / 2;
+  if (split) {
+    if (hipEventRecord(c_->ev_fork, st_) != hipSuccess || hipStreamWaitEvent(c_->side, c_->ev_fork, 0) != hipSuccess)
+      throw StepError{MIMOSE_ERR_HIP, "fork of the forward streams failed"};
+  }
   for (int l = 0; l < N; ++l) {
     LayerActs& A = c_->acts[l];
     A.x = x;
     alloc_layer(l, A);
     const bool timed = collect_ && !dry_ && (int)c_->ev_layer.size() == 2 * N;
     if (timed) HIPCHK(c_, hipEventRecord(c_->ev_layer[2 * l], st_));
-    layer_forward(l, A);
+    if (split) {
+      layer_forward_rows(l, A, 0, nb0, st_);
+      layer_forward_rows(l, A, nb0, B_ - nb0, c_->side);
+    } else {
+      layer_forward(l, A);
+    }
     if (timed) HIPCHK(c_, hipEventRecord(c_->ev_layer[2 * l + 1], st_));
     a_bytes[l] = ar.top() - A.mark;
     b_bytes[l] = A.after_out - A.mark;
-    if ((plan_ >> l) & 1) { ar.pop_to(A.after_out); A.dropped = true; }
+    if ((plan_ >> l) & 1) {
+      ar.pop_to(A.after_out); A.dropped = true;
+      if (split && l + 1 < N) cross_sync();   // the next layer writes where this one's tensors are still read
+    }
     x = A.out;
+  }
+  if (split) {
+    if (hipEventRecord(c_->ev_join, c_->side) != hipSuccess || hipStreamWaitEvent(st_, c_->ev_join, 0) != hipSuccess)
+      throw StepError{MIMOSE_ERR_HIP, "join of the forward streams failed"};
   }
 
   embed_sort(tokens);                     // host work hidden behind the queued forward
