@@ -16,6 +16,8 @@
 // fp32: a plain 64x64x16 LDS-tiled kernel (small-model configuration only).
 #include "device_common.h"
 #include "gemm_device.h"
+
+#include <hip/hip_ext.h>
 #include "kernels.h"
 
 namespace mk {
@@ -373,7 +375,7 @@ static void launch_splitk_reduce(const GemmDev& p, hipStream_t st) {
 }
 
 template <bool AK, bool BKM>
-static void launch_bgemm(const GemmDev& p, hipStream_t st) {
+static void launch_bgemm(const GemmDev& p, hipStream_t st, hipEvent_t t0, hipEvent_t t1) {
   constexpr int smem = 2 * (Tile<AK>::ELEMS + Tile<BKM>::ELEMS) * 2;
   static bool configured = false;
   if (!configured) {
@@ -382,12 +384,12 @@ static void launch_bgemm(const GemmDev& p, hipStream_t st) {
   }
   const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
   const int total = tiles_m * tiles_n * p.splits, per = (total + 7) / 8;
-  hipLaunchKernelGGL((bgemm_kernel<AK, BKM>), dim3(per * 8), dim3(256), smem, st, p, tiles_n, total, per);
+  hipExtLaunchKernelGGL((bgemm_kernel<AK, BKM>), dim3(per * 8), dim3(256), smem, st, t0, t1, 0, p, tiles_n, total, per);
   if (p.splits > 1) launch_splitk_reduce(p, st);
 }
 
 // direct-to-LDS pipeline (gemm_dma.hip); false when the operands do not meet its alignment rules
-bool launch_bgemm_dma(const GemmDev& p, hipStream_t st);
+bool launch_bgemm_dma(const GemmDev& p, hipStream_t st, hipEvent_t t0, hipEvent_t t1);
 
 static bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
 
@@ -402,7 +404,7 @@ bool gemm(int dtype, const GemmArgs& g, hipStream_t st) {
   if (p.gelu && (p.c_f32 || !p.gelu_out)) return false;
   if (dtype == F32) {
     dim3 grid((g.N + 63) / 64, (g.M + 63) / 64);
-    hipLaunchKernelGGL(sgemm_kernel, grid, dim3(256), 0, st, p);
+    hipExtLaunchKernelGGL(sgemm_kernel, grid, dim3(256), 0, st, g.time_start, g.time_stop, 0, p);
     return true;
   }
   if ((g.lda & 7) || (g.ldb & 7) || !aligned16(g.A) || !aligned16(g.B)) return false;
@@ -422,11 +424,11 @@ bool gemm(int dtype, const GemmArgs& g, hipStream_t st) {
   // B m-major (weight gradients, data gradients): the direct-to-LDS pipeline measures faster there;
   // the register-staged kernel below is ahead when both operands are k-major (forward)
   p.vec = vec ? 1 : 0;
-  if (!g.b_kmajor && launch_bgemm_dma(p, st)) {
+  if (!g.b_kmajor && launch_bgemm_dma(p, st, g.time_start, g.time_stop)) {
     if (p.splits > 1) launch_splitk_reduce(p, st);
     return true;
   }
-#define LAUNCH_(AKV, BKV) launch_bgemm<AKV, BKV>(p, st)
+#define LAUNCH_(AKV, BKV) launch_bgemm<AKV, BKV>(p, st, g.time_start, g.time_stop)
   if (g.a_kmajor && g.b_kmajor) LAUNCH_(true, true);
   else if (g.a_kmajor && !g.b_kmajor) LAUNCH_(true, false);
   else if (!g.a_kmajor && g.b_kmajor) LAUNCH_(false, true);

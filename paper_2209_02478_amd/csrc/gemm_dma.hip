@@ -21,6 +21,8 @@
 // with tile t+2.  The reduction order over k is fixed by the shape alone.
 #include "gemm_device.h"
 
+#include <hip/hip_ext.h>
+
 namespace mk {
 
 namespace {
@@ -264,27 +266,28 @@ __global__ __launch_bounds__(256, 3) void bgemm_dma_kernel(GemmDev p, int tiles_
 }
 
 template <bool AK, bool BKM>
-static void launch_t(const GemmDev& p, hipStream_t st) {
+static void launch_t(const GemmDev& p, hipStream_t st, hipEvent_t t0, hipEvent_t t1) {
   const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
   const int total = tiles_m * tiles_n * p.splits, per = (total + 7) / 8;
   const bool ktail = p.K % BK != 0;
   dim3 grid(per * 8), block(256);
-  if (ktail) hipLaunchKernelGGL((bgemm_dma_kernel<AK, BKM, true>), grid, block, 0, st, p, tiles_n, total, per);
-  else hipLaunchKernelGGL((bgemm_dma_kernel<AK, BKM, false>), grid, block, 0, st, p, tiles_n, total, per);
+  // t0, t1 (optional): events bound to this kernel's own start and end
+  if (ktail) hipExtLaunchKernelGGL((bgemm_dma_kernel<AK, BKM, true>), grid, block, 0, st, t0, t1, 0, p, tiles_n, total, per);
+  else hipExtLaunchKernelGGL((bgemm_dma_kernel<AK, BKM, false>), grid, block, 0, st, t0, t1, 0, p, tiles_n, total, per);
 }
 
 // Requirements: 16-byte chunks must be wholly inside or wholly outside the matrix along the
 // reduction index of a k-major operand (K % 8 == 0), and physically present along the rows of an
 // m-major operand (its leading dimension covers the row count rounded up to 8).
-bool launch_bgemm_dma(const GemmDev& p, hipStream_t st) {
+bool launch_bgemm_dma(const GemmDev& p, hipStream_t st, hipEvent_t t0, hipEvent_t t1) {
   auto up8 = [](int64_t v) { return (v + 7) / 8 * 8; };
   if ((p.a_k || p.b_k) && (p.K & 7)) return false;
   if (!p.a_k && p.lda < up8(p.M)) return false;
   if (!p.b_k && p.ldb < up8(p.N)) return false;
-  if (p.a_k && p.b_k) launch_t<true, true>(p, st);
-  else if (p.a_k && !p.b_k) launch_t<true, false>(p, st);
-  else if (!p.a_k && p.b_k) launch_t<false, true>(p, st);
-  else launch_t<false, false>(p, st);
+  if (p.a_k && p.b_k) launch_t<true, true>(p, st, t0, t1);
+  else if (p.a_k && !p.b_k) launch_t<true, false>(p, st, t0, t1);
+  else if (!p.a_k && p.b_k) launch_t<false, true>(p, st, t0, t1);
+  else launch_t<false, false>(p, st, t0, t1);
   return true;
 }
 

@@ -35,6 +35,9 @@ struct GemmArgs {
   float* a_rowsum = nullptr;       // [M] fp32: sum_k A(m,k) (bias gradient of a weight-gradient product)
   void* workspace = nullptr;       // optional scratch of gemm_workspace_bytes(M, N) for split reductions
   size_t workspace_bytes = 0;
+  // optional, both or neither: recorded by the product kernel's own start and end (not by markers
+  // around the launch), for per-kernel timing; a split product's reduction kernel is outside
+  hipEvent_t time_start = nullptr, time_stop = nullptr;
 };
 
 // scratch that lets a bf16 product with fp32 output cut its reduction in parts (0: never splits);

@@ -255,8 +255,14 @@ class Step {
   void gemm(const mk::GemmArgs& a) {
     if (dry_) return;
     forked_ = false;                      // the main stream moves on: later side work needs a new fork
-    Timed t(this, MIMOSE_K_GEMM, 2.0 * a.M * a.N * a.K);
-    if (!mk::gemm(dt_, a, st_)) throw StepError{MIMOSE_ERR_INVALID_ARG, "gemm: unsupported alignment"};
+    mk::GemmArgs b = a;
+    if (c_->prof_on) {                    // timed by the kernel's own start and end, not by markers around the launch
+      b.time_start = c_->prof_event();
+      b.time_stop = c_->prof_event();
+      if (b.time_start && b.time_stop) c_->prof_pending.push_back({MIMOSE_K_GEMM, 2.0 * a.M * a.N * a.K, b.time_start, b.time_stop});
+      else b.time_start = b.time_stop = nullptr;
+    }
+    if (!mk::gemm(dt_, b, st_)) throw StepError{MIMOSE_ERR_INVALID_ARG, "gemm: unsupported alignment"};
   }
   // Y[T,out] = X[T,in] W[out,in]^T + bias (+ resid) (GELU: Y = pre-activation, act = GELU(Y))
   void linear(const void* X, int in, int wi, int bi, void* Y, int out, int64_t ldy, const void* resid = nullptr,
