@@ -29,7 +29,11 @@ namespace {
 
 constexpr int D = 64;          // head size
 constexpr int TK = 64;         // rows of a streamed tile
-constexpr int LDT = 72;        // LDS row stride in elements (144 bytes)
+constexpr int LDT = 72;        // LDS row stride in elements of the tiles read 16 bytes at a time (144 bytes)
+// Row stride of the transposed tiles, which are written and read 8 bytes at a time: 34 dwords, an
+// odd multiple of two, so that the 8-byte reads of lanes 0..31 (one row each) fall in all different
+// banks; with 36 dwords rows r and r + 16 met in the same banks (half of those reads conflicted).
+constexpr int LDTT = 68;
 constexpr int ROWS_PER_BLOCK = 128;
 
 constexpr float LOG2E = 1.44269504088896340736f;
@@ -52,7 +56,7 @@ __device__ __forceinline__ bf16x8 regs_to_frag(const f32x16& v, int c) {
   return __builtin_bit_cast(bf16x8, u);
 }
 // A operand from a transposed tile: row `row`, reduction indices base+4h+{0..3}, base+8+4h+{0..3}
-__device__ __forceinline__ bf16x8 ld_frag_t(const bf16_t (*tile)[LDT], int row, int base, int h) {
+__device__ __forceinline__ bf16x8 ld_frag_t(const bf16_t (*tile)[LDTT], int row, int base, int h) {
   uint2 lo = *(const uint2*)&tile[row][base + 4 * h];
   uint2 hi = *(const uint2*)&tile[row][base + 8 + 4 * h];
   uint4 u = make_uint4(lo.x, lo.y, hi.x, hi.y);
@@ -71,7 +75,7 @@ __device__ __forceinline__ void fetch_tile(const bf16_t* src, int64_t ld, int r0
   }
 }
 template <bool NORMAL, bool TRANSPOSED>
-__device__ __forceinline__ void stash_tile(const uint4 (&v)[4], int t, bf16_t (*normal)[LDT], bf16_t (*transposed)[LDT]) {
+__device__ __forceinline__ void stash_tile(const uint4 (&v)[4], int t, bf16_t (*normal)[LDT], bf16_t (*transposed)[LDTT]) {
   const int rq = t >> 3, cb = t & 7;
   if (NORMAL) {
 #pragma unroll
@@ -124,7 +128,7 @@ __global__ __launch_bounds__(256, 2) void fa_fwd_kernel(const bf16_t* __restrict
                                                      float* __restrict__ lse, const int32_t* __restrict__ lens,
                                                      int L, int nh, DropDesc drop) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[TK][LDT];   // [key][d]
-  __shared__ __attribute__((aligned(16))) bf16_t Vt[D][LDT];    // [d][key]
+  __shared__ __attribute__((aligned(16))) bf16_t Vt[D][LDTT];   // [d][key]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, ql = lane & 31, h = lane >> 5;
   const int bh = blockIdx.y, b = bh / nh, hh = bh - b * nh;
   const int H = nh * D;
@@ -229,7 +233,7 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dq_kernel(const bf16_t* __restr
                                                         bf16_t* __restrict__ dqkv, const int32_t* __restrict__ lens, int L,
                                                         int nh, DropDesc drop) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[TK][LDT];   // [key][d]
-  __shared__ __attribute__((aligned(16))) bf16_t Kt[D][LDT];    // [d][key]
+  __shared__ __attribute__((aligned(16))) bf16_t Kt[D][LDTT];   // [d][key]
   __shared__ __attribute__((aligned(16))) bf16_t Vs[TK][LDT];   // [key][d]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, ql = lane & 31, h = lane >> 5;
   const int bh = blockIdx.y, b = bh / nh, hh = bh - b * nh;
@@ -319,9 +323,9 @@ __global__ __launch_bounds__(256, 2) void fa_bwd_dkv_kernel(const bf16_t* __rest
                                                          bf16_t* __restrict__ dqkv, const int32_t* __restrict__ lens, int L,
                                                         int nh, DropDesc drop) {
   __shared__ __attribute__((aligned(16))) bf16_t Qs[TK][LDT];   // [query][d]
-  __shared__ __attribute__((aligned(16))) bf16_t Qt[D][LDT];    // [d][query]
+  __shared__ __attribute__((aligned(16))) bf16_t Qt[D][LDTT];   // [d][query]
   __shared__ __attribute__((aligned(16))) bf16_t Gs[TK][LDT];   // dO [query][d]
-  __shared__ __attribute__((aligned(16))) bf16_t Gt[D][LDT];    // dO [d][query]
+  __shared__ __attribute__((aligned(16))) bf16_t Gt[D][LDTT];   // dO [d][query]
   __shared__ __attribute__((aligned(16))) float lse_s[TK], delta_s[TK];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, kl = lane & 31, h = lane >> 5;
   const int bh = blockIdx.y, b = bh / nh, hh = bh - b * nh;
