@@ -107,23 +107,28 @@ __device__ __forceinline__ bf16x8 frag_read(const bf16_t* at) {
   return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
-// sum over the tile's reduction indices of tile row tid/2 (two threads per row, any fixed order)
+// Row sums of the A tile over its reduction indices (the bias gradient riding on a
+// weight-gradient product), accumulated per thread over the k tiles and reduced once at the end.
+// k-major tile: thread = (row tid/2, half of the 32 indices), one float.
+// m-major tile (the layout weight gradients have): a thread owns one 16-byte chunk = 8 consecutive
+// rows, for reduction indices tid/16 and tid/16 + 16: two 16-byte reads per tile, eight floats.
 template <bool KM>
-__device__ __forceinline__ float rowsum_part(const bf16_t* tile, int tid) {
-  float s = 0.f;
-  const int r = tid >> 1, half = tid & 1;
+__device__ __forceinline__ void rowsum_acc(const bf16_t* tile, int tid, float (&rs)[8]) {
   if (KM) {
-    const bf16_t* src = &tile[r * BK + half * (BK / 2)];            // chunk order inside a row is immaterial
+    const int r = tid >> 1, half = tid & 1;
+    const bf16_t* src = &tile[r * BK + half * (BK / 2)];              // chunk order inside a row is immaterial
 #pragma unroll
-    for (int e = 0; e < BK / 2; ++e) s += bf16_to_f32(src[e]);
+    for (int e = 0; e < BK / 2; ++e) rs[0] += bf16_to_f32(src[e]);
   } else {
+    const int c = tid & 15;
 #pragma unroll
-    for (int e = 0; e < BK / 2; ++e) {
-      const int q = half * (BK / 2) + e;
-      s += bf16_to_f32(tile[q * 128 + (((r >> 3) ^ (4 * (q & 3))) * 8) + (r & 7)]);
+    for (int j = 0; j < 2; ++j) {
+      const int q = (tid >> 4) + 16 * j;
+      const bf16x8 v = *(const bf16x8*)&tile[q * 128 + ((c ^ (4 * (q & 3))) * 8)];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) rs[e] += (float)v[e];
     }
   }
-  return s;
 }
 
 }  // namespace
@@ -159,7 +164,7 @@ __global__ __launch_bounds__(256, 3) void bgemm_dma_kernel(GemmDev p, int tiles_
   const int kt_begin = split * per_split;
   const int nk = max(0, min(nk_all, kt_begin + per_split) - kt_begin);
   const bool do_rowsum = p.a_rowsum && tile_n == 0;
-  float rs = 0.f;
+  float rs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   // this thread's direct loads: wave w issues loads 2w, 2w+1 of each operand tile, lane = slot
   Src srcA[DMA_PER_WAVE], srcB[DMA_PER_WAVE];
@@ -209,7 +214,7 @@ __global__ __launch_bounds__(256, 3) void bgemm_dma_kernel(GemmDev p, int tiles_
     }
   auto compute = [&](const bf16_t* stage) {
     static_assert(BK == 32, "two k halves per tile");
-    if (do_rowsum) rs += rowsum_part<AK>(stage, tid);
+    if (do_rowsum) rowsum_acc<AK>(stage, tid, rs);
     __builtin_amdgcn_iglp_opt(0);
     bf16x8 af[2], bfr[2];
 #pragma unroll
@@ -256,9 +261,24 @@ __global__ __launch_bounds__(256, 3) void bgemm_dma_kernel(GemmDev p, int tiles_
     rowsum = p.partial + (int64_t)p.splits * p.M * p.N + (int64_t)split * p.M;
   }
   if (do_rowsum) {
-    const float tot = rs + __shfl_xor(rs, 1, 64);
-    const int m = m0 + (tid >> 1);
-    if ((tid & 1) == 0 && m < p.M) rowsum[m] = tot;
+    if (AK) {
+      const float tot = rs[0] + __shfl_xor(rs[0], 1, 64);
+      const int m = m0 + (tid >> 1);
+      if ((tid & 1) == 0 && m < p.M) rowsum[m] = tot;
+    } else {
+      // sixteen threads hold parts of every row: through the (now dead) ring, summed in a fixed order
+      float* red = (float*)ring;                                      // [16 index groups][128 rows]
+      __syncthreads();
+#pragma unroll
+      for (int e = 0; e < 8; ++e) red[(tid >> 4) * 128 + (tid & 15) * 8 + e] = rs[e];
+      __syncthreads();
+      if (tid < 128) {
+        float tot = 0.f;
+#pragma unroll
+        for (int g = 0; g < 16; ++g) tot += red[g * 128 + tid];
+        if (m0 + tid < p.M) rowsum[m0 + tid] = tot;
+      }
+    }
   }
   static_assert(sizeof(ring) >= 4 * 64 * 32 * sizeof(float), "staging needs 8 KB per wave");
   float* wstage = (float*)ring + wave * 64 * 32;
