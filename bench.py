@@ -207,6 +207,8 @@ def main():
         "planner_us_per_step": round((s1["planner_ns_total"] - s0["planner_ns_total"]) / K / 1e3, 2),
         "max_peak_over_budget": round(max_peak / budget, 4),
         "kernels": kernels,
+        "kernels_timing": "gemm: events bound to each kernel's own start and end; other classes: markers around the launch, "
+                          "which read a few microseconds more than the kernel itself (see profiles/ for the kernel trace)",
         "update": upd,
         "roofline": {"bound": "mfma", "kernel": "bgemm_kernel / bgemm_dma_kernel (every GEMM launch of the timed steps)",
                      "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
