@@ -380,6 +380,51 @@ def test_bert_base_shape_step():
     m.close()
 
 
+def test_bert_base_shape_padded_with_dropout():
+    """BERT-base shape, full batch of 32 padded to L = 64 with per-sample lengths, dropout 0.1 on
+    every site, half the layers rebuilt: parity with the oracle (float32 build, bf16-rounded
+    weights) and the same bits as the run that keeps every layer."""
+    wl = synthdata.WORKLOADS["bert_base"]
+    shape = wl.shape
+    params = synthdata.make_params(shape, wl.seed)
+    rng = np.random.default_rng(7)
+    lengths = [64] + [int(v) for v in rng.integers(8, 65, wl.batch - 1)]
+    tokens, labels, lens = synthdata.make_padded_batch(shape, lengths, 6)
+    p = float(np.float32(0.1))
+    m = mi.Mimose(synthdata.shape_dict(shape), 0, arena_bytes=4096 * MiB)
+    m.load_params(params)
+    m.set_dropout(p, p, 2024, 3)
+    m.force_plan(0b101010101010)
+    loss, peak, _ = m.train_step(tokens, labels, lengths=lens)
+    G = m.grads()
+    ref_loss, RG = oracle_step_dropout(shape, params, tokens, labels, om.Dropout(p, p, 2024, 3), lens)
+    assert abs(loss - ref_loss) <= 1e-2 * abs(ref_loss), (loss, ref_loss)
+    worst = max((rel_l2(G[k], ref), k) for k, ref in RG.items())
+    print("bert_base padded + dropout: loss", loss, ref_loss, "worst grad", worst)
+    assert worst[0] <= 2e-2, worst
+    m.set_dropout(p, p, 2024, 3)
+    m.force_plan(0)
+    loss0, peak0, _ = m.train_step(tokens, labels, lengths=lens)
+    assert loss0 == loss and peak0 > peak
+    for k, g in m.grads().items():
+        assert np.array_equal(g, G[k]), k
+    m.close()
+
+
+def test_bert_stages_shape_step():
+    """The stack with three feed-forward widths at full size (batch 32, L = 64): parity with the oracle."""
+    wl = synthdata.WORKLOADS["bert_stages"]
+    shape = wl.shape
+    params = synthdata.make_params(shape, wl.seed)
+    tokens, labels = synthdata.make_batch(shape, wl.batch, 64, 5)
+    m = mi.Mimose(synthdata.shape_dict(shape), 0, arena_bytes=4096 * MiB)
+    m.load_params(params)
+    m.force_plan(0b000011110000)
+    loss, peak, plan, worst = check_against_oracle(shape, m, params, tokens, labels, 1e-2, 2e-2, np.float32)
+    print("bert_stages L=64: loss", loss, "worst grad", worst)
+    m.close()
+
+
 def test_bert_base_full_length_under_budget():
     """Launch configuration of the benchmark at the longest length (B=32, L=512): the planner
     keeps the measured peak under 60 % of the no-checkpoint peak, the loss sits at its
