@@ -294,7 +294,7 @@ def train_step(cfg: Cfg, params: Dict[str, np.ndarray], tokens: np.ndarray,
     masked in every attention and padded positions carry no label.
     dropout (optional): see Dropout; None or zero probabilities leave every value as it is.
     """
-    P = {k: np.asarray(v, dtype=dtype) for k, v in params.items()}
+    P = {k: np.asanyarray(v, dtype=dtype) for k, v in params.items()}
     B, L = tokens.shape
     T = B * L
     H = cfg.hidden

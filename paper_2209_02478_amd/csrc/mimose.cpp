@@ -95,6 +95,9 @@ struct mimose_ctx {
   // the last weight-gradient product of a layer is waited for one layer later: ev_early marks
   // the side stream just before it, ev_late just after it
   hipEvent_t ev_early = nullptr, ev_late = nullptr;
+  // end of a layer's first weight-gradient product, which reads the incoming gradient where the
+  // layer's last data-gradient product writes when the carriers have the storage type
+  hipEvent_t ev_w2 = nullptr;
   std::vector<hipEvent_t> ev_layer;   // begin / end of each layer's forward in a collecting step
   Arena arena;
   uint64_t fixed_top = 0;
@@ -595,6 +598,11 @@ void Step::layer_backward(int l, LayerActs& A) {
   fork();
   if (part2) ln_bwd_reduce(part2, p.ln2g, p.ln2b);
   wgrad(dffn, H, H, A.act, F, p.w2, p.b2);
+  // Carriers of the storage type: that product reads gA_ (dffn is oA_, which is gA_), and the
+  // layer's last data gradient writes gA_ before the streams join, so it is ordered by an event.
+  const bool guard_gA = !dry_ && side_busy_ && dffn == gA_;
+  if (guard_gA && hipEventRecord(c_->ev_w2, c_->side) != hipSuccess)
+    throw StepError{MIMOSE_ERR_HIP, "marking the weight-gradient stream failed"};
   void* dact = talloc(TF);
   dgrad(dffn, H, H, p.w2, dact, F);
   {
@@ -636,6 +644,8 @@ void Step::layer_backward(int l, LayerActs& A) {
   }
   const void* a = f_.pre_ln ? A.n1 : A.x;
   wgrad(dqkv, 3 * H, 3 * H, a, H, p.wqkv, p.bqkv, late_ok());
+  if (guard_gA && hipStreamWaitEvent(st_, c_->ev_w2, 0) != hipSuccess)
+    throw StepError{MIMOSE_ERR_HIP, "waiting for the weight-gradient stream failed"};
   if (f_.pre_ln) {
     dgrad(dqkv, 3 * H, 3 * H, p.wqkv, gA_, H);                                // gA = d LN1(x)
     join();
@@ -1021,7 +1031,8 @@ int mimose_init(const mimose_model_cfg* cfg, uint64_t mem_budget_bytes, void* ar
         hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&c->ev_early, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&c->ev_late, hipEventDisableTiming) != hipSuccess)
+        hipEventCreateWithFlags(&c->ev_late, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_w2, hipEventDisableTiming) != hipSuccess)
       return fail(nullptr, MIMOSE_ERR_HIP, "creating the weight-gradient stream failed");
     // gradients start at zero so that a read before the first step is defined
     mk::fill_zero(c->params.front().g, (int64_t)((char*)c->arena.alloc(0) - (char*)c->params.front().g), c->stream);
@@ -1293,6 +1304,7 @@ void mimose_destroy(mimose_ctx* c) {
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
     if (c->ev_early) (void)hipEventDestroy(c->ev_early);
     if (c->ev_late) (void)hipEventDestroy(c->ev_late);
+    if (c->ev_w2) (void)hipEventDestroy(c->ev_w2);
     if (c->side) (void)hipStreamDestroy(c->side);
     if (c->stage) (void)hipHostFree(c->stage);
     if (c->loss_host) (void)hipHostFree(c->loss_host);

@@ -274,3 +274,64 @@ def test_padding_content_does_not_matter():
     loss3, G3 = om.train_step(cfg, params, tokens, labels, lengths=np.full(3, tokens.shape[1]))
     loss4, G4 = om.train_step(cfg, params, tokens, labels)
     assert loss3 == loss4 and all(np.array_equal(G3[k], G4[k]) for k in G3)
+
+
+# ---------------------------------------------------------------- the FLOP count behind the throughput figures
+class _CountingArray(np.ndarray):
+    """ndarray that adds 2*m*n*k to a counter for every matrix product it takes part in."""
+    flops = 0
+
+    def __array_ufunc__(self, ufunc, method, *inputs, out=None, **kw):
+        plain = tuple(i.view(np.ndarray) if isinstance(i, np.ndarray) else i for i in inputs)
+        if out is not None:
+            kw["out"] = tuple(o.view(np.ndarray) if isinstance(o, np.ndarray) else o for o in out)
+        res = getattr(ufunc, method)(*plain, **kw)
+        if ufunc is np.matmul and method == "__call__":
+            a, b = plain
+            _CountingArray.flops += 2 * int(np.prod(res.shape)) * a.shape[-1]
+        if isinstance(res, tuple):
+            return tuple(r.view(_CountingArray) if isinstance(r, np.ndarray) else r for r in res)
+        return res.view(_CountingArray) if isinstance(res, np.ndarray) else res
+
+
+def _counted_step(cfg, params, tokens, labels, plan):
+    _CountingArray.flops = 0
+    om.train_step(cfg, {k: v.astype(np.float64).view(_CountingArray) for k, v in params.items()}, tokens, labels, plan=plan)
+    return _CountingArray.flops
+
+
+@pytest.mark.parametrize("variant", [dict(), dict(pre_ln=1, head=0), dict(ffn_by_layer=(48, 32, 16), n_layers=3)])
+def test_flops_per_step_equals_the_products_the_definition_performs(variant):
+    """useful = every product of forward and backward at 2mnk; recompute = the products of the rebuilt
+    layers' forwards: counted while the oracle runs, not retyped."""
+    shape = small_shape(**variant)
+    cfg, params, tokens, labels = setup(shape, 3, 7)
+    base = _counted_step(cfg, params, tokens, labels, 0)
+    assert base > 0
+    useful, re0 = om.flops_per_step(cfg, 3, 7)
+    assert re0 == 0.0 and useful == base
+    for plan in range(1, 1 << shape.n_layers):
+        u, re = om.flops_per_step(cfg, 3, 7, plan=plan)
+        assert u == base and re == _counted_step(cfg, params, tokens, labels, plan) - base, plan
+    assert om.flops_per_step(cfg, 3, 7, n_recomputed=2) == om.flops_per_step(cfg, 3, 7, plan=0b11)
+
+
+def test_flops_per_step_worked_example_and_causal_half():
+    """BERT-base at L = 200, B = 32: per token and layer 24H^2 + 4LH = 14.16 + 0.61 MFLOP, head
+    2H^2 + 2HV = 1.18 + 46.88, forward 225.4, training 3 x forward = 676 MFLOP per token, 4.33 TFLOP
+    per step; a rebuilt layer costs its forward again; a causal mask halves the attention term."""
+    cfg = om.Cfg(12, 768, 12, 3072, 30522, 512)
+    useful, re = om.flops_per_step(cfg, 32, 200, plan=0b101)
+    T = 6400
+    layer = 24 * 768 ** 2 + 4 * 200 * 768
+    head = 2 * 768 ** 2 + 2 * 768 * 30522
+    assert layer == 14_155_776 + 614_400 and head == 1_179_648 + 46_881_792
+    assert useful == 3.0 * T * (12 * layer + head)
+    assert abs(useful / T / 1e6 - 676.0) < 0.5 and abs(useful / 1e12 - 4.33) < 0.005
+    assert re == 2.0 * T * layer
+    causal = om.Cfg(12, 768, 12, 3072, 30522, 512, causal=1)
+    uc, rc = om.flops_per_step(causal, 32, 200, plan=0b1)
+    assert useful - uc == 3.0 * T * 12 * (2 * 200 * 768)
+    assert rc == T * (24 * 768 ** 2 + 2 * 200 * 768)
+    lm = om.Cfg(12, 768, 12, 3072, 30522, 512, head=0)
+    assert useful - om.flops_per_step(lm, 32, 200)[0] == 3.0 * T * 2 * 768 ** 2
