@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmimose.so")
-SOURCES = ["gemm.hip", "gemm_dma.hip", "rowops.hip", "attention.hip", "attention_mfma.hip", "ops_abi.cpp", "mimose.cpp", "planner.cpp"]
+SOURCES = ["gemm.hip", "gemm_dma.hip", "gemm_pp.hip", "rowops.hip", "attention.hip", "attention_mfma.hip", "ops_abi.cpp", "mimose.cpp", "planner.cpp"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

@@ -18,6 +18,9 @@
 #include "gemm_device.h"
 
 #include <hip/hip_ext.h>
+
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace mk {
@@ -363,15 +366,36 @@ int gemm_splits(int M, int N) {
   return s < 1 ? 1 : (s > 8 ? 8 : s);
 }
 
+// the kernel with 256 x 256 tiles (gemm_pp.hip) and its tile count
+bool launch_bgemm_pp(const GemmDev& p, hipStream_t st, hipEvent_t t0, hipEvent_t t1);
+int bgemm_pp_tiles(int M, int N);
+static int pp_splits(int M, int N) {
+  const int tiles = bgemm_pp_tiles(M, N);
+  int s = (256 + tiles - 1) / tiles;
+  return s < 1 ? 1 : (s > 8 ? 8 : s);
+}
+// Which products go to the large-tile kernel: it runs one block per compute unit, so its time is
+// a whole number of rounds of 256 units (tile, k part), and it pays where those rounds are
+// well filled; measured against the 128 x 128 kernels on the shapes of the step (same box, same
+// run): ahead by 10-35 % from about 0.8 of a full last round on (0.7 when the reduction is long
+// enough to hide the start and the end of a tile), behind below that.
+static bool use_pp(int M, int N, int K, int units) {
+  if (M < 256 || N < 256 || K < 512) return false;
+  const int rounds = (units + 255) / 256;
+  const double fill = (double)units / (256.0 * rounds);
+  return fill >= 0.8 || (fill >= 0.7 && K >= 2048);
+}
+
 size_t gemm_workspace_bytes(int M, int N) {
-  const int s = gemm_splits(M, N);
+  const int s = std::max(gemm_splits(M, N), pp_splits(M, N));
   return s > 1 ? ((size_t)s * M * N + (size_t)s * M) * 4 : 0;
 }
 
-static void launch_splitk_reduce(const GemmDev& p, hipStream_t st) {
+// t1 (optional): event bound to the end of this kernel, which ends the product it belongs to
+static void launch_splitk_reduce(const GemmDev& p, hipStream_t st, hipEvent_t t1) {
   const int64_t MN = (int64_t)p.M * p.N;
-  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((MN / 4 + 256) / 256)), dim3(256), 0, st, p.partial,
-                     (float*)p.C, p.ldc, p.a_rowsum, p.M, p.N, p.splits);
+  hipExtLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((MN / 4 + 256) / 256)), dim3(256), 0, st, nullptr, t1, 0,
+                        p.partial, (float*)p.C, p.ldc, p.a_rowsum, p.M, p.N, p.splits);
 }
 
 template <bool AK, bool BKM>
@@ -384,8 +408,9 @@ static void launch_bgemm(const GemmDev& p, hipStream_t st, hipEvent_t t0, hipEve
   }
   const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
   const int total = tiles_m * tiles_n * p.splits, per = (total + 7) / 8;
-  hipExtLaunchKernelGGL((bgemm_kernel<AK, BKM>), dim3(per * 8), dim3(256), smem, st, t0, t1, 0, p, tiles_n, total, per);
-  if (p.splits > 1) launch_splitk_reduce(p, st);
+  hipExtLaunchKernelGGL((bgemm_kernel<AK, BKM>), dim3(per * 8), dim3(256), smem, st, t0, p.splits > 1 ? nullptr : t1, 0, p,
+                        tiles_n, total, per);
+  if (p.splits > 1) launch_splitk_reduce(p, st, t1);
 }
 
 // direct-to-LDS pipeline (gemm_dma.hip); false when the operands do not meet its alignment rules
@@ -409,23 +434,39 @@ bool gemm(int dtype, const GemmArgs& g, hipStream_t st) {
   }
   if ((g.lda & 7) || (g.ldb & 7) || !aligned16(g.A) || !aligned16(g.B)) return false;
   // few output tiles and a long reduction (weight gradients): cut k so the whole chip works
-  if (g.workspace && g.c_f32 && !g.bias && !g.resid && !g.gelu && aligned16(g.workspace)) {
-    const int want = gemm_splits(g.M, g.N), by_k = (g.K + 255) / 256;   // >= 256 reduction indices per part
+  const bool may_split = g.workspace && g.c_f32 && !g.bias && !g.resid && !g.gelu && aligned16(g.workspace);
+  auto splits_for = [&](int want) {
+    const int by_k = (g.K + 255) / 256;                                   // >= 256 reduction indices per part
     const int sp = want < by_k ? want : by_k;
-    if (sp > 1 && g.workspace_bytes >= ((size_t)sp * g.M * g.N + (size_t)sp * g.M) * 4) {
-      p.splits = sp;
-      p.partial = (float*)g.workspace;
-    }
-  }
+    return may_split && sp > 1 && g.workspace_bytes >= ((size_t)sp * g.M * g.N + (size_t)sp * g.M) * 4 ? sp : 1;
+  };
   // vector epilogue: eight consecutive columns (16 bytes of bf16, 32 of fp32) per access
   const bool vec = (g.ldc & (g.c_f32 ? 3 : 7)) == 0 && aligned16(g.C) &&
                    (!g.resid || ((g.ldr & 7) == 0 && aligned16(g.resid))) && (!g.bias || aligned16(g.bias)) &&
                    (!g.gelu_out || aligned16(g.gelu_out));
+  p.vec = vec ? 1 : 0;
+  // large tiles where their rounds are well filled (a choice made from the shape alone)
+  {
+    const int sp = splits_for(pp_splits(g.M, g.N));
+    if (use_pp(g.M, g.N, g.K, bgemm_pp_tiles(g.M, g.N) * sp)) {
+      p.splits = sp;
+      p.partial = sp > 1 ? (float*)g.workspace : nullptr;
+      if (launch_bgemm_pp(p, st, g.time_start, sp > 1 ? nullptr : g.time_stop)) {
+        if (p.splits > 1) launch_splitk_reduce(p, st, g.time_stop);
+        return true;
+      }
+      p.splits = 1; p.partial = nullptr;
+    }
+  }
+  // few output tiles and a long reduction (weight gradients): cut k so the whole chip works
+  {
+    const int sp = splits_for(gemm_splits(g.M, g.N));
+    if (sp > 1) { p.splits = sp; p.partial = (float*)g.workspace; }
+  }
   // B m-major (weight gradients, data gradients): the direct-to-LDS pipeline measures faster there;
   // the register-staged kernel below is ahead when both operands are k-major (forward)
-  p.vec = vec ? 1 : 0;
-  if (!g.b_kmajor && launch_bgemm_dma(p, st, g.time_start, g.time_stop)) {
-    if (p.splits > 1) launch_splitk_reduce(p, st);
+  if (!g.b_kmajor && launch_bgemm_dma(p, st, g.time_start, p.splits > 1 ? nullptr : g.time_stop)) {
+    if (p.splits > 1) launch_splitk_reduce(p, st, g.time_stop);
     return true;
   }
 #define LAUNCH_(AKV, BKV) launch_bgemm<AKV, BKV>(p, st, g.time_start, g.time_stop)

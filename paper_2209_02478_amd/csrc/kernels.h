@@ -36,7 +36,7 @@ struct GemmArgs {
   void* workspace = nullptr;       // optional scratch of gemm_workspace_bytes(M, N) for split reductions
   size_t workspace_bytes = 0;
   // optional, both or neither: recorded by the product kernel's own start and end (not by markers
-  // around the launch), for per-kernel timing; a split product's reduction kernel is outside
+  // around the launch), for per-kernel timing; a split product ends with its reduction kernel
   hipEvent_t time_start = nullptr, time_stop = nullptr;
 };
 

@@ -147,6 +147,76 @@ def test_gemm_many_tiles(a_k, b_k):
     close(host(Cf), ref, 0, k=20.0)
 
 
+@pytest.mark.parametrize("a_k,b_k", [(1, 1), (1, 0), (0, 0), (0, 1)])
+def test_gemm_large_tiles(a_k, b_k):
+    """Shapes the dispatch gives to the kernel with 256 x 256 tiles (14 x 15 = 210 of 256 units in its
+    one round; reduction 520 = 8 tiles of 64 and a tail of 8): ragged edges in both dimensions,
+    bias + residual + GELU, row sums, fp32 output, and the same bits on a second run."""
+    dtype, M, N, K = 1, 3500, 3800, 520
+    rng = np.random.default_rng(170 + 2 * a_k + b_k)
+    A = rng.standard_normal((M, K)).astype(np.float32) * 0.5
+    B = rng.standard_normal((N, K)).astype(np.float32) * 0.5
+    bias = rng.standard_normal(N).astype(np.float32)
+    resid = rng.standard_normal((M, N)).astype(np.float32)
+    up = lambda v: (v + 7) // 8 * 8
+    def lay(X, kmajor):
+        R, Kk = X.shape
+        if kmajor:
+            buf = np.zeros((R, up(Kk) + 8), np.float32); buf[:, :Kk] = X
+            return buf, up(Kk) + 8
+        buf = np.zeros((Kk, up(R)), np.float32); buf[:, :R] = X.T
+        return buf, up(R)
+    Ab, lda = lay(A, a_k)
+    Bb, ldb = lay(B, b_k)
+    dA, dB, dbias, dres = dev(Ab, dtype), dev(Bb, dtype), dev(bias, dtype), dev(resid, dtype)
+    ref = quant(A, dtype) @ quant(B, dtype).T
+    ldc = up(N) + 8
+    C = torch.full((M, ldc), 7.0, dtype=dA.dtype, device=DEV)
+    Gt = torch.full((M, ldc), 7.0, dtype=dA.dtype, device=DEV)
+    mi.mimose_op_gemm(dtype, dA, lda, a_k, dB, ldb, b_k, C, ldc, 0, M, N, K, bias=dbias, gelu_out=Gt, gelu=1)
+    sync()
+    pre = ref + quant(bias, dtype)
+    assert np.all(host(C)[:, N:] == 7.0) and np.all(host(Gt)[:, N:] == 7.0), "wrote outside the N columns"
+    close(host(C)[:, :N], pre, dtype, k=2.0)
+    close(host(Gt)[:, :N], om.gelu_fwd(pre, False), dtype, scale=np.abs(pre).max(), k=3.0)
+    # fp32 output with residual; row sums when A is stored m-major (the weight-gradient form)
+    Cf = torch.full((M, N), 7.0, dtype=torch.float32, device=DEV)
+    rs = torch.full((M,), 9.0, dtype=torch.float32, device=DEV)
+    mi.mimose_op_gemm(dtype, dA, lda, a_k, dB, ldb, b_k, Cf, N, 1, M, N, K, resid=dres, ldr=N, a_rowsum=rs)
+    sync()
+    first = host(Cf)
+    close(first, ref + quant(resid, dtype), 0, k=20.0)
+    close(host(rs), quant(A, dtype).astype(np.float64).sum(1), 0, k=20.0)
+    Cf.fill_(3.0)
+    mi.mimose_op_gemm(dtype, dA, lda, a_k, dB, ldb, b_k, Cf, N, 1, M, N, K, resid=dres, ldr=N, a_rowsum=rs)
+    sync()
+    assert np.array_equal(host(Cf), first)
+
+
+def test_gemm_large_tiles_split_reduction():
+    """Weight-gradient shape of the fused QKV projection (27 tiles of 256 x 256, the reduction cut
+    in 8 parts = 216 units) with a ragged reduction length, row sums included."""
+    dtype, M, N, T = 1, 2304, 768, 2100
+    rng = np.random.default_rng(171)
+    dY = rng.standard_normal((T, M)).astype(np.float32)
+    X = rng.standard_normal((T, N)).astype(np.float32)
+    ddY, dX = dev(dY, dtype), dev(X, dtype)
+    nws = mi.mimose_op_gemm_workspace_bytes(M, N)
+    assert nws >= 8 * (M * N + M) * 4
+    ws = torch.zeros(nws, dtype=torch.uint8, device=DEV)
+    W = torch.full((M, N), 9.0, dtype=torch.float32, device=DEV)
+    rs = torch.full((M,), 9.0, dtype=torch.float32, device=DEV)
+    mi.mimose_op_gemm(dtype, ddY, M, 0, dX, N, 0, W, N, 1, M, N, T, a_rowsum=rs, workspace=ws, workspace_bytes=nws)
+    sync()
+    first = host(W)
+    close(first, quant(dY, dtype).T @ quant(X, dtype), 0, k=40.0)
+    close(host(rs), quant(dY, dtype).sum(0), 0, k=40.0)
+    W.fill_(1.0)
+    mi.mimose_op_gemm(dtype, ddY, M, 0, dX, N, 0, W, N, 1, M, N, T, a_rowsum=rs, workspace=ws, workspace_bytes=nws)
+    sync()
+    assert np.array_equal(host(W), first)
+
+
 def test_gemm_rejects_misaligned_bf16():
     a = torch.zeros(64 * 20, dtype=torch.bfloat16, device=DEV)
     with pytest.raises(mi.MimoseError):
