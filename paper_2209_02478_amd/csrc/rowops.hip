@@ -120,7 +120,8 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const TD* __restrict__ dy, 
 }
 
 // out[c] = sum over partial rows, c in [0, ncols): 16 row groups x 16 columns per block,
-// each group adds its rows in order, groups are combined in order.
+// each group adds its rows in order, groups are combined in order.  (Fallback for column counts
+// or pointers that do not allow 16-byte accesses.)
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int P,
                                                               int ncols, float* __restrict__ out0,
                                                               float* __restrict__ out1, int split) {
@@ -137,6 +138,39 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
 #pragma unroll
     for (int i = 0; i < 16; ++i) t += red[i][cg];
     if (c < split) out0[c] = t; else out1[c - split] = t;
+  }
+}
+
+// The same sums with whole 128-byte lines: a block owns 32 columns, 32 row groups x 8 lanes of four
+// columns; a group adds rows g, g + 32, ... in order, eight loads in flight at a time (a chain of
+// dependent loads costs a memory latency per row), groups are combined in order.
+__global__ __launch_bounds__(256) void reduce_partials_vec_kernel(const float* __restrict__ partial, int P,
+                                                                  int ncols, float* __restrict__ out0,
+                                                                  float* __restrict__ out1, int split) {
+  __shared__ float4 red[32][8];
+  const int cq = threadIdx.x & 7, rg = threadIdx.x >> 3;
+  const int c = blockIdx.x * 32 + cq * 4;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (c < ncols)
+    for (int r0 = rg; r0 < P; r0 += 32 * 8) {
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int r = r0 + 32 * u;
+        v[u] = r < P ? *(const float4*)(partial + (int64_t)r * ncols + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+    }
+  red[rg][cq] = s;
+  __syncthreads();
+  if (rg == 0 && c < ncols) {
+    float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int i = 0; i < 32; ++i) { const float4 q = red[i][cq]; t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w; }
+    const float e[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { const int cc = c + k; if (cc < split) out0[cc] = e[k]; else out1[cc - split] = e[k]; }
   }
 }
 
@@ -717,8 +751,12 @@ void layernorm_bwd_rows(int dtype, const void* dy, bool dy_f32, const void* x, b
 void layernorm_bwd_reduce(const float* partial, float* dgamma, float* dbeta, int T_, int H, hipStream_t st) {
   if (T_ <= 0) return;
   int P = (T_ + kRowsPerChunk - 1) / kRowsPerChunk;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((2 * H + 15) / 16), dim3(256), 0, st, partial, P, 2 * H,
-                     dgamma, dbeta, H);
+  if ((H & 1) == 0 && (((uintptr_t)partial) & 15) == 0)      // rows of 2H floats: every float4 inside a row, lines aligned
+    hipLaunchKernelGGL(reduce_partials_vec_kernel, dim3((2 * H + 31) / 32), dim3(256), 0, st, partial, P, 2 * H, dgamma,
+                       dbeta, H);
+  else
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((2 * H + 15) / 16), dim3(256), 0, st, partial, P, 2 * H, dgamma,
+                       dbeta, H);
 }
 void layernorm_bwd(int dtype, const void* dy, bool dy_f32, const void* x, bool x_f32, const void* gamma, void* dx,
                    const void* add, float* dgamma, float* dbeta, float* partial, int T_, int H, float eps,
