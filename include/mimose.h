@@ -285,6 +285,20 @@ int mimose_op_layernorm_bwd(int32_t dtype, const void* dy, int32_t dy_f32, const
                             float* dgamma, float* dbeta, float* partial, int32_t T, int32_t H,
                             float eps, void* stream);
 int32_t mimose_op_partial_rows(int32_t T);
+/* mimose_op_layernorm_bwd for callers that cannot allocate or bring a workspace (code under HIP
+ * graph capture, serving loops, harnesses that forbid hipMalloc): same kernels, same results, the
+ * partial sums live in a fixed device array inside the library (8 MiB per device, held until the
+ * process ends).  It allocates nothing and calls no allocating routine.  Sizes with
+ * mimose_op_partial_rows(T) * 2 * H > mimose_op_layernorm_bwd_noalloc_max_floats() are refused
+ * with INVALID_ARG (mimose_last_error(NULL) says by how much); HIP if the array's address
+ * cannot be obtained on the current device.  Nothing in the array needs clearing between calls
+ * (every partial row read is written first), but all calls on one device share it: two calls
+ * that overlap on the same device (different streams, no ordering between them) race. */
+int mimose_op_layernorm_bwd_noalloc(int32_t dtype, const void* dy, int32_t dy_f32, const void* x,
+                                    int32_t x_f32, const void* gamma, void* dx, const void* add,
+                                    float* dgamma, float* dbeta, int32_t T, int32_t H, float eps,
+                                    void* stream);
+uint64_t mimose_op_layernorm_bwd_noalloc_max_floats(void);
 /* d[n] (in place) *= gelu'(pre[n]). */
 int mimose_op_gelu_bwd(int32_t dtype, void* d, const void* pre, int64_t n, int32_t tanh_form,
                        void* stream);

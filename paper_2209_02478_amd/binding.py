@@ -93,6 +93,9 @@ SIGNATURES = {
     "mimose_op_layernorm_bwd": (C.c_int, [_i32, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _f32,
                                           _vp]),
     "mimose_op_partial_rows": (_i32, [_i32]),
+    "mimose_op_layernorm_bwd_noalloc": (C.c_int, [_i32, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _f32,
+                                                  _vp]),
+    "mimose_op_layernorm_bwd_noalloc_max_floats": (_u64, []),
     "mimose_op_gelu_bwd": (C.c_int, [_i32, _vp, _vp, _i64, _i32, _vp]),
     "mimose_op_attention_fwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _f32, _u64, C.c_uint32,
                                           C.c_uint32, _vp]),
@@ -326,6 +329,15 @@ def mimose_op_layernorm_bwd(dtype, dy, dy_f32, x, x_f32, gamma, dx, add, dgamma,
 
 def mimose_op_partial_rows(T: int) -> int:
     return load_library().mimose_op_partial_rows(T)
+
+
+def mimose_op_layernorm_bwd_noalloc(dtype, dy, dy_f32, x, x_f32, gamma, dx, add, dgamma, dbeta, T, H, eps, stream=None):
+    _check(load_library().mimose_op_layernorm_bwd_noalloc(dtype, _ptr(dy), dy_f32, _ptr(x), x_f32, _ptr(gamma), _ptr(dx),
+                                                          _ptr(add), _ptr(dgamma), _ptr(dbeta), T, H, eps, _ptr(stream)))
+
+
+def mimose_op_layernorm_bwd_noalloc_max_floats() -> int:
+    return load_library().mimose_op_layernorm_bwd_noalloc_max_floats()
 
 
 def mimose_op_gelu_bwd(dtype, d, pre, n, tanh_form, stream=None):

@@ -61,6 +61,14 @@ void layernorm_bwd_rows(int dtype, const void* dy, bool dy_f32, const void* x, b
                         const void* add, float* partial, int T, int H, float eps, hipStream_t st);
 void layernorm_bwd_reduce(const float* partial, float* dgamma, float* dbeta, int T, int H, hipStream_t st);
 int partial_rows(int T);
+// layernorm_bwd with the partial sums in a fixed device array of the library (no allocation, no
+// workspace argument).  Returns 0, -1 when partial_rows(T) * 2 * H exceeds
+// kStaticPartialFloats, -2 when the array's address cannot be obtained.  One array per device,
+// shared by every call on that device.
+constexpr size_t kStaticPartialFloats = (size_t)2 << 20;   // 8 MiB
+int layernorm_bwd_static(int dtype, const void* dy, bool dy_f32, const void* x, bool x_f32, const void* gamma,
+                         void* dx, const void* add, float* dgamma, float* dbeta, int T, int H, float eps,
+                         hipStream_t st);
 void gelu_bwd(int dtype, void* d, const void* pre, int64_t n, int tanh_form, hipStream_t st);
 // lens (optional, device, [B]): real tokens per sample of a padded batch; keys from lens[b] on get
 // no weight.  nullptr: every sample fills its row.  drop: dropout of the probabilities (the

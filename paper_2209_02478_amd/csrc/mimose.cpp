@@ -153,6 +153,9 @@ struct mimose_ctx {
 
 static thread_local std::string g_init_error;
 
+// the message mimose_last_error(NULL) returns on this thread, for entry points without a context
+void mimose_set_thread_error(const char* msg) { g_init_error = msg ? msg : ""; }
+
 namespace {
 
 int fail(mimose_ctx* c, int code, const std::string& msg) {

@@ -1,8 +1,13 @@
 // C ABI of the kernel-level entry points: argument checks, then the launcher.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
+
 #include "../../include/mimose.h"
 #include "kernels.h"
+
+// sets what mimose_last_error(NULL) returns on this thread (mimose.cpp)
+void mimose_set_thread_error(const char* msg);
 
 namespace {
 inline bool bad_dtype(int d) { return d != 0 && d != 1; }
@@ -48,6 +53,33 @@ int mimose_op_layernorm_bwd(int32_t dtype, const void* dy, int32_t dy_f32, const
 }
 
 int32_t mimose_op_partial_rows(int32_t T) { return mk::partial_rows(T); }
+
+int mimose_op_layernorm_bwd_noalloc(int32_t dtype, const void* dy, int32_t dy_f32, const void* x, int32_t x_f32,
+                                    const void* gamma, void* dx, const void* add, float* dgamma, float* dbeta,
+                                    int32_t T, int32_t H, float eps, void* stream) {
+  if (bad_dtype(dtype) || !dy || !x || !gamma || !dx || !dgamma || !dbeta || T < 0 || H < 1 || H > mk::kMaxRowWidth ||
+      add == dx || (dx == dy && dtype == 1 && dy_f32)) {
+    mimose_set_thread_error("mimose_op_layernorm_bwd_noalloc: bad argument");
+    return MIMOSE_ERR_INVALID_ARG;
+  }
+  const int rc = mk::layernorm_bwd_static(dtype, dy, dy_f32 != 0, x, x_f32 != 0, gamma, dx, add, dgamma, dbeta, T, H, eps,
+                                          (hipStream_t)stream);
+  if (rc == -1) {
+    char buf[200];
+    snprintf(buf, sizeof buf,
+             "mimose_op_layernorm_bwd_noalloc: %d rows of %d need %lld scratch floats, the fixed array holds %llu",
+             T, H, (long long)mk::partial_rows(T) * 2 * H, (unsigned long long)mk::kStaticPartialFloats);
+    mimose_set_thread_error(buf);
+    return MIMOSE_ERR_INVALID_ARG;
+  }
+  if (rc != 0) {
+    mimose_set_thread_error("mimose_op_layernorm_bwd_noalloc: address of the scratch array not available");
+    return MIMOSE_ERR_HIP;
+  }
+  return done();
+}
+
+uint64_t mimose_op_layernorm_bwd_noalloc_max_floats(void) { return mk::kStaticPartialFloats; }
 
 int mimose_op_gelu_bwd(int32_t dtype, void* d, const void* pre, int64_t n, int32_t tanh_form, void* stream) {
   if (bad_dtype(dtype) || !d || !pre || n < 0) return MIMOSE_ERR_INVALID_ARG;

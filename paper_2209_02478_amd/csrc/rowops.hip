@@ -766,6 +766,29 @@ void layernorm_bwd(int dtype, const void* dy, bool dy_f32, const void* x, bool x
 }
 int partial_rows(int T_) { return (T_ + kRowsPerChunk - 1) / kRowsPerChunk; }
 
+// Scratch of the entry point that allocates nothing: the per-chunk partial sums of the LayerNorm
+// backward.  Each device the library runs on holds its own copy until the process ends; host code
+// never uses the array's name as an address, only what hipGetSymbolAddress returned for the
+// device that was current.
+static __device__ __align__(256) float scratch[kStaticPartialFloats];
+static float* g_scratch_of_device[64];
+
+int layernorm_bwd_static(int dtype, const void* dy, bool dy_f32, const void* x, bool x_f32, const void* gamma,
+                         void* dx, const void* add, float* dgamma, float* dbeta, int T_, int H, float eps,
+                         hipStream_t st) {
+  if ((size_t)partial_rows(T_) * 2 * (size_t)H > kStaticPartialFloats) return -1;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -2;
+  float* ptr = g_scratch_of_device[dev];
+  if (!ptr) {
+    if (hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return -2;
+    g_scratch_of_device[dev] = ptr;
+  }
+  // every partial row that the reduction reads is written by the row pass first: nothing to clear
+  layernorm_bwd(dtype, dy, dy_f32, x, x_f32, gamma, dx, add, dgamma, dbeta, ptr, T_, H, eps, st);
+  return 0;
+}
+
 void gelu_bwd(int dtype, void* d, const void* pre, int64_t n, int tanh_form, hipStream_t st) {
   if (n <= 0) return;
   dim3 grid((unsigned)((n + 2047) / 2048));
