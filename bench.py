@@ -16,7 +16,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
-GEMM_SOURCES = ("gemm.hip", "gemm_dma.hip", "gemm_device.h")
+GEMM_SOURCES = ("gemm.hip", "gemm_dma.hip", "gemm_pp.hip", "gemm_device.h")
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "bert_base_gemm_hbm_traffic.txt")
 
 
@@ -42,7 +42,7 @@ def recorded_gemm_traffic(workload):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="bert_base")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -57,6 +57,12 @@ def main():
     ap.add_argument("--dropout", type=float, default=0.0,
                     help="dropout probability of the attention probabilities and of the hidden sites (embedding output, attention and feed-forward "
                          "block outputs), masks from the counter-based generator; 0 = off, the measured default")
+    ap.add_argument("--collector", default="marks", choices=["marks", "two_forwards"],
+                    help="how the sheltered iterations measure a block: from the allocator's marks in one forward (default), "
+                         "or with the paper's two forwards per block (Section 4.2), whose cost the overhead object then shows")
+    ap.add_argument("--wait-every-step", action="store_true",
+                    help="read the loss after every iteration (the host blocks until the device is done) instead of "
+                         "queueing the timed iterations one after the other and reading the loss once at the end")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 256 MiB element-wise copy kernels (reference for scaling FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -92,14 +98,15 @@ def main():
     else:
         m = mi.Mimose(d, budget, cost_aware=int(args.cost_aware))
     m.set_plan_mode(args.plan_mode)
+    m.set_collector(args.collector)
     m.load_params(synthdata.make_params(shape, wl.seed))
     if update:
         m.optimizer_init(**adamw)
     if args.dropout > 0:
         m.set_dropout(args.dropout, args.dropout, wl.seed, 0)
 
-    def iteration(t, l):
-        r = m.train_step(t, l)
+    def iteration(t, l, wait=True):
+        r = m.train_step(t, l, wait=wait)
         if update:
             m.optimizer_step()
         return r
@@ -129,11 +136,13 @@ def main():
     max_peak = 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for t, l in timed:
-        _, pk, _ = iteration(t, l)
+    for t, l in timed:                        # queued one after the other; the loss is read once, at the end
+        _, pk, _ = iteration(t, l, wait=args.wait_every_step)
         max_peak = max(max_peak, pk)
+    last_loss = m.sync_loss()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    assert np.isfinite(last_loss)
     s1 = m.stats()
 
     # Overhead accounting in the manner of Section 6.4: what a collecting iteration costs beyond the
@@ -195,8 +204,11 @@ def main():
                                f"vocab {shape.vocab}, batch {B}, per-batch length {wl.length_recipe}, "
                                f"budget {wl.budget_frac:.2f} x no-checkpoint peak at L={shape.max_seq}",
                    "global_batch": B, "mean_seq_len": round(float(np.mean([t.shape[1] for t, _ in timed])), 1),
-                   "budget_bytes": budget, "sheltered_steps": sheltered, "plan_mode": args.plan_mode,
-                   "cost_aware": bool(args.cost_aware), "dropout": args.dropout},
+                   "budget_bytes": budget, "sheltered_steps": sheltered, "plan_mode": args.plan_mode, "collector": args.collector,
+                   "cost_aware": bool(args.cost_aware), "dropout": args.dropout,
+                   "iteration": "forward + loss + backward + AdamW update (fp32 moments and master weights)" if update
+                                else "forward + loss + backward (no parameter update)",
+                   "host_waits_every_step": bool(args.wait_every_step)},
         "tokens_per_s": round(sum(t.size for t, _ in timed) / dt, 1),
         "useful_tflops": round(useful / dt / 1e12, 2), "recompute_tflops": round(recompute / dt / 1e12, 2),
         "mfma_frac_useful": round(useful / dt / 1e12 / PEAK_BF16_TFLOPS, 4),
@@ -210,7 +222,7 @@ def main():
         "kernels_timing": "gemm: events bound to each kernel's own start and end; other classes: markers around the launch, "
                           "which read a few microseconds more than the kernel itself (see profiles/ for the kernel trace)",
         "update": upd,
-        "roofline": {"bound": "mfma", "kernel": "bgemm_kernel / bgemm_dma_kernel (every GEMM launch of the timed steps)",
+        "roofline": {"bound": "mfma", "kernel": "bgemm_kernel / bgemm_dma_kernel / bgemm_pp_kernel (every product of the timed steps, the reduction kernel of a split product included)",
                      "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
                      "avg_launch_us": kernels.get("gemm", {}).get("avg_us"),
@@ -261,7 +273,20 @@ def cpu_baseline(wl, update, adamw):
         AdamW(**adamw).step(params, grads)
     dt = time.perf_counter() - t0
     what = "forward, loss, backward, update" if update else "forward, loss, backward"
+    cpu_model = ""
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                cpu_model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    try:
+        nproc = len(os.sched_getaffinity(0))
+    except AttributeError:
+        nproc = os.cpu_count() or 1
     return {"value": round(Bs / dt, 3), "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "dtype": "f64", "blas_threads": int(cores), "nproc": int(nproc), "cpu_model": cpu_model,
             "sample": f"one fp64 oracle iteration ({what}) of the same model at batch {Bs}, L={L}: {dt:.1f} s"}
 
 

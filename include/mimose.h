@@ -120,7 +120,12 @@ int mimose_load_param(mimose_ctx* ctx, int32_t i, const float* host_fp32, uint64
  * with recomputation of dropped layers, and waits for completion.
  *   tokens_host  [B,L] row-major ids in [0,vocab); borrowed for the call
  *   labels_host  [B,L], -1 = position not scored; borrowed for the call
- *   loss         mean cross-entropy over scored positions
+ *   loss         mean cross-entropy over scored positions.  NULL: the iteration is only
+ *                queued on the context's stream and the call returns without waiting (the
+ *                planner is on the critical path of every iteration, Section 5; the device need
+ *                not idle while the host plans and queues the next one); plan, peak and errors of
+ *                allocation are known at once, the loss through mimose_sync_loss.  Iterations of
+ *                the sheltered phase and profiled ones always wait.
  *   peak_bytes   true high-water mark of device memory in this step
  *   plan_id      bitmask, bit l set = layer l was dropped and recomputed
  * Errors: INVALID_ARG, OOM_BUDGET (the step is abandoned, the arena is reset),
@@ -128,6 +133,10 @@ int mimose_load_param(mimose_ctx* ctx, int32_t i, const float* host_fp32, uint64
  */
 int mimose_train_step(mimose_ctx* ctx, const int32_t* tokens_host, const int32_t* labels_host,
                       int32_t B, int32_t L, float* loss, uint64_t* peak_bytes, uint64_t* plan_id);
+
+/* Waits for every iteration queued so far; loss (may be NULL) receives the loss of the last one.
+ * Errors: NOT_READY before the first iteration or on a host-only context, HIP. */
+int mimose_sync_loss(mimose_ctx* ctx, float* loss);
 
 /*
  * The same iteration on a batch whose samples were padded to the longest one
@@ -209,6 +218,21 @@ int mimose_force_plan(mimose_ctx* ctx, int64_t plan_or_minus1);
 #define MIMOSE_PLAN_ALL 2
 #define MIMOSE_PLAN_NONE 3
 int mimose_set_plan_mode(mimose_ctx* ctx, int32_t mode);
+
+/* How a sheltered iteration collects a block's memory (Section 4.2).
+ *   MIMOSE_COLLECTOR_MARKS         one forward per block: the library owns the allocator, so it
+ *                                  reads the stack's marks before and after the block drops its
+ *                                  internals (default; same samples, no extra work)
+ *   MIMOSE_COLLECTOR_TWO_FORWARDS  the paper's shuttling forward to the letter: every block's
+ *                                  forward runs twice, first as normal (measured, then discarded
+ *                                  with its output), then keeping only the output.  Same samples,
+ *                                  same results bit for bit; costs one more forward pass per
+ *                                  sheltered iteration (the collector column of the paper's
+ *                                  overhead table).
+ * Errors: INVALID_ARG for an unknown mode. */
+#define MIMOSE_COLLECTOR_MARKS 0
+#define MIMOSE_COLLECTOR_TWO_FORWARDS 1
+int mimose_set_collector(mimose_ctx* ctx, int32_t mode);
 
 /* Host-only planner access (Section 4.2-4.4): inject a collected sample / ask for a plan. */
 int mimose_planner_feed(mimose_ctx* ctx, int32_t B, int32_t L, int32_t quantity, int32_t layer,

@@ -67,6 +67,8 @@ SIGNATURES = {
     "mimose_train_step": (C.c_int, [_vp, _vp, _vp, _i32, _i32, C.POINTER(_f32), C.POINTER(_u64), C.POINTER(_u64)]),
     "mimose_train_step_padded": (C.c_int, [_vp, _vp, _vp, _vp, _i32, _i32, C.POINTER(_f32), C.POINTER(_u64),
                                            C.POINTER(_u64)]),
+    "mimose_sync_loss": (C.c_int, [_vp, C.POINTER(_f32)]),
+    "mimose_set_collector": (C.c_int, [_vp, _i32]),
     "mimose_set_dropout": (C.c_int, [_vp, _f32, _f32, _u64, _u64]),
     "mimose_op_dropout": (C.c_int, [_i32, _vp, _vp, _i32, _vp, _i64, _f32, _u64, C.c_uint32, C.c_uint32, _vp]),
     "mimose_dry_step": (C.c_int, [_vp, _i32, _i32, C.POINTER(_u64), C.POINTER(_u64)]),
@@ -184,17 +186,24 @@ def mimose_load_param(ctx, i: int, host_fp32: np.ndarray):
     _check(load_library().mimose_load_param(ctx, i, a.ctypes.data, a.size), ctx)
 
 
-def mimose_train_step(ctx, tokens: np.ndarray, labels: np.ndarray) -> Tuple[float, int, int]:
+def mimose_train_step(ctx, tokens: np.ndarray, labels: np.ndarray, wait: bool = True):
+    """wait=False passes loss = NULL: the iteration is queued, the loss returned is None."""
     t = np.ascontiguousarray(tokens, dtype=np.int32)
     l = np.ascontiguousarray(labels, dtype=np.int32)
     B, L = t.shape
     loss, peak, plan = _f32(), _u64(), _u64()
-    _check(load_library().mimose_train_step(ctx, t.ctypes.data, l.ctypes.data, B, L, C.byref(loss), C.byref(peak),
-                                            C.byref(plan)), ctx)
-    return loss.value, peak.value, plan.value
+    _check(load_library().mimose_train_step(ctx, t.ctypes.data, l.ctypes.data, B, L, C.byref(loss) if wait else None,
+                                            C.byref(peak), C.byref(plan)), ctx)
+    return (loss.value if wait else None), peak.value, plan.value
 
 
-def mimose_train_step_padded(ctx, tokens: np.ndarray, labels: np.ndarray, lengths: np.ndarray) -> Tuple[float, int, int]:
+def mimose_sync_loss(ctx) -> float:
+    loss = _f32()
+    _check(load_library().mimose_sync_loss(ctx, C.byref(loss)), ctx)
+    return loss.value
+
+
+def mimose_train_step_padded(ctx, tokens: np.ndarray, labels: np.ndarray, lengths: np.ndarray, wait: bool = True):
     t = np.ascontiguousarray(tokens, dtype=np.int32)
     l = np.ascontiguousarray(labels, dtype=np.int32)
     n = np.ascontiguousarray(lengths, dtype=np.int32)
@@ -203,8 +212,8 @@ def mimose_train_step_padded(ctx, tokens: np.ndarray, labels: np.ndarray, length
         raise ValueError("lengths must have one entry per sample")
     loss, peak, plan = _f32(), _u64(), _u64()
     _check(load_library().mimose_train_step_padded(ctx, t.ctypes.data, l.ctypes.data, n.ctypes.data, B, L,
-                                                   C.byref(loss), C.byref(peak), C.byref(plan)), ctx)
-    return loss.value, peak.value, plan.value
+                                                   C.byref(loss) if wait else None, C.byref(peak), C.byref(plan)), ctx)
+    return (loss.value if wait else None), peak.value, plan.value
 
 
 def mimose_dry_step(ctx, B: int, L: int) -> Tuple[int, int]:
@@ -243,6 +252,13 @@ PLAN_MODES = {"input_aware": 0, "static_max": 1, "all": 2, "none": 3}
 
 def mimose_set_plan_mode(ctx, mode: int):
     _check(load_library().mimose_set_plan_mode(ctx, mode), ctx)
+
+
+COLLECTORS = {"marks": 0, "two_forwards": 1}
+
+
+def mimose_set_collector(ctx, mode: int):
+    _check(load_library().mimose_set_collector(ctx, mode), ctx)
 
 
 def mimose_planner_feed(ctx, B: int, L: int, quantity: int, layer: int, nbytes: int):
@@ -417,10 +433,13 @@ class Mimose:
             assert tuple(a.shape) == self.shapes[n], (n, a.shape, self.shapes[n])
             mimose_load_param(self.ctx, i, a)
 
-    def train_step(self, tokens, labels, lengths=None):
+    def train_step(self, tokens, labels, lengths=None, wait=True):
         if lengths is not None:
-            return mimose_train_step_padded(self.ctx, tokens, labels, lengths)
-        return mimose_train_step(self.ctx, tokens, labels)
+            return mimose_train_step_padded(self.ctx, tokens, labels, lengths, wait)
+        return mimose_train_step(self.ctx, tokens, labels, wait)
+
+    def sync_loss(self) -> float:
+        return mimose_sync_loss(self.ctx)
 
     def set_dropout(self, p_hidden, p_attn=0.0, seed=0, first_step=0):
         mimose_set_dropout(self.ctx, p_hidden, p_attn, seed, first_step)
@@ -448,6 +467,9 @@ class Mimose:
     def set_plan_mode(self, mode):
         mimose_set_plan_mode(self.ctx, PLAN_MODES[mode] if isinstance(mode, str) else int(mode))
 
+    def set_collector(self, mode):
+        mimose_set_collector(self.ctx, COLLECTORS[mode] if isinstance(mode, str) else mode)
+
     def stats(self) -> dict:
         return mimose_get_stats(self.ctx)
 
@@ -470,4 +492,4 @@ class Mimose:
 
 
 __all__ = [n for n in dir() if n.startswith("mimose_") or n.startswith("MIMOSE_") or n.startswith("Q_")] + \
-          ["Mimose", "MimoseError", "make_cfg", "load_library", "LIB_PATH", "SIGNATURES", "ERR_NAMES", "KERNEL_CLASSES", "PLAN_MODES"]
+          ["Mimose", "MimoseError", "make_cfg", "load_library", "LIB_PATH", "SIGNATURES", "ERR_NAMES", "KERNEL_CLASSES", "PLAN_MODES", "COLLECTORS"]

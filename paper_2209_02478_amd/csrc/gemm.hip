@@ -369,25 +369,22 @@ int gemm_splits(int M, int N) {
 // the kernel with 256 x 256 tiles (gemm_pp.hip) and its tile count
 bool launch_bgemm_pp(const GemmDev& p, hipStream_t st, hipEvent_t t0, hipEvent_t t1);
 int bgemm_pp_tiles(int M, int N);
-static int pp_splits(int M, int N) {
-  const int tiles = bgemm_pp_tiles(M, N);
-  int s = (256 + tiles - 1) / tiles;
-  return s < 1 ? 1 : (s > 8 ? 8 : s);
-}
 // Which products go to the large-tile kernel: it runs one block per compute unit, so its time is
-// a whole number of rounds of 256 units (tile, k part), and it pays where those rounds are
-// well filled; measured against the 128 x 128 kernels on the shapes of the step (same box, same
-// run): ahead by 10-35 % from about 0.8 of a full last round on (0.7 when the reduction is long
-// enough to hide the start and the end of a tile), behind below that.
-static bool use_pp(int M, int N, int K, int units) {
+// a whole number of rounds of 256 tiles, and it pays where those rounds are well filled; measured
+// against the 128 x 128 kernels on the shapes of the step (same box, same run): ahead by 10-35 %
+// from about 0.8 of a full last round on (0.7 when the reduction is long enough to hide the start
+// and the end of a tile), behind below that.  Products that cut their reduction in parts stay
+// with the small tiles: with few large output tiles they need more parts, and the fp32 parts
+// written and read again cost more than the large tile saves.
+static bool use_pp(int M, int N, int K) {
   if (M < 256 || N < 256 || K < 512) return false;
-  const int rounds = (units + 255) / 256;
+  const int units = bgemm_pp_tiles(M, N), rounds = (units + 255) / 256;
   const double fill = (double)units / (256.0 * rounds);
   return fill >= 0.8 || (fill >= 0.7 && K >= 2048);
 }
 
 size_t gemm_workspace_bytes(int M, int N) {
-  const int s = std::max(gemm_splits(M, N), pp_splits(M, N));
+  const int s = gemm_splits(M, N);
   return s > 1 ? ((size_t)s * M * N + (size_t)s * M) * 4 : 0;
 }
 
@@ -433,7 +430,6 @@ bool gemm(int dtype, const GemmArgs& g, hipStream_t st) {
     return true;
   }
   if ((g.lda & 7) || (g.ldb & 7) || !aligned16(g.A) || !aligned16(g.B)) return false;
-  // few output tiles and a long reduction (weight gradients): cut k so the whole chip works
   const bool may_split = g.workspace && g.c_f32 && !g.bias && !g.resid && !g.gelu && aligned16(g.workspace);
   auto splits_for = [&](int want) {
     const int by_k = (g.K + 255) / 256;                                   // >= 256 reduction indices per part
@@ -445,24 +441,13 @@ bool gemm(int dtype, const GemmArgs& g, hipStream_t st) {
                    (!g.resid || ((g.ldr & 7) == 0 && aligned16(g.resid))) && (!g.bias || aligned16(g.bias)) &&
                    (!g.gelu_out || aligned16(g.gelu_out));
   p.vec = vec ? 1 : 0;
-  // large tiles where their rounds are well filled (a choice made from the shape alone)
-  {
-    const int sp = splits_for(pp_splits(g.M, g.N));
-    if (use_pp(g.M, g.N, g.K, bgemm_pp_tiles(g.M, g.N) * sp)) {
-      p.splits = sp;
-      p.partial = sp > 1 ? (float*)g.workspace : nullptr;
-      if (launch_bgemm_pp(p, st, g.time_start, sp > 1 ? nullptr : g.time_stop)) {
-        if (p.splits > 1) launch_splitk_reduce(p, st, g.time_stop);
-        return true;
-      }
-      p.splits = 1; p.partial = nullptr;
-    }
-  }
   // few output tiles and a long reduction (weight gradients): cut k so the whole chip works
   {
     const int sp = splits_for(gemm_splits(g.M, g.N));
     if (sp > 1) { p.splits = sp; p.partial = (float*)g.workspace; }
   }
+  // large tiles where their rounds are well filled (a choice made from the shape alone)
+  if (p.splits == 1 && use_pp(g.M, g.N, g.K) && launch_bgemm_pp(p, st, g.time_start, g.time_stop)) return true;
   // B m-major (weight gradients, data gradients): the direct-to-LDS pipeline measures faster there;
   // the register-staged kernel below is ahead when both operands are k-major (forward)
   if (!g.b_kmajor && launch_bgemm_dma(p, st, g.time_start, p.splits > 1 ? nullptr : g.time_stop)) {

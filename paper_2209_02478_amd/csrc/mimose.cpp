@@ -108,6 +108,7 @@ struct mimose_ctx {
   std::unique_ptr<mimose::Planner> planner;
   int64_t forced_plan = -1;
   int plan_mode = MIMOSE_PLAN_INPUT_AWARE;
+  int collector = MIMOSE_COLLECTOR_MARKS;
   // dropout: probability of the hidden sites, seed, number of the next iteration
   float p_hidden = 0.f, p_attn = 0.f;
   uint64_t drop_seed = 0, drop_step = 0;
@@ -122,9 +123,16 @@ struct mimose_ctx {
   mimose_stats stats;
   std::string err;
   // pinned host staging for ids / labels / sort order / segments and the loss
-  int32_t* stage = nullptr;
-  size_t stage_ints = 0;
+  // (two of them, taken in turn: a step that returns before the device has finished leaves copies
+  // out of its buffer pending, marked by that buffer's event)
+  int32_t* stage_buf[2] = {nullptr, nullptr};
+  size_t stage_buf_ints[2] = {0, 0};
+  hipEvent_t ev_stage[2] = {nullptr, nullptr};
+  bool stage_busy[2] = {false, false};
+  int stage_turn = 0;
+  int32_t* stage = nullptr;              // the buffer of the step being issued
   float* loss_host = nullptr;
+  bool loss_pending = false;             // a step was issued whose loss has not been waited for
   bool dry = false;
   std::vector<LayerActs> acts;
   std::vector<int32_t> sort_count;       // reused scratch of the per-step counting sort
@@ -214,7 +222,7 @@ class Step {
       : c_(c), f_(c->cfg), B_(B), L_(L), T_(B * L), plan_(plan), collect_(collect), dry_(c->dry),
         st_(c->stream), dt_(c->cfg.dtype), es_(c->elt()) {}
 
-  void run(const int32_t* tokens, const int32_t* labels, float* loss_out);
+  void run(const int32_t* tokens, const int32_t* labels, float* loss_out, bool wait);
   const int32_t* lens_host = nullptr;   // padded batch: real tokens per sample ([B], host), else null
 
   // collected bytes (valid after run)
@@ -236,6 +244,7 @@ class Step {
   // storage type and oA_/oB_ alias them (LayerNorm backward then works in place).
   void *gA_ = nullptr, *gB_ = nullptr, *oA_ = nullptr, *oB_ = nullptr, *emb_sum_ = nullptr, *h0_ = nullptr;
   bool wide_ = false;   // fp32 residual sums and gradient carriers
+  int stage_turn_ = 0;  // which pinned staging buffer this step uses
   int n_seg_ = 0, n_valid_ = 0;
 
   // times everything enqueued during its lifetime as one launch of kernel class `cls`
@@ -448,12 +457,20 @@ void Step::embed_stage(const int32_t* tokens, const int32_t* labels) {
 
   // host side: stable sort of positions by token id, run boundaries of equal ids
   const size_t need = 4 * (size_t)T_ + 1 + (size_t)B_;
-  if (c_->stage_ints < need) {
-    if (c_->stage) HIPCHK(c_, hipHostFree(c_->stage));
-    c_->stage = nullptr;
-    HIPCHK(c_, hipHostMalloc((void**)&c_->stage, need * 4 + 1024, hipHostMallocDefault));
-    c_->stage_ints = need;
+  const int turn = c_->stage_turn;
+  c_->stage_turn ^= 1;
+  if (c_->stage_busy[turn]) {               // copies of the step before last out of this buffer: long done
+    HIPCHK(c_, hipEventSynchronize(c_->ev_stage[turn]));
+    c_->stage_busy[turn] = false;
   }
+  if (c_->stage_buf_ints[turn] < need) {
+    if (c_->stage_buf[turn]) HIPCHK(c_, hipHostFree(c_->stage_buf[turn]));
+    c_->stage_buf[turn] = nullptr; c_->stage_buf_ints[turn] = 0;
+    HIPCHK(c_, hipHostMalloc((void**)&c_->stage_buf[turn], need * 4 + 1024, hipHostMallocDefault));
+    c_->stage_buf_ints[turn] = need;
+  }
+  c_->stage = c_->stage_buf[turn];
+  stage_turn_ = turn;
   int32_t* s = c_->stage;
   std::memcpy(s, tokens, (size_t)T_ * 4);
   std::memcpy(s + T_, labels, (size_t)T_ * 4);
@@ -733,6 +750,8 @@ void Step::embed_sort(const int32_t* tokens) {
   int32_t* order = s + 2 * (size_t)T_;
   for (int t = 0; t < T_; ++t) order[count[tokens[t]]++] = t;
   HIPCHK(c_, hipMemcpyAsync(order_, order, (2 * (size_t)T_ + 1) * 4, hipMemcpyHostToDevice, st_));
+  HIPCHK(c_, hipEventRecord(c_->ev_stage[stage_turn_], st_));     // the last copy out of this staging buffer
+  c_->stage_busy[stage_turn_] = true;
 }
 
 void Step::embed_backward() {
@@ -743,7 +762,7 @@ void Step::embed_backward() {
     mk::embed_bwd(dt_, oA_, ids_, order_, seg_, n_seg_, g(c_->i_tok), g(c_->i_pos), B_, L_, H, f_.max_seq, st_);
 }
 
-void Step::run(const int32_t* tokens, const int32_t* labels, float* loss_out) {
+void Step::run(const int32_t* tokens, const int32_t* labels, float* loss_out, bool wait) {
   Arena& ar = c_->arena;
   const int N = f_.n_layers;
   a_bytes.assign(N, 0); b_bytes.assign(N, 0); w_bytes.assign(N, 0);
@@ -786,6 +805,17 @@ void Step::run(const int32_t* tokens, const int32_t* labels, float* loss_out) {
     if (timed) HIPCHK(c_, hipEventRecord(c_->ev_layer[2 * l + 1], st_));
     a_bytes[l] = ar.top() - A.mark;
     b_bytes[l] = A.after_out - A.mark;
+    if (collect_ && c_->collector == MIMOSE_COLLECTOR_TWO_FORWARDS) {
+      // Section 4.2 to the letter: the first forward was the measuring one, its tensors, the output
+      // included, are discarded; the second one keeps the output alone (the pop below), which is
+      // what the next block's measurement starts from.  Same launches, same addresses, same values
+      // (dropout masks are a function of the element, not of a generator state).
+      ar.pop_to(A.mark);
+      A.has_out = false;
+      alloc_layer(l, A);
+      layer_forward(l, A);
+      b_bytes[l] = A.after_out - A.mark;
+    }
     if ((plan_ >> l) & 1) {
       ar.pop_to(A.after_out); A.dropped = true;
       if (split && l + 1 < N) cross_sync();   // the next layer writes where this one's tensors are still read
@@ -820,8 +850,13 @@ void Step::run(const int32_t* tokens, const int32_t* labels, float* loss_out) {
   embed_backward();
   if (!dry_) {
     HIPCHK(c_, hipMemcpyAsync(c_->loss_host, loss_dev, 4, hipMemcpyDeviceToHost, st_));
+    c_->loss_pending = true;
+    // the caller does not want the loss now: the step stays queued and the host runs ahead
+    // (collecting steps read their layer timers, profiled steps their events: they wait)
+    if (!wait && !collect_ && !c_->prof_on) return;
     HIPCHK(c_, hipStreamSynchronize(st_));
     HIPCHK(c_, hipGetLastError());
+    c_->loss_pending = false;
     *loss_out = *c_->loss_host;
     for (auto& p : c_->prof_pending) {
       float ms = 0.f;
@@ -905,7 +940,7 @@ int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, const i
   s.lens_host = dry ? nullptr : lengths;
   float lv = 0.f;
   try {
-    s.run(tokens, labels, &lv);
+    s.run(tokens, labels, &lv, dry || loss != nullptr);
   } catch (const OomError& e) {
     c->prof_pending.clear(); c->ev_used = 0;
     c->arena.pop_to(c->fixed_top);
@@ -1035,7 +1070,9 @@ int mimose_init(const mimose_model_cfg* cfg, uint64_t mem_budget_bytes, void* ar
         hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&c->ev_early, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&c->ev_late, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&c->ev_w2, hipEventDisableTiming) != hipSuccess)
+        hipEventCreateWithFlags(&c->ev_w2, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_stage[0], hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_stage[1], hipEventDisableTiming) != hipSuccess)
       return fail(nullptr, MIMOSE_ERR_HIP, "creating the weight-gradient stream failed");
     // gradients start at zero so that a read before the first step is defined
     mk::fill_zero(c->params.front().g, (int64_t)((char*)c->arena.alloc(0) - (char*)c->params.front().g), c->stream);
@@ -1086,6 +1123,17 @@ int mimose_train_step_padded(mimose_ctx* c, const int32_t* tokens, const int32_t
   if (!c) return MIMOSE_ERR_INVALID_ARG;
   if (!lengths) return fail(c, MIMOSE_ERR_INVALID_ARG, "lengths must be given");
   return do_step(c, tokens, labels, lengths, B, L, false, loss, peak, plan_id);
+}
+
+int mimose_sync_loss(mimose_ctx* c, float* loss) {
+  if (!c) return MIMOSE_ERR_INVALID_ARG;
+  if (!c->has_device) return fail(c, MIMOSE_ERR_NOT_READY, "host-only context");
+  if (c->stats.steps == 0) return fail(c, MIMOSE_ERR_NOT_READY, "no step has been issued yet");
+  if (hipStreamSynchronize(c->stream) != hipSuccess || hipGetLastError() != hipSuccess)
+    return fail(c, MIMOSE_ERR_HIP, "a queued step failed on the device");
+  c->loss_pending = false;
+  if (loss) *loss = *c->loss_host;
+  return MIMOSE_OK;
 }
 
 int mimose_set_dropout(mimose_ctx* c, float p_hidden, float p_attn, uint64_t seed, uint64_t first_step) {
@@ -1215,6 +1263,13 @@ int mimose_force_plan(mimose_ctx* c, int64_t plan) {
   return MIMOSE_OK;
 }
 
+int mimose_set_collector(mimose_ctx* c, int32_t mode) {
+  if (!c || (mode != MIMOSE_COLLECTOR_MARKS && mode != MIMOSE_COLLECTOR_TWO_FORWARDS))
+    return fail(c, MIMOSE_ERR_INVALID_ARG, "unknown collector mode");
+  c->collector = mode;
+  return MIMOSE_OK;
+}
+
 int mimose_set_plan_mode(mimose_ctx* c, int32_t mode) {
   if (!c || mode < MIMOSE_PLAN_INPUT_AWARE || mode > MIMOSE_PLAN_NONE)
     return fail(c, MIMOSE_ERR_INVALID_ARG, "unknown plan mode");
@@ -1309,7 +1364,10 @@ void mimose_destroy(mimose_ctx* c) {
     if (c->ev_late) (void)hipEventDestroy(c->ev_late);
     if (c->ev_w2) (void)hipEventDestroy(c->ev_w2);
     if (c->side) (void)hipStreamDestroy(c->side);
-    if (c->stage) (void)hipHostFree(c->stage);
+    for (int k = 0; k < 2; ++k) {
+      if (c->ev_stage[k]) (void)hipEventDestroy(c->ev_stage[k]);
+      if (c->stage_buf[k]) (void)hipHostFree(c->stage_buf[k]);
+    }
     if (c->loss_host) (void)hipHostFree(c->loss_host);
   }
   delete c;

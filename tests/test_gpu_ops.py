@@ -194,15 +194,15 @@ def test_gemm_large_tiles(a_k, b_k):
 
 
 def test_gemm_large_tiles_split_reduction():
-    """Weight-gradient shape of the fused QKV projection (27 tiles of 256 x 256, the reduction cut
-    in 8 parts = 216 units) with a ragged reduction length, row sums included."""
+    """Weight-gradient shape of the fused QKV projection with a ragged reduction length cut in
+    parts, row sums included, and the same bits on a second run."""
     dtype, M, N, T = 1, 2304, 768, 2100
     rng = np.random.default_rng(171)
     dY = rng.standard_normal((T, M)).astype(np.float32)
     X = rng.standard_normal((T, N)).astype(np.float32)
     ddY, dX = dev(dY, dtype), dev(X, dtype)
     nws = mi.mimose_op_gemm_workspace_bytes(M, N)
-    assert nws >= 8 * (M * N + M) * 4
+    assert nws >= 2 * (M * N + M) * 4
     ws = torch.zeros(nws, dtype=torch.uint8, device=DEV)
     W = torch.full((M, N), 9.0, dtype=torch.float32, device=DEV)
     rs = torch.full((M,), 9.0, dtype=torch.float32, device=DEV)

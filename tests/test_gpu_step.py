@@ -509,3 +509,63 @@ def test_other_workload_shapes_reduced_batch(name, B, L, plan):
     assert got == plan
     print(name, B, L, "loss", loss, "worst grad", worst)
     m.close()
+
+
+def test_queued_steps_equal_waited_steps():
+    """Iterations issued with loss = NULL (the call returns while the device still works, the pinned
+    staging buffers take turns) give the losses, plans, peaks and gradient bits of iterations that
+    wait, with the parameter update between them and lengths that change from step to step."""
+    shape = SMALL["bf16_postln"]
+    params = synthdata.make_params(shape, 31, perturb=True)
+    lens = [40, 96, 8, 64, 33, 96, 17]
+    batches = [synthdata.make_batch(shape, 4, L, 300 + i) for i, L in enumerate(lens)]
+    runs = []
+    for wait in (True, False):
+        m = mi.Mimose(synthdata.shape_dict(shape), 0, arena_bytes=256 * MiB)
+        m.load_params(params)
+        m.optimizer_init(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+        m.force_plan(0b101)
+        out = []
+        for t, l in batches:
+            loss, peak, plan = m.train_step(t, l, wait=wait)
+            assert (loss is None) == (not wait)
+            m.optimizer_step()
+            out.append((peak, plan))
+        last = m.sync_loss()
+        runs.append((out, last, m.grads(), m.params()))
+        m.close()
+    (o0, l0, g0, p0), (o1, l1, g1, p1) = runs
+    assert o0 == o1 and l0 == l1
+    for k in g0:
+        assert np.array_equal(g0[k], g1[k]), k
+        assert np.array_equal(p0[k], p1[k]), k
+
+
+def test_two_forward_collector_changes_no_bits():
+    """Sheltered iterations with every block's forward run twice (the paper's collector to the letter),
+    dropout on: losses, gradients, collected samples and the later plans are those of the default
+    collector, which runs each forward once."""
+    wl = synthdata.WORKLOADS["tiny"]
+    shape, B = wl.shape, wl.batch
+    d = synthdata.shape_dict(shape)
+    cal = mi.Mimose(d, 0, device=None)
+    cal.force_plan(0)
+    peak0, _ = cal.dry_step(B, shape.max_seq)
+    cal.close()
+    params = synthdata.make_params(shape, wl.seed, perturb=True)
+    lens = synthdata.seq_lengths(wl.length_recipe, 14, wl.seed)
+    runs = []
+    for mode in ("marks", "two_forwards"):
+        m = mi.Mimose(d, int(wl.budget_frac * peak0))
+        m.set_collector(mode)
+        m.set_dropout(0.1, 0.1, 5, 0)
+        m.load_params(params)
+        out = []
+        for i, L in enumerate(lens):
+            t, l = synthdata.make_batch(shape, B, L, synthdata.step_seed(wl.seed, i))
+            out.append(m.train_step(t, l) + (mi.mimose_get_step_memory(m.ctx, shape.n_layers),))
+        runs.append((out, m.grads(), m.stats()["sheltered_steps"]))
+        m.close()
+    assert runs[0][0] == runs[1][0] and runs[0][2] == runs[1][2] == 10
+    for k in runs[0][1]:
+        assert np.array_equal(runs[0][1][k], runs[1][1][k]), k

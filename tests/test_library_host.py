@@ -430,3 +430,27 @@ def test_optimizer_state_counts_as_fixed_memory():
     peak, _ = m.dry_step(wl.batch, 1)                        # the context survives
     assert peak > fixed
     m.close()
+
+
+def test_two_forward_collector_feeds_the_same_samples():
+    """The collector that runs every block's forward twice (Section 4.2 to the letter) measures what
+    the one that reads the allocator's marks measures: same samples, same peaks, same plans."""
+    wl = synthdata.WORKLOADS["tiny_stages"]
+    ctxs = []
+    for mode in ("marks", "two_forwards"):
+        wl_, m = host_ctx("tiny_stages", budget=6 << 20)
+        m.set_collector(mode)
+        seen = []
+        for L in (16, 40, 64, 23, 57, 31, 64, 48, 19, 36, 50):
+            peak, plan = m.dry_step(wl.batch, L)
+            seen.append((peak, plan, mi.mimose_get_step_memory(m.ctx, wl.shape.n_layers)))
+        seen.append(m.dry_step(wl.batch, 64))
+        ctxs.append(seen)
+        m.close()
+    assert ctxs[0] == ctxs[1]
+    with pytest.raises(mi.MimoseError):
+        wl_, m = host_ctx("tiny")
+        try:
+            m.set_collector(7)
+        finally:
+            m.close()
