@@ -60,6 +60,11 @@ def main():
     ap.add_argument("--collector", default="marks", choices=["marks", "two_forwards"],
                     help="how the sheltered iterations measure a block: from the allocator's marks in one forward (default), "
                          "or with the paper's two forwards per block (Section 4.2), whose cost the overhead object then shows")
+    ap.add_argument("--hbm-kernels", action="store_true",
+                    help="instead of the training run: launch every HBM-bound kernel of the step on its own, through the "
+                         "kernel-level entry points, at the BERT-base median size and at the BERT-large stress size, and "
+                         "print their algorithmic bytes, durations and GB/s (run it under rocprofv3 --kernel-trace for the "
+                         "kernels' own durations)")
     ap.add_argument("--wait-every-step", action="store_true",
                     help="read the loss after every iteration (the host blocks until the device is done) instead of "
                          "queueing the timed iterations one after the other and reading the loss once at the end")
@@ -79,6 +84,9 @@ def main():
     if not os.path.exists(mi.LIB_PATH):
         from paper_2209_02478_amd import build as b
         b.build(verbose=False)
+    if args.hbm_kernels:
+        print(json.dumps(hbm_kernels(mi, torch)))
+        return
     wl = synthdata.WORKLOADS[args.workload]
     shape, B, N = wl.shape, wl.batch, wl.shape.n_layers
     d = synthdata.shape_dict(shape)
@@ -245,6 +253,86 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, update, adamw)
     print(json.dumps(out))
+
+
+def hbm_kernels(mi, torch):
+    """Every HBM-bound kernel alone, bf16, at (T, H, F, V) of the BERT-base median batch (B=32, L=200) and of
+    the BERT-large stress batch (B=256, L=512).  Each launch works on buffers of its own, enough of them to
+    exceed the 256 MB last-level cache, so the bytes come from HBM.  Algorithmic bytes per token: LayerNorm
+    forward 4H (6H from an fp32 sum), backward 6H bf16 (10H with fp32 gradient and input), GELU backward 6F,
+    softmax cross-entropy 4V (in place), embedding forward 6H + 4."""
+    dev = "cuda:0"
+    bf, f32 = torch.bfloat16, torch.float32
+    rows = []
+
+    def timed(name, size, bytes_per_launch, n_sets, launch):
+        for k in range(min(n_sets, 3)):
+            launch(k)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = max(n_sets, 10)
+        e0.record()
+        for k in range(reps):
+            launch(k % n_sets)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        rows.append({"kernel": name, "size": size, "bytes_per_launch": int(bytes_per_launch), "launches": reps,
+                     "avg_us_events": round(us, 2), "gbs": round(bytes_per_launch / (us * 1e-6) / 1e9, 1),
+                     "frac_of_8TBs": round(bytes_per_launch / (us * 1e-6) / 8e12, 3)})
+
+    for tag, T, H, F, V in (("bert_base median: T=6400 H=768 F=3072 V=30522", 6400, 768, 3072, 30522),
+                            ("bert_large stress: T=131072 H=1024 F=4096 V=30522", 131072, 1024, 4096, 30522)):
+        def sets(bytes_one):                      # buffers sets so that the rotation exceeds 512 MB, at most 64
+            return int(max(2, min(64, (512 << 20) // max(bytes_one, 1) + 1)))
+        gam = torch.ones(H, dtype=bf, device=dev); bet = torch.zeros(H, dtype=bf, device=dev)
+        # LayerNorm forward, bf16 rows and fp32 rows (the unrounded residual sum of post-LN blocks)
+        n = sets(T * H * 4)
+        xs = [torch.randn(T, H, device=dev).to(bf) for _ in range(n)]
+        ys = [torch.empty(T, H, dtype=bf, device=dev) for _ in range(n)]
+        timed("layernorm_fwd bf16", tag, 4 * H * T, n, lambda k: mi.mimose_op_layernorm_fwd(1, xs[k], 0, gam, bet, ys[k], T, H, 1e-5))
+        n = sets(T * H * 6)
+        xw = [torch.randn(T, H, device=dev) for _ in range(n)]
+        timed("layernorm_fwd fp32 rows in", tag, 6 * H * T, n, lambda k: mi.mimose_op_layernorm_fwd(1, xw[k], 1, gam, bet, ys[k % len(ys)], T, H, 1e-5))
+        # LayerNorm backward: fp32 gradient and input (post-LN blocks) and all-bf16
+        part = torch.empty(mi.mimose_op_partial_rows(T) * 2 * H, dtype=f32, device=dev)
+        dg = torch.empty(H, dtype=f32, device=dev); db = torch.empty(H, dtype=f32, device=dev)
+        n = sets(T * H * 10)
+        dyw = [torch.randn(T, H, device=dev) for _ in range(n)]
+        dxs = [torch.empty(T, H, dtype=bf, device=dev) for _ in range(n)]
+        timed("layernorm_bwd fp32 dy and x in", tag, 10 * H * T, n,
+              lambda k: mi.mimose_op_layernorm_bwd(1, dyw[k], 1, xw[k % len(xw)], 1, gam, dxs[k], None, dg, db, part, T, H, 1e-5))
+        timed("layernorm_bwd bf16", tag, 6 * H * T, len(xs),
+              lambda k: mi.mimose_op_layernorm_bwd(1, xs[k], 0, ys[k], 0, gam, dxs[k % len(dxs)], None, dg, db, part, T, H, 1e-5))
+        del xw, dyw, dxs, xs, ys
+        # GELU backward in place
+        n = sets(T * F * 4)
+        ds = [torch.randn(T, F, device=dev).to(bf) for _ in range(n)]
+        ps = [torch.randn(T, F, device=dev).to(bf) for _ in range(n)]
+        timed("gelu_bwd", tag, 6 * F * T, n, lambda k: mi.mimose_op_gelu_bwd(1, ds[k], ps[k], T * F, 0))
+        del ds, ps
+        # softmax cross-entropy in place (the stress size in chunks of 16384 rows: the logits of 131072 tokens are 8 GB)
+        Tx = min(T, 16384)
+        ldv = (V + 63) // 64 * 64
+        n = sets(Tx * ldv * 2)
+        lg = [torch.randn(Tx, ldv, device=dev).to(bf) for _ in range(n)]
+        lab = torch.randint(0, V, (Tx,), dtype=torch.int32, device=dev)
+        rl = torch.empty(Tx, dtype=f32, device=dev); ls = torch.empty(1, dtype=f32, device=dev)
+        timed("softmax_xent", tag if Tx == T else tag + " (rows 16384 at a time)", 4 * ldv * Tx, n,
+              lambda k: mi.mimose_op_softmax_xent(1, lg[k], ldv, lab, rl, ls, Tx, V, Tx))
+        del lg
+        # embedding forward with LayerNorm
+        L = 200 if T == 6400 else 512
+        B = T // L
+        tok = torch.randn(V, H, device=dev).to(bf); pos = torch.randn(512, H, device=dev).to(bf)
+        ids = torch.randint(0, V, (T,), dtype=torch.int32, device=dev)
+        n = sets(T * H * 4)
+        so = [torch.empty(T, H, dtype=bf, device=dev) for _ in range(n)]
+        yo = [torch.empty(T, H, dtype=bf, device=dev) for _ in range(n)]
+        timed("embed_fwd", tag, (6 * H + 4) * T, n, lambda k: mi.mimose_op_embed_fwd(1, ids, tok, pos, gam, bet, so[k], yo[k], B, L, H, 1e-5, 1))
+        del so, yo
+    return {"what": "HBM-bound kernels alone, bf16, buffers rotated past the last-level cache; durations from events around "
+                    "the launches (a kernel trace of the same command gives the kernels' own)", "peak_gbs": 8000, "kernels": rows}
 
 
 def cpu_baseline(wl, update, adamw):

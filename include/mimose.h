@@ -78,6 +78,9 @@ typedef struct {
   /* estimator + scheduler time of the iterations that had to generate a plan (cache misses),
    * for the overhead accounting of Section 6.4; min is 0 until the first miss */
   uint64_t plan_gen_count, plan_gen_ns_total, plan_gen_ns_min, plan_gen_ns_max;
+  /* iterations whose cached plan did not fit (the estimator under-predicted): the plan was
+   * dropped, the key planned again against the missing bytes, the iteration issued again */
+  uint64_t replans;
 } mimose_stats;
 
 /* quantities of the collector's sample table (Section 4.2), see mimose_planner_feed */
@@ -128,6 +131,9 @@ int mimose_load_param(mimose_ctx* ctx, int32_t i, const float* host_fp32, uint64
  *                the sheltered phase and profiled ones always wait.
  *   peak_bytes   true high-water mark of device memory in this step
  *   plan_id      bitmask, bit l set = layer l was dropped and recomputed
+ * A planner-made plan that turns out not to fit (the estimator under-predicted) is dropped from
+ * the cache, the size is planned again against the bytes that were missing and the iteration is
+ * issued once more, as long as that selects more layers (stats.replans counts these).
  * Errors: INVALID_ARG, OOM_BUDGET (the step is abandoned, the arena is reset),
  * BUDGET_INFEASIBLE, HIP, NOT_READY (host-only context).
  */

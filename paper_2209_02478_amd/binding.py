@@ -39,7 +39,7 @@ class mimose_stats(C.Structure):
                 ("useful_flops_last", "recompute_flops_last", "useful_flops_total", "recompute_flops_total")] + \
                [(n, C.c_uint64) for n in
                 ("peak_bytes_last", "peak_bytes_max", "predicted_peak_last", "fixed_bytes", "budget_bytes",
-                 "plan_gen_count", "plan_gen_ns_total", "plan_gen_ns_min", "plan_gen_ns_max")]
+                 "plan_gen_count", "plan_gen_ns_total", "plan_gen_ns_min", "plan_gen_ns_max", "replans")]
 
     def as_dict(self) -> dict:
         return {n: getattr(self, n) for n, _ in self._fields_}

@@ -35,15 +35,31 @@ template <typename T> __device__ __forceinline__ float rnd(float v);
 template <> __device__ __forceinline__ float rnd<float>(float v) { return v; }
 template <> __device__ __forceinline__ float rnd<bf16_t>(float v) { return bf16_to_f32(f32_to_bf16(v)); }
 
+// Sums (maxima) over the 64 lanes of a wave, the result in every lane.  Inside a row of 16 lanes
+// four rotating DPP adds (by 8, 4, 2, 1) leave the row's total in each of its lanes; the four
+// rows are then read through scalar registers and combined in row order.  A butterfly of
+// cross-lane shuffles costs six dependent trips through the LDS crossbar instead, which is what
+// the row-wise kernels spent most of their time on.  The order of the additions is fixed.
+template <int CTRL>
+__device__ __forceinline__ float dpp_rotate(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float lane_value(float v, int lane) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  v += dpp_rotate<0x128>(v);   // row_ror:8
+  v += dpp_rotate<0x124>(v);   // row_ror:4
+  v += dpp_rotate<0x122>(v);   // row_ror:2
+  v += dpp_rotate<0x121>(v);   // row_ror:1
+  return ((lane_value(v, 0) + lane_value(v, 16)) + lane_value(v, 32)) + lane_value(v, 48);
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
+  v = fmaxf(v, dpp_rotate<0x128>(v));
+  v = fmaxf(v, dpp_rotate<0x124>(v));
+  v = fmaxf(v, dpp_rotate<0x122>(v));
+  v = fmaxf(v, dpp_rotate<0x121>(v));
+  return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
 }
 
 __device__ __forceinline__ float gelu_erf(float x) {

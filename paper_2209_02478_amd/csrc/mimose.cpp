@@ -906,8 +906,8 @@ int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, const i
   // ---- plan (host only, on the critical path of every iteration)
   const auto t0 = std::chrono::steady_clock::now();
   uint64_t plan = 0;
-  bool collect = false, generated = false;
-  int64_t predicted = 0;
+  bool collect = false, generated = false, planned = false;
+  int64_t predicted = 0, xq_planned = 0;
   if (c->forced_plan >= 0) {
     plan = (uint64_t)c->forced_plan & all;
   } else if (c->plan_mode == MIMOSE_PLAN_ALL) {
@@ -931,6 +931,8 @@ int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, const i
       return fail(c, MIMOSE_ERR_BUDGET_INFEASIBLE, "predicted peak exceeds the budget even with every layer checkpointed");
     }
     plan = po.plan;
+    planned = true;
+    xq_planned = xq;
   }
   const uint64_t ns = (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
                           std::chrono::steady_clock::now() - t0).count();
@@ -945,6 +947,17 @@ int do_step(mimose_ctx* c, const int32_t* tokens, const int32_t* labels, const i
     c->prof_pending.clear(); c->ev_used = 0;
     c->arena.pop_to(c->fixed_top);
     if (!dry && c->has_device) { if (c->side) (void)hipStreamSynchronize(c->side); (void)hipStreamSynchronize(c->stream); }
+    // A plan of the planner's own that does not fit means the estimator under-predicted (the paper
+    // keeps 0.5-1 GB free for that, Section 6.4).  The cached plan would fail again on every batch
+    // of this size, so it is dropped and the key planned anew against what was missing; the
+    // iteration is then issued again, as long as that yields a plan with more layers.
+    if (planned && plan != all) {
+      mimose::PlanOut po;
+      if (c->planner->replan(xq_planned, (int64_t)(e.top + e.want - e.cap), plan, &po)) {
+        c->stats.replans++;
+        return do_step(c, tokens, labels, lengths, B, L, dry, loss, peak, plan_id);
+      }
+    }
     char buf[160];
     snprintf(buf, sizeof buf, "allocation of %llu bytes at %llu exceeds the budget of %llu bytes",
              (unsigned long long)e.want, (unsigned long long)e.top, (unsigned long long)e.cap);

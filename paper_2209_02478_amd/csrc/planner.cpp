@@ -246,10 +246,31 @@ int Planner::query(int64_t x, PlanOut* out, bool* hit) {
   ++misses;
   if (hit) *hit = false;
   const Components c = predict(key);
-  const int64_t eff = budget_ > 0 ? budget_ - reserve_ : 0;
+  auto sh = short_.find(key);
+  const int64_t eff = budget_ > 0 ? std::max<int64_t>(1, budget_ - reserve_ - (sh == short_.end() ? 0 : sh->second)) : 0;
   *out = schedule(c, eff, tol_, cost_aware_);
   cache_[key] = *out;
   return out->feasible ? 0 : -2;
+}
+
+bool Planner::replan(int64_t x, int64_t over, uint64_t old_plan, PlanOut* out) {
+  if (budget_ <= 0 || (!fitted_ && !fit_all())) return false;
+  const int64_t key = key_of(x);
+  cache_.erase(key);
+  const Components c = predict(key);
+  const int64_t step = std::max<int64_t>(std::max<int64_t>(over, 0) + guard_, budget_ / 64);
+  for (int tries = 0; tries < 64; ++tries) {
+    short_[key] += step;
+    const int64_t eff = budget_ - reserve_ - short_[key];
+    if (eff <= 0) break;
+    const PlanOut po = schedule(c, eff, tol_, cost_aware_);
+    if (po.plan != old_plan) {
+      cache_[key] = po;
+      *out = po;
+      return true;
+    }
+  }
+  return false;
 }
 
 }  // namespace mimose

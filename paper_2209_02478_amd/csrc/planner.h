@@ -57,6 +57,11 @@ class Planner {
   // 0 ok, -1 estimator not ready, -2 infeasible (out still filled with the all-layers plan)
   int query(int64_t x, PlanOut* out, bool* hit);
   int64_t key_of(int64_t x) const;
+  // A step run under the cached plan of x (old_plan) needed at least `over` bytes more than the
+  // budget: the estimator under-predicted.  Forgets that plan and plans this key against a budget
+  // lowered step by step (by what was missing, at least 1/64 of the budget) until Algorithm 1,
+  // continuing from the larger excess, selects another set.  False when no other plan exists.
+  bool replan(int64_t x, int64_t over, uint64_t old_plan, PlanOut* out);
   Components predict(int64_t x);
   uint64_t hits = 0, misses = 0;
   size_t cache_entries() const { return cache_.size(); }
@@ -74,6 +79,7 @@ class Planner {
   std::map<std::pair<int, int>, PolyFit> series_;
   bool fitted_ = false;
   std::unordered_map<int64_t, PlanOut> cache_;
+  std::unordered_map<int64_t, int64_t> short_;   // per key: bytes by which earlier plans fell short
 };
 
 }  // namespace mimose

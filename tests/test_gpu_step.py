@@ -569,3 +569,47 @@ def test_two_forward_collector_changes_no_bits():
     assert runs[0][0] == runs[1][0] and runs[0][2] == runs[1][2] == 10
     for k in runs[0][1]:
         assert np.array_equal(runs[0][1][k], runs[1][1][k]), k
+
+
+@pytest.mark.parametrize("name,responsive", [("bert_large", 6), ("gpt2_medium", 6), ("bert_large_stress", 6)])
+def test_larger_workloads_on_device_under_their_budget(name, responsive):
+    """The larger workloads with their own batch size, length recipe and budget fraction on the
+    device: the sheltered phase and some responsive iterations.  Every measured peak stays under the
+    budget, equals the peak model on the measured components, and every plan is the oracle planner's
+    for the same samples; the loss sits at its closed-form initial value."""
+    wl = synthdata.WORKLOADS[name]
+    shape, B, n = wl.shape, wl.batch, wl.shape.n_layers
+    d = synthdata.shape_dict(shape)
+    cal = mi.Mimose(d, 0, device=None)
+    cal.force_plan(0)
+    peak0, _ = cal.dry_step(B, shape.max_seq)
+    cal.close()
+    budget = int(wl.budget_frac * peak0)
+    m = mi.Mimose(d, budget)
+    m.load_params(synthdata.make_params(shape, wl.seed))
+    ref = op.Planner(n, budget, guard=4096)
+    lens = synthdata.seq_lengths(wl.length_recipe, 10 + responsive, wl.seed)
+    lens[10] = shape.max_seq                       # the longest input among the responsive ones
+    expect = np.log(shape.vocab) + 0.5 * 0.02 ** 2 * shape.hidden
+    nonempty = 0
+    for i, L in enumerate(lens):
+        tokens, labels = synthdata.make_batch(shape, B, int(L), synthdata.step_seed(wl.seed, i))
+        sheltered = ref.sheltered()
+        loss, peak, plan = m.train_step(tokens, labels)
+        print(name, "step", i, "L", int(L), "plan", bin(plan), "peak/budget", round(peak / budget, 4), flush=True)
+        assert peak <= budget and abs(loss - expect) < 0.03 * expect
+        mem = m.step_memory()
+        c = op.Components(F=mem["F"], e=mem["e"], g=mem["g"], a=mem["a"], b=mem["b"], w=mem["w"])
+        assert peak == op.simulate_peak(c, plan)
+        x = B * int(L)
+        if sheltered:
+            assert plan == (1 << n) - 1
+            for l in range(n):
+                ref.feed(x, op.Q_A, l, c.a[l]); ref.feed(x, op.Q_B, l, c.b[l]); ref.feed(x, op.Q_W, l, c.w[l])
+            ref.feed(x, op.Q_E, -1, c.e); ref.feed(x, op.Q_G, -1, c.g); ref.feed(x, op.Q_F, -1, c.F)
+            ref.end_sheltered_step(x)
+        else:
+            assert plan == ref.query(x).plan
+            nonempty += plan != 0
+    assert nonempty >= 1 and m.stats()["replans"] == 0
+    m.close()

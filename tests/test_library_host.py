@@ -454,3 +454,42 @@ def test_two_forward_collector_feeds_the_same_samples():
             m.set_collector(7)
         finally:
             m.close()
+
+
+def test_underpredicted_plan_is_dropped_and_replanned():
+    """Samples fed to the estimator that understate every layer's kept bytes give a plan that does not
+    fit when the step allocates for real.  The library drops that plan from its cache, plans the
+    size again against the bytes that were missing and issues the step again; the batch, and every
+    later batch of that size, then runs under the budget with more layers checkpointed."""
+    wl = synthdata.WORKLOADS["tiny"]
+    shape, B, n = wl.shape, wl.batch, wl.shape.n_layers
+    d = synthdata.shape_dict(shape)
+    # the true components, from a context without budget
+    ref = mi.Mimose(d, 0, device=None)
+    ref.force_plan(0)
+    peak0, _ = ref.dry_step(B, 64)
+    true = {}
+    for L in (16, 32, 48, 64):
+        ref.dry_step(B, L)
+        true[L] = mi.mimose_get_step_memory(ref.ctx, n)
+    ref.close()
+    budget = int(0.8 * peak0)
+    m = mi.Mimose(d, budget, device=None)
+    for L, c in true.items():                      # kept bytes understated by 30 %: too few layers get chosen
+        for l in range(n):
+            mi.mimose_planner_feed(m.ctx, B, L, mi.Q_LAYER_KEPT, l, int(0.7 * c["a"][l]))
+            mi.mimose_planner_feed(m.ctx, B, L, mi.Q_LAYER_BOUNDARY, l, c["b"][l])
+            mi.mimose_planner_feed(m.ctx, B, L, mi.Q_LAYER_BWD, l, c["w"][l])
+        mi.mimose_planner_feed(m.ctx, B, L, mi.Q_EMBED, -1, c["e"])
+        mi.mimose_planner_feed(m.ctx, B, L, mi.Q_HEAD, -1, c["g"])
+        mi.mimose_planner_feed(m.ctx, B, L, mi.Q_FIXED, -1, c["F"])
+    for L in (16, 32, 48, 64, 16, 32, 48, 64, 16, 32):
+        mi.mimose_planner_end_step(m.ctx, B, L)
+    naive, _ = mi.mimose_planner_query(m.ctx, B, 64)
+    peak, plan = m.dry_step(B, 64)
+    assert peak <= budget and bin(plan).count("1") > bin(naive).count("1")
+    st = m.stats()
+    assert st["replans"] >= 1
+    peak2, plan2 = m.dry_step(B, 64)               # the repaired plan is the cached one now
+    assert (peak2, plan2) == (peak, plan) and m.stats()["replans"] == st["replans"]
+    m.close()
