@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--dropout", type=float, default=0.0,
                     help="dropout probability of the attention probabilities and of the hidden sites (embedding output, attention and feed-forward "
                          "block outputs), masks from the counter-based generator; 0 = off, the measured default")
+    ap.add_argument("--size-quantum", type=int, default=1,
+                    help="plan-cache key granularity in tokens (Section 5: similar input sizes share a plan): a batch of x tokens "
+                         "uses the plan made for x rounded up to a multiple of this; 1 = exact sizes")
     ap.add_argument("--collector", default="marks", choices=["marks", "two_forwards"],
                     help="how the sheltered iterations measure a block: from the allocator's marks in one forward (default), "
                          "or with the paper's two forwards per block (Section 4.2), whose cost the overhead object then shows")
@@ -104,7 +107,7 @@ def main():
     if args.plan_mode == "none":                      # the no-checkpoint limit needs the whole peak
         m = mi.Mimose(d, 0, arena_bytes=peak0 + (1 << 20))
     else:
-        m = mi.Mimose(d, budget, cost_aware=int(args.cost_aware))
+        m = mi.Mimose(d, budget, cost_aware=int(args.cost_aware), size_quantum=args.size_quantum)
     m.set_plan_mode(args.plan_mode)
     m.set_collector(args.collector)
     m.load_params(synthdata.make_params(shape, wl.seed))
@@ -212,7 +215,7 @@ def main():
                                f"vocab {shape.vocab}, batch {B}, per-batch length {wl.length_recipe}, "
                                f"budget {wl.budget_frac:.2f} x no-checkpoint peak at L={shape.max_seq}",
                    "global_batch": B, "mean_seq_len": round(float(np.mean([t.shape[1] for t, _ in timed])), 1),
-                   "budget_bytes": budget, "sheltered_steps": sheltered, "plan_mode": args.plan_mode, "collector": args.collector,
+                   "budget_bytes": budget, "sheltered_steps": sheltered, "plan_mode": args.plan_mode, "collector": args.collector, "size_quantum": args.size_quantum,
                    "cost_aware": bool(args.cost_aware), "dropout": args.dropout,
                    "iteration": "forward + loss + backward + AdamW update (fp32 moments and master weights)" if update
                                 else "forward + loss + backward (no parameter update)",
