@@ -43,9 +43,8 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 // below (the compiler's own tracking drains the whole ring once per turn).
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"      // m0 is a reserved register: named as clobbered on purpose
-__device__ __forceinline__ void direct_load(const bf16_t* g, const bf16_t* lds) {
-  const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void*)lds);
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(base) : "memory", "m0");
+__device__ __forceinline__ void direct_load(const bf16_t* g, uint32_t lds_byte_address) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_byte_address) : "memory", "m0");
 }
 #pragma clang diagnostic pop
 
@@ -147,7 +146,8 @@ __global__ __launch_bounds__(256, 3) void bgemm_dma_kernel(GemmDev p, int tiles_
   const int gsize = min(tiles_m - first_m, GROUP_M);
   const int in_group = t - group * GROUP_M * tiles_n;
   const int tile_m = first_m + in_group % gsize, tile_n = in_group / gsize;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);          // wave-uniform: LDS addresses of the loads stay scalar
   const int wm = wave >> 1, wn = wave & 1;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
@@ -174,21 +174,28 @@ __global__ __launch_bounds__(256, 3) void bgemm_dma_kernel(GemmDev p, int tiles_
     srcA[j] = make_src<AK>((const bf16_t*)p.A, p.lda, p.M, m0, kt_begin * BK, slot);
     srcB[j] = make_src<BKM>((const bf16_t*)p.B, p.ldb, p.N, n0, kt_begin * BK, slot);
   }
-  auto issue = [&](bf16_t* stage, int kt) {                           // k tile kt (relative) -> ring stage
-    bf16_t* a_stage = stage;
-    bf16_t* b_stage = stage + TILE_ELEMS;
+  // LDS side of a load: byte address of the ring + stage + this wave's share, all scalar, so that
+  // issuing a load is an M0 write, the load itself and a pointer increment
+  const uint32_t ring_lds = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void*)ring) +
+                            (uint32_t)wave * DMA_PER_WAVE * 1024u;
+  int k_issue = 0;                                                    // reduction offset of the next tile to issue
+  auto issue = [&](int stage_index) {                                 // the next k tile -> ring stage
+    const uint32_t a_lds = ring_lds + (uint32_t)stage_index * (STAGE_ELEMS * 2u);
+    const uint32_t b_lds = a_lds + TILE_ELEMS * 2u;
 #pragma unroll
     for (int j = 0; j < DMA_PER_WAVE; ++j) {
-      const bf16_t* ga = srcA[j].p + kt * srcA[j].step;
-      const bf16_t* gb = srcB[j].p + kt * srcB[j].step;
+      const bf16_t* ga = srcA[j].p;
+      const bf16_t* gb = srcB[j].p;
       if (KTAIL) {                                                    // chunks past K read zeros
-        if (srcA[j].k_first + kt * BK >= p.K) ga = (const bf16_t*)g_zero_chunk;
-        if (srcB[j].k_first + kt * BK >= p.K) gb = (const bf16_t*)g_zero_chunk;
+        if (srcA[j].k_first + k_issue >= p.K) ga = (const bf16_t*)g_zero_chunk;
+        if (srcB[j].k_first + k_issue >= p.K) gb = (const bf16_t*)g_zero_chunk;
       }
-      const int off = (wave * DMA_PER_WAVE + j) * 512;                // elements: 1 KB per wave-level load
-      direct_load(ga, a_stage + off);
-      direct_load(gb, b_stage + off);
+      direct_load(ga, a_lds + (uint32_t)j * 1024u);
+      direct_load(gb, b_lds + (uint32_t)j * 1024u);
+      srcA[j].p += srcA[j].step;
+      srcB[j].p += srcB[j].step;
     }
+    k_issue += BK;
   };
   // The MFMAs of a tile's second k half are held back until the next tile's first fragments have
   // been requested (after that tile's barrier), so the matrix pipe has work while they travel.
@@ -235,15 +242,15 @@ __global__ __launch_bounds__(256, 3) void bgemm_dma_kernel(GemmDev p, int tiles_
   constexpr int PER_TILE = 2 * DMA_PER_WAVE;                          // direct loads per thread and k tile
   static_assert(STAGES == 3, "one newer tile in flight while a tile is multiplied");
   if (nk > 0) {
-    issue(ring, 0);
-    if (nk > 1) issue(ring + STAGE_ELEMS, 1);
+    issue(0);
+    if (nk > 1) issue(1);
     int cur = 0;                                                      // stage of tile kt
     for (int kt = 0; kt < nk; ++kt) {
       if (kt + 1 < nk) __builtin_amdgcn_s_waitcnt(vmcnt_imm(PER_TILE));
       else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
       __builtin_amdgcn_s_barrier();
       const int fill = cur == 0 ? 2 : cur - 1;                        // stage of tile kt - 1 == stage of tile kt + 2
-      if (kt + 2 < nk) issue(ring + fill * STAGE_ELEMS, kt + 2);
+      if (kt + 2 < nk) issue(fill);
       compute(ring + cur * STAGE_ELEMS);
       cur = cur == 2 ? 0 : cur + 1;
     }
