@@ -285,6 +285,9 @@ void mimose_destroy(mimose_ctx* ctx);
  * Kernel-level entry points (device pointers, current device, given stream).
  * These are the kernels the training step is made of, exposed for parity tests
  * and per-kernel measurement.  dtype as in mimose_model_cfg.  No allocation.
+ * They have no counterpart in the paper, which runs stock library kernels under
+ * its planner and describes none of its own: what each computes is the model's
+ * standard operation named in its comment.
  * ---------------------------------------------------------------------- */
 
 /* C[M,N] = sum_k A(m,k) B(n,k) (+ bias[n]) (+ resid[m,n]); optional GELU: C receives the
