@@ -445,13 +445,13 @@ __global__ __launch_bounds__(256) void xent_kernel(T* __restrict__ logits, int64
   }
 }
 
-// bf16 rows of up to 16 * THREADS 16-byte chunks: the row is read once, kept in registers as
+// bf16 rows of up to NCH * THREADS 16-byte chunks: the row is read once, kept in registers as
 // fp32, and written once.
-template <int THREADS>
+template <int THREADS, int NCH>
 __global__ __launch_bounds__(THREADS) void xent_bf16_kernel(bf16_t* __restrict__ logits, int64_t ldl,
                                                             const int32_t* __restrict__ labels,
                                                             float* __restrict__ row_loss, int V, float inv_n) {
-  constexpr int NCH = 16, NW = THREADS / 64;
+  constexpr int NW = THREADS / 64;
   __shared__ float sm[NW], ss[NW];
   const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   bf16_t* lr = logits + (int64_t)row * ldl;
@@ -481,11 +481,13 @@ __global__ __launch_bounds__(THREADS) void xent_bf16_kernel(bf16_t* __restrict__
   float bm = sm[0];
 #pragma unroll
   for (int w = 1; w < NW; ++w) bm = fmaxf(bm, sm[w]);
+  // the exponentials are kept (in place of the logits): the gradient is made from them, so each
+  // element costs one exponential, not two
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < NCH; ++i)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s += __expf(v[i][e] - bm);
+    for (int e = 0; e < 8; ++e) { v[i][e] = __expf(v[i][e] - bm); s += v[i][e]; }
   s = wave_sum(s);
   if (lane == 0) ss[wave] = s;
   __syncthreads();
@@ -494,10 +496,8 @@ __global__ __launch_bounds__(THREADS) void xent_bf16_kernel(bf16_t* __restrict__
   for (int w = 0; w < NW; ++w) bs += ss[w];
   const float lse = bm + __logf(bs);
   if (tid == 0) row_loss[row] = label >= 0 ? lse - picked : 0.f;
-  // (the exponential is taken twice per element rather than kept between the passes: the row then
-  // stays in registers as the bf16 pairs it was loaded as, 64 registers instead of 128, and the
-  // higher occupancy is worth more than the second exponential: measured, 220 against 232 us)
   const float scale = label >= 0 ? inv_n : 0.f;
+  const float pscale = scale / bs;                    // softmax = exp(v - max) / sum
 #pragma unroll
   for (int i = 0; i < NCH; ++i) {
     const int c = tid + THREADS * i;
@@ -506,7 +506,7 @@ __global__ __launch_bounds__(THREADS) void xent_bf16_kernel(bf16_t* __restrict__
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int col = c * 8 + e;
-        g[e] = col < V ? (__expf(v[i][e] - lse) - (col == label ? 1.f : 0.f)) * scale : 0.f;
+        g[e] = v[i][e] * pscale - (col == label ? scale : 0.f);   // columns >= V hold exp(-inf) = 0
       }
       Chunk<bf16_t>::store(lr + c * 8, g);
     }
@@ -806,9 +806,15 @@ void softmax_xent(int dtype, void* logits, int64_t ldl, const int32_t* labels, f
   const int64_t nch = ldl / 8;
   if (dtype == BF16 && ldl % 8 == 0 && ((((uintptr_t)logits) & 15) == 0) && nch <= 16 * 1024) {
     bf16_t* lg = (bf16_t*)logits;
-    if (nch <= 16 * 256) hipLaunchKernelGGL(xent_bf16_kernel<256>, dim3(T_), dim3(256), 0, st, lg, ldl, labels, row_loss, V, inv_n);
-    else if (nch <= 16 * 512) hipLaunchKernelGGL(xent_bf16_kernel<512>, dim3(T_), dim3(512), 0, st, lg, ldl, labels, row_loss, V, inv_n);
-    else hipLaunchKernelGGL(xent_bf16_kernel<1024>, dim3(T_), dim3(1024), 0, st, lg, ldl, labels, row_loss, V, inv_n);
+    // threads x chunks per thread: the fewest registers per thread that hold the row (more waves per SIMD)
+#define X_(TH, NC) hipLaunchKernelGGL((xent_bf16_kernel<TH, NC>), dim3(T_), dim3(TH), 0, st, lg, ldl, labels, row_loss, V, inv_n)
+    if (nch <= 4 * 256) X_(256, 4);
+    else if (nch <= 8 * 256) X_(256, 8);
+    else if (nch <= 4 * 1024) X_(1024, 4);
+    else if (nch <= 8 * 512) X_(512, 8);
+    else if (nch <= 8 * 1024) X_(1024, 8);
+    else X_(1024, 16);
+#undef X_
   } else if (dtype == BF16) hipLaunchKernelGGL(xent_kernel<bf16_t>, dim3(T_), dim3(256), 0, st, (bf16_t*)logits, ldl, labels, row_loss, V, inv_n);
   else hipLaunchKernelGGL(xent_kernel<float>, dim3(T_), dim3(256), 0, st, (float*)logits, ldl, labels, row_loss, V, inv_n);
   hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(256), 0, st, row_loss, T_, inv_n, loss);
