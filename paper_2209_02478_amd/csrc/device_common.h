@@ -96,6 +96,19 @@ __device__ __forceinline__ float gelu_erf_grad(float x) {
   float pdf = 0.39894228040143267794f * __expf(-0.5f * x * x);
   return cdf + x * pdf;
 }
+// the same with the rational erf above: its exponential, exp(-x^2 / 2), is also the density's, so
+// the derivative costs one exponential and one reciprocal (used where the result is rounded to bf16)
+__device__ __forceinline__ float gelu_erf_grad_bf16(float x) {
+  const float ax = fabsf(x) * 0.70710678118654752440f;
+  const float t = __frcp_rn(fmaf(0.3275911f, ax, 1.0f));
+  float p = fmaf(t, 1.061405429f, -1.453152027f);
+  p = fmaf(t, p, 1.421413741f);
+  p = fmaf(t, p, -0.284496736f);
+  p = fmaf(t, p, 0.254829592f);
+  const float e = __expf(-ax * ax);
+  const float erf_x = copysignf(1.0f - p * t * e, x);
+  return 0.5f * (1.0f + erf_x) + x * 0.39894228040143267794f * e;
+}
 __device__ __forceinline__ float gelu_tanh_grad(float x) {
   const float c = 0.79788456080286535588f;
   float t = tanhf(c * (x + 0.044715f * x * x * x));

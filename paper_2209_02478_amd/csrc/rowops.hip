@@ -396,14 +396,14 @@ __global__ __launch_bounds__(256) void gelu_bwd_bf16_kernel(bf16_t* __restrict__
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       float x = bf16_to_f32(pp[e]);
-      float gp = tanh_form ? gelu_tanh_grad(x) : gelu_erf_grad(x);
+      float gp = tanh_form ? gelu_tanh_grad(x) : gelu_erf_grad_bf16(x);
       dp[e] = f32_to_bf16(bf16_to_f32(dp[e]) * gp);
     }
     *(uint4*)(d + i) = dv;
   } else {
     for (int e = 0; i + e < n; ++e) {
       float x = bf16_to_f32(pre[i + e]);
-      float gp = tanh_form ? gelu_tanh_grad(x) : gelu_erf_grad(x);
+      float gp = tanh_form ? gelu_tanh_grad(x) : gelu_erf_grad_bf16(x);
       d[i + e] = f32_to_bf16(bf16_to_f32(d[i + e]) * gp);
     }
   }
