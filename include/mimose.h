@@ -306,6 +306,11 @@ int mimose_op_gemm(int32_t dtype, const void* A, int64_t lda, int32_t a_kmajor, 
  * into parts that are summed in a fixed order (a function of M and N only; 0 = never needed).
  * Passing NULL workspace to mimose_op_gemm is always allowed. */
 uint64_t mimose_op_gemm_workspace_bytes(int32_t M, int32_t N);
+/* Scratch for the products with a very long reduction (K >= 8192) behind a k-major A and an
+ * m-major B, no epilogue, few output tiles (the head's data gradient, reduced over the
+ * vocabulary): with it they cut their reduction in parts on the large tiles.  A function of N
+ * alone.  Passing less, or NULL, to mimose_op_gemm is always allowed. */
+uint64_t mimose_op_gemm_long_k_workspace_bytes(int32_t N);
 /* y = LayerNorm(x) * gamma + beta over rows of length H <= 1024.  x_f32: with dtype bf16 the
  * input rows are fp32 (an unrounded residual sum); ignored for dtype fp32. */
 int mimose_op_layernorm_fwd(int32_t dtype, const void* x, int32_t x_f32, const void* gamma,

@@ -91,6 +91,7 @@ SIGNATURES = {
     "mimose_op_gemm": (C.c_int, [_i32, _vp, _i64, _i32, _vp, _i64, _i32, _vp, _i64, _i32, _i32, _i32, _i32,
                                  _vp, _vp, _i64, _vp, _i32, _vp, _vp, _u64, _vp]),
     "mimose_op_gemm_workspace_bytes": (_u64, [_i32, _i32]),
+    "mimose_op_gemm_long_k_workspace_bytes": (_u64, [_i32]),
     "mimose_op_layernorm_fwd": (C.c_int, [_i32, _vp, _i32, _vp, _vp, _vp, _i32, _i32, _f32, _vp]),
     "mimose_op_layernorm_bwd": (C.c_int, [_i32, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _f32,
                                           _vp]),
@@ -329,6 +330,10 @@ def mimose_op_gemm(dtype, A, lda, a_kmajor, B, ldb, b_kmajor, Cm, ldc, c_f32, M,
 
 def mimose_op_gemm_workspace_bytes(M: int, N: int) -> int:
     return load_library().mimose_op_gemm_workspace_bytes(M, N)
+
+
+def mimose_op_gemm_long_k_workspace_bytes(N: int) -> int:
+    return load_library().mimose_op_gemm_long_k_workspace_bytes(N)
 
 
 def mimose_op_layernorm_fwd(dtype, x, x_f32, gamma, beta, y, T, H, eps, stream=None):

@@ -324,12 +324,17 @@ __global__ __launch_bounds__(256, 2) void bgemm_kernel(GemmDev p, int tiles_n, i
   store_tile<1>(q, acc, m0 + wm * 64, n0 + wn * 64, lane, (float*)smem_raw + wave * 4096);
 }
 
-// C[m][n] = sum over splits (in order) of partial tiles; row sums likewise.  fp32 output only.
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, float* __restrict__ C,
+// C[m][n] = sum over splits (in order) of partial tiles; row sums likewise.  C is fp32, or bf16
+// (the sum rounded once) when OUT_BF16.
+template <bool OUT_BF16>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, void* __restrict__ Cv,
                                                             int64_t ldc, float* __restrict__ rowsum, int M, int N,
                                                             int splits) {
   const int64_t MN = (int64_t)M * N;
   const int64_t idx = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  auto put = [&](int64_t o, float v) {
+    if (OUT_BF16) ((bf16_t*)Cv)[o] = f32_to_bf16(v); else ((float*)Cv)[o] = v;
+  };
   if (idx < MN) {
     const int m = (int)(idx / N), n = (int)(idx - (int64_t)m * N);
     if ((N & 3) == 0) {
@@ -338,15 +343,21 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
         const float4 v = *(const float4*)(partial + k * MN + idx);
         s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
       }
-      float* dst = C + (int64_t)m * ldc + n;
-      dst[0] = s.x; dst[1] = s.y; dst[2] = s.z; dst[3] = s.w;
+      const int64_t o = (int64_t)m * ldc + n;
+      if (OUT_BF16 && (ldc & 3) == 0) {
+        uint2 w;
+        w.x = pack_bf16x2(s.x, s.y); w.y = pack_bf16x2(s.z, s.w);
+        *(uint2*)((bf16_t*)Cv + o) = w;
+      } else {
+        put(o, s.x); put(o + 1, s.y); put(o + 2, s.z); put(o + 3, s.w);
+      }
     } else {
       for (int e = 0; e < 4 && idx + e < MN; ++e) {
         const int64_t q = idx + e;
         float s2 = partial[q];
         for (int k = 1; k < splits; ++k) s2 += partial[k * MN + q];
         const int mm = (int)(q / N), nn = (int)(q - (int64_t)mm * N);
-        C[(int64_t)mm * ldc + nn] = s2;
+        put((int64_t)mm * ldc + nn, s2);
       }
     }
   }
@@ -384,6 +395,23 @@ static bool use_pp(int M, int N, int K) {
   return fill >= 0.7;
 }
 
+// Data-gradient products with a very long reduction and few output tiles (the head's, whose
+// reduction runs over the vocabulary): on the large tiles, the reduction cut in parts so that
+// about 200 units exist; with K in the tens of thousands a tile's start and end vanish and the
+// parts are small against the operands (T = 6400, K = 30528: 330 us in three parts, 535 us on
+// 128 x 128 tiles; T = 2048: 117 against 341 us).  The parts' rows are capped so that the scratch
+// is a constant of the model, not a function of the batch.
+constexpr int kLongK = 8192;
+constexpr int64_t kLongKRows = 24576;            // parts x M at most
+size_t gemm_long_k_workspace_bytes(int N) { return (size_t)kLongKRows * N * 4; }
+static int long_k_splits(int M, int N) {
+  const int tiles = bgemm_pp_tiles(M, N);
+  int s = (205 + tiles - 1) / tiles;
+  const int cap = (int)(kLongKRows / M);
+  if (s > cap) s = cap;
+  return s < 1 ? 1 : (s > 8 ? 8 : s);
+}
+
 size_t gemm_workspace_bytes(int M, int N) {
   const int s = gemm_splits(M, N);
   return s > 1 ? ((size_t)s * M * N + (size_t)s * M) * 4 : 0;
@@ -392,8 +420,13 @@ size_t gemm_workspace_bytes(int M, int N) {
 // t1 (optional): event bound to the end of this kernel, which ends the product it belongs to
 static void launch_splitk_reduce(const GemmDev& p, hipStream_t st, hipEvent_t t1) {
   const int64_t MN = (int64_t)p.M * p.N;
-  hipExtLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((MN / 4 + 256) / 256)), dim3(256), 0, st, nullptr, t1, 0,
-                        p.partial, (float*)p.C, p.ldc, p.a_rowsum, p.M, p.N, p.splits);
+  const dim3 grid((unsigned)((MN / 4 + 256) / 256));
+  if (p.c_f32)
+    hipExtLaunchKernelGGL(splitk_reduce_kernel<false>, grid, dim3(256), 0, st, nullptr, t1, 0, p.partial, p.C, p.ldc,
+                          p.a_rowsum, p.M, p.N, p.splits);
+  else
+    hipExtLaunchKernelGGL(splitk_reduce_kernel<true>, grid, dim3(256), 0, st, nullptr, t1, 0, p.partial, p.C, p.ldc,
+                          p.a_rowsum, p.M, p.N, p.splits);
 }
 
 template <bool AK, bool BKM>
@@ -424,6 +457,7 @@ bool gemm(int dtype, const GemmArgs& g, hipStream_t st) {
   p.M = g.M; p.N = g.N; p.K = g.K;
   p.a_k = g.a_kmajor; p.b_k = g.b_kmajor; p.c_f32 = g.c_f32; p.gelu = g.gelu;
   p.splits = 1; p.partial = nullptr;
+  p.a_tail_zero = g.a_tail_zero ? 1 : 0;
   if (p.gelu && (p.c_f32 || !p.gelu_out)) return false;
   if (dtype == F32) {
     dim3 grid((g.N + 63) / 64, (g.M + 63) / 64);
@@ -442,6 +476,19 @@ bool gemm(int dtype, const GemmArgs& g, hipStream_t st) {
                    (!g.resid || ((g.ldr & 7) == 0 && aligned16(g.resid))) && (!g.bias || aligned16(g.bias)) &&
                    (!g.gelu_out || aligned16(g.gelu_out));
   p.vec = vec ? 1 : 0;
+  // a very long reduction behind a k-major A and an m-major B (the head's data gradient)
+  if (g.a_kmajor && !g.b_kmajor && g.K >= kLongK && g.M >= 256 && g.N >= 256 && !g.bias && !g.resid && !g.gelu &&
+      !g.a_rowsum && g.M <= kLongKRows) {
+    int sp = long_k_splits(g.M, g.N);
+    if (sp > 1 && !(g.workspace && aligned16(g.workspace) && g.workspace_bytes >= (size_t)sp * g.M * g.N * 4)) sp = 1;
+    p.splits = sp;
+    p.partial = sp > 1 ? (float*)g.workspace : nullptr;
+    if (launch_bgemm_pp(p, st, g.time_start, sp > 1 ? nullptr : g.time_stop)) {
+      if (sp > 1) launch_splitk_reduce(p, st, g.time_stop);
+      return true;
+    }
+    p.splits = 1; p.partial = nullptr;
+  }
   // few output tiles and a long reduction (weight gradients): cut k so the whole chip works
   {
     const int sp = splits_for(gemm_splits(g.M, g.N));

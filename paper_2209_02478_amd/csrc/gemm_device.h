@@ -18,6 +18,7 @@ struct GemmDev {
   int M, N, K;
   int a_k, b_k, c_f32, gelu;
   int vec;               // C, bias, residual and GELU output allow 16-byte accesses at columns n % 8 == 0
+  int a_tail_zero;       // A k-major, K % 8 != 0: the columns up to the next multiple of 8 exist and are zero
   int splits;            // > 1: k range cut in `splits` parts, raw fp32 tiles go to `partial`
   float* partial;        // [splits][M][N] followed by [splits][M] row sums
 };

@@ -402,12 +402,15 @@ static void launch_pp(const GemmDev& p, hipStream_t st, hipEvent_t t0, hipEvent_
 }
 
 // 256 x 256 block tiles, 2 x 4 waves of 128 x 64, rings of 3 A and 2 B tiles.
-// Requirements as for the other direct-load kernel: K % 8 == 0 when an operand is k-major, the
+// Requirements as for the other direct-load kernel: K % 8 == 0 when an operand is k-major (or
+// zeros vouched for behind a k-major A's last column, with B m-major), the
 // leading dimension of an m-major operand covers its row count rounded up to 8; row sums only
 // with an m-major A.
 bool launch_bgemm_pp(const GemmDev& p, hipStream_t st, hipEvent_t t0, hipEvent_t t1) {
   auto up8 = [](int64_t v) { return (v + 7) / 8 * 8; };
-  if ((p.a_k || p.b_k) && (p.K & 7)) return false;
+  // a chunk of a k-major operand that straddles K is moved whole: allowed only where the caller
+  // vouches for zeros behind A's last column while B (m-major) reads zeros from row K on
+  if ((p.a_k || p.b_k) && (p.K & 7) && !(p.a_tail_zero && p.a_k && !p.b_k && p.lda >= up8(p.K))) return false;
   if (!p.a_k && p.lda < up8(p.M)) return false;
   if (!p.b_k && p.ldb < up8(p.N)) return false;
   if (p.a_rowsum && p.a_k) return false;

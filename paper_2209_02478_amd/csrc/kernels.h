@@ -33,6 +33,9 @@ struct GemmArgs {
   void* gelu_out = nullptr;        // [M, ldc], storage dtype
   int gelu = GELU_NONE;
   float* a_rowsum = nullptr;       // [M] fp32: sum_k A(m,k) (bias gradient of a weight-gradient product)
+  // A k-major with K not a multiple of 8: its columns [K, K rounded up to 8) exist (lda covers
+  // them) and hold zeros, so a kernel that moves whole 16-byte chunks may read them
+  bool a_tail_zero = false;
   void* workspace = nullptr;       // optional scratch of gemm_workspace_bytes(M, N) for split reductions
   size_t workspace_bytes = 0;
   // optional, both or neither: recorded by the product kernel's own start and end (not by markers
@@ -43,6 +46,10 @@ struct GemmArgs {
 // scratch that lets a bf16 product with fp32 output cut its reduction in parts (0: never splits);
 // a function of the output shape alone
 size_t gemm_workspace_bytes(int M, int N);
+// scratch that lets a data-gradient product with a very long reduction and few output tiles (the
+// vocabulary-long one of the head: A k-major, B m-major, no epilogue) cut its reduction in parts:
+// a function of the column count alone, so that it is a constant of the model
+size_t gemm_long_k_workspace_bytes(int N);
 
 // returns false when the arguments violate the kernel's alignment assumptions
 bool gemm(int dtype, const GemmArgs& g, hipStream_t st);

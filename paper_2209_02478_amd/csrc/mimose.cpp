@@ -715,16 +715,26 @@ void Step::head(float* loss_dev) {
     with_workspace(a);
   }
   void* dhs = f_.pre_ln ? talloc(TH) : gA_;            // post-LN: straight into the (possibly fp32) carrier
+  // scratch of the vocabulary-long data gradient (its own: the decoder's weight gradient uses the
+  // other one at the same time on the second stream); a constant of the model
+  const size_t long_ws_bytes = dt_ == mk::BF16 && V >= 8192 ? mk::gemm_long_k_workspace_bytes(H) : 0;
+  void* long_ws = long_ws_bytes ? c_->arena.alloc(long_ws_bytes) : nullptr;
+  // the loss kernel left zeros in the padding columns [V, ldv) of the logits' gradient
+  auto vocab_dgrad = [&](void* out, bool out_f32) {
+    mk::GemmArgs a{logits, ldv, true, w(c_->i_tok), H, false, out, H, out_f32, T_, H, V};
+    a.a_tail_zero = true;
+    a.workspace = long_ws; a.workspace_bytes = long_ws_bytes;
+    gemm(a);
+  };
   if (f_.head) {
     void* dt = talloc(TH);
-    { mk::GemmArgs a{logits, ldv, true, w(c_->i_tok), H, false, dt, H, false, T_, H, V}; gemm(a); }
+    vocab_dgrad(dt, false);
     ln_bwd(dt, gz, c_->i_hg, c_->i_hb, dt, nullptr);                          // dt = d gz
     if (!dry_) mk::gelu_bwd(dt_, dt, z, TH, f_.gelu_tanh, st_);               // dt = d z
     wgrad(dt, H, H, hs, H, c_->i_wt, c_->i_bt);
     dgrad(dt, H, H, c_->i_wt, dhs, H, nullptr, wide_);
   } else {
-    mk::GemmArgs a{logits, ldv, true, w(c_->i_tok), H, false, dhs, H, wide_, T_, H, V};
-    gemm(a);
+    vocab_dgrad(dhs, wide_);
   }
   if (f_.pre_ln) ln_bwd(dhs, hlast, c_->i_fg, c_->i_fb, gA_, nullptr);
   join();

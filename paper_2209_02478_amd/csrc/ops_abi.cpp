@@ -34,6 +34,8 @@ uint64_t mimose_op_gemm_workspace_bytes(int32_t M, int32_t N) {
   return M > 0 && N > 0 ? mk::gemm_workspace_bytes(M, N) : 0;
 }
 
+uint64_t mimose_op_gemm_long_k_workspace_bytes(int32_t N) { return N > 0 ? mk::gemm_long_k_workspace_bytes(N) : 0; }
+
 int mimose_op_layernorm_fwd(int32_t dtype, const void* x, int32_t x_f32, const void* gamma, const void* beta, void* y,
                             int32_t T, int32_t H, float eps, void* stream) {
   if (bad_dtype(dtype) || !x || !gamma || !beta || !y || T < 0 || H < 1 || H > mk::kMaxRowWidth) return MIMOSE_ERR_INVALID_ARG;

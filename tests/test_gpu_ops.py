@@ -217,6 +217,37 @@ def test_gemm_large_tiles_split_reduction():
     assert np.array_equal(host(W), first)
 
 
+@pytest.mark.parametrize("c_f32", [0, 1])
+def test_gemm_long_reduction_in_parts(c_f32):
+    """Data-gradient layout with a very long reduction and few output tiles (the shape class of the
+    head's data gradient): with the scratch it runs on the large tiles in parts; bf16 and fp32
+    output, ragged rows, the same bits twice, and the same values as without the scratch."""
+    dtype, M, N, K = 1, 600, 768, 8320
+    rng = np.random.default_rng(181 + c_f32)
+    A = (rng.standard_normal((M, K)) * 0.1).astype(np.float32)
+    B = rng.standard_normal((N, K)).astype(np.float32)
+    dA = dev(A, dtype)
+    dB = dev(np.ascontiguousarray(B.T), dtype)                      # m-major: [K][N]
+    ref = quant(A, dtype) @ quant(B, dtype).T
+    nws = mi.mimose_op_gemm_long_k_workspace_bytes(N)
+    assert nws >= 8 * M * N * 4
+    ws = torch.zeros(nws, dtype=torch.uint8, device=DEV)
+    odt = torch.float32 if c_f32 else dA.dtype
+    C = torch.full((M, N), 7.0, dtype=odt, device=DEV)
+    mi.mimose_op_gemm(dtype, dA, K, 1, dB, N, 0, C, N, c_f32, M, N, K, workspace=ws, workspace_bytes=nws)
+    sync()
+    first = host(C)
+    close(first, ref, 0 if c_f32 else dtype, k=40.0 if c_f32 else 2.0)
+    C.fill_(3.0)
+    mi.mimose_op_gemm(dtype, dA, K, 1, dB, N, 0, C, N, c_f32, M, N, K, workspace=ws, workspace_bytes=nws)
+    sync()
+    assert np.array_equal(host(C), first)
+    C.fill_(3.0)
+    mi.mimose_op_gemm(dtype, dA, K, 1, dB, N, 0, C, N, c_f32, M, N, K)      # no scratch: one part
+    sync()
+    close(host(C), ref, 0 if c_f32 else dtype, k=40.0 if c_f32 else 2.0)
+
+
 def test_gemm_rejects_misaligned_bf16():
     a = torch.zeros(64 * 20, dtype=torch.bfloat16, device=DEV)
     with pytest.raises(mi.MimoseError):
