@@ -381,18 +381,17 @@ int gemm_splits(int M, int N) {
 bool launch_bgemm_pp(const GemmDev& p, hipStream_t st, hipEvent_t t0, hipEvent_t t1);
 int bgemm_pp_tiles(int M, int N);
 // Which products go to the large-tile kernel: it runs one block per compute unit, so its time is
-// a whole number of rounds of 256 tiles, and it pays where those rounds are well filled; measured
-// against the 128 x 128 kernels on the shapes of the step (same box, same run): ahead by 10-35 %
-// from 0.7 of a full last round on (e.g. T = 6400 by 2304: 225 tiles, 30 against 39 us; the
-// vocabulary products; every product at T = 16384), 5-7 % behind at 0.59 (300 tiles), 20 % behind
-// at 0.29 (75 tiles).  Products that cut their reduction in parts stay with the small tiles: with
-// few large output tiles they need more parts, and the fp32 parts written and read again cost
-// more than the large tile saves.
+// a whole number of rounds of 256 tiles, and it pays where those rounds are well filled.  Measured
+// against the 128 x 128 kernels with K = 768 and 2304 or 3072 columns over row counts from 4608
+// to 9984 (same box, same run): ahead by 25-34 % when the last round is filled to 0.77 or more,
+// by 2-9 % between 0.63 and 0.70, behind by 2-15 % from 0.61 down.  Products that cut their
+// reduction in parts stay with the small tiles: with few large output tiles they need more
+// parts, and the fp32 parts written and read again cost more than the large tile saves.
 static bool use_pp(int M, int N, int K) {
   if (M < 256 || N < 256 || K < 512) return false;
   const int units = bgemm_pp_tiles(M, N), rounds = (units + 255) / 256;
   const double fill = (double)units / (256.0 * rounds);
-  return fill >= 0.7;
+  return fill >= 0.62;
 }
 
 // Data-gradient products with a very long reduction and few output tiles (the head's, whose
