@@ -125,7 +125,18 @@ def main():
     sheltered = 10
     total = sheltered + args.warmup + args.steps
     lens = synthdata.seq_lengths(wl.length_recipe, total, wl.seed)
-    batches = [synthdata.make_batch(shape, B, L, synthdata.step_seed(wl.seed, i)) for i, L in enumerate(lens)]
+    last_note = [time.perf_counter()]
+
+    def note(what):                           # a line on stderr every half minute of a long run
+        if time.perf_counter() - last_note[0] > 30:
+            sys.stderr.write(f"bench.py: {what}\n")
+            sys.stderr.flush()
+            last_note[0] = time.perf_counter()
+
+    batches = []
+    for i, L in enumerate(lens):
+        batches.append(synthdata.make_batch(shape, B, L, synthdata.step_seed(wl.seed, i)))
+        note(f"made batch {i + 1} of {total}")
 
     if args.pmc_calibration:
         src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda:0")
@@ -147,9 +158,10 @@ def main():
     max_peak = 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for t, l in timed:                        # queued one after the other; the loss is read once, at the end
+    for i, (t, l) in enumerate(timed):        # queued one after the other; the loss is read once, at the end
         _, pk, _ = iteration(t, l, wait=args.wait_every_step)
         max_peak = max(max_peak, pk)
+        note(f"timed iteration {i + 1} of {len(timed)} issued")
     last_loss = m.sync_loss()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -170,8 +182,9 @@ def main():
 
     # same steps again with per-kernel events on the work stream
     mi.mimose_profile_enable(m.ctx, 1)
-    for t, l in timed:
+    for i, (t, l) in enumerate(timed):
         iteration(t, l)
+        note(f"per-kernel timing pass, iteration {i + 1} of {len(timed)}")
     torch.cuda.synchronize()
     upd = None
     if update:                                # the update alone, back to back, on the context's stream
