@@ -271,7 +271,10 @@ __global__ __launch_bounds__(256, 2) void bgemm_kernel(GemmDev p, int tiles_n, i
   bf16_t* Bs = As + 2 * TA::ELEMS;                   // two buffers of TB::ELEMS
   const int unit = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (unit >= total) return;
-  const int t = unit / p.splits, split = unit - t * p.splits;
+  // units run part by part (all tiles of the first k range, then of the second, ...): an XCD's
+  // contiguous run of units then shares one k range of both operands in its L2
+  const int n_tiles = total / p.splits;
+  const int split = unit / n_tiles, t = unit - split * n_tiles;
   // tiles run down groups of GROUP_M row panels, so the tiles in flight on one XCD cover a
   // squarish patch of C and share both A and B panels in its L2
   const int tiles_m = (p.M + BM - 1) / BM;

@@ -140,7 +140,10 @@ __global__ __launch_bounds__(256, 3) void bgemm_dma_kernel(GemmDev p, int tiles_
   __shared__ __attribute__((aligned(1024))) bf16_t ring[STAGES * STAGE_ELEMS];
   const int unit = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (unit >= total) return;
-  const int t = unit / p.splits, split = unit - t * p.splits;
+  // units run part by part (all tiles of the first k range, then of the second, ...): an XCD's
+  // contiguous run of units then shares one k range of both operands in its L2
+  const int n_tiles = total / p.splits;
+  const int split = unit / n_tiles, t = unit - split * n_tiles;
   const int tiles_m = (p.M + BM - 1) / BM;
   const int group = t / (GROUP_M * tiles_n), first_m = group * GROUP_M;
   const int gsize = min(tiles_m - first_m, GROUP_M);
