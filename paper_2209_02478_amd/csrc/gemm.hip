@@ -78,7 +78,7 @@ __global__ __launch_bounds__(256) void sgemm_kernel(GemmDev p) {
 
 // ------------------------------------------------------------------ bf16 MFMA
 constexpr int BM = 128, BN = 128, BK = 64;
-constexpr int GROUP_M = 8;                      // row panels per tile group
+constexpr int GROUP_M = 4;                      // row panels per tile group (4-6 measured best in the step, 8 and 1 about 0.5 % behind, 64 3 % behind)
 constexpr int NCH = BK / 16;                    // 16-byte chunks per thread and operand tile
 constexpr int KCH = BK / 8;                     // chunks along k of a k-major row
 constexpr int LDK = BK + 8;        // row stride of a k-major tile [128 rows][64 k] (144 B: conflict-free 16 B reads)

@@ -30,7 +30,7 @@ namespace {
 constexpr int BM = 128, BN = 128, BK = 32;
 constexpr int STAGES = 3;
 constexpr int TILE_ELEMS = 128 * BK;             // either layout: 8 KB
-constexpr int GROUP_M = 8;
+constexpr int GROUP_M = 4;
 constexpr int DMA_PER_WAVE = TILE_ELEMS * 2 / 1024 / 4;   // 1 KB direct loads per wave and operand tile: 2
 
 __device__ __attribute__((aligned(16))) uint32_t g_zero_chunk[4] = {0u, 0u, 0u, 0u};

@@ -40,7 +40,7 @@ namespace mk {
 namespace {
 
 constexpr int PBK = 64;                          // reduction indices per stage
-constexpr int PGROUP_M = 8;                      // row panels per tile group (L2 reuse)
+constexpr int PGROUP_M = 4;                      // row panels per tile group (L2 reuse)
 
 __device__ __attribute__((aligned(16))) uint32_t g_zero16[4] = {0u, 0u, 0u, 0u};
 
