@@ -493,3 +493,15 @@ def test_underpredicted_plan_is_dropped_and_replanned():
     peak2, plan2 = m.dry_step(B, 64)               # the repaired plan is the cached one now
     assert (peak2, plan2) == (peak, plan) and m.stats()["replans"] == st["replans"]
     m.close()
+
+
+def test_sync_loss_and_collector_refuse_without_device_or_steps():
+    """mimose_sync_loss: NOT_READY on a host-only context (nothing can be queued there)."""
+    wl, m = host_ctx("tiny")
+    with pytest.raises(mi.MimoseError) as e:
+        m.sync_loss()
+    assert "host-only" in str(e.value)
+    m.dry_step(wl.batch, 16)
+    with pytest.raises(mi.MimoseError):
+        m.sync_loss()
+    m.close()
